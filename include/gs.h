@@ -1,0 +1,198 @@
+/*
+ * gs.h -- C boundary of the random-walk + skip-gram (SGNS) node-embedding path
+ * for AMD gfx950.
+ *
+ * The calls follow the statement of the problem in GraphScale (arXiv
+ * 2407.15452): a trainer that holds the whole graph topology (Sec. 3.1),
+ * samples random walks from its source nodes and turns them into positive and
+ * negative samples (Sec. 2.2, Sec. 3.2), and then reads, and writes back, only
+ * the rows of the N x d embedding matrices that the batch names (Sec. 3.2),
+ * with a barrier after the write (Sec. 3.2, "Synchronization").
+ *
+ * Conventions shared by every call
+ *  - Every pointer is a DEVICE pointer unless its comment says "host".  The
+ *    gs_csr / gs_alias descriptors themselves are small host structs that hold
+ *    device pointers.  The caller owns all memory; the library allocates
+ *    nothing that outlives a call and frees nothing.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue work; outputs, including the scalar outputs written
+ *    through device pointers, are valid once the stream has been synchronised.
+ *  - Calls that need scratch memory take (ws, ws_bytes); the matching
+ *    *_workspace_bytes() function (host, O(1)) returns the size to provide.
+ *    ws must be 256-byte aligned.  Its contents are undefined afterwards.
+ *  - Return value: GS_OK or a negative gs_status.  Arguments are validated on
+ *    the host only; nothing is enqueued when a call fails validation.  The
+ *    contents of index arrays are not validated: node ids outside
+ *    [0, num_nodes) in CSR rows, centers, contexts or negatives are undefined
+ *    behaviour (ids in edge lists and in `starts` are checked by the kernels).
+ *  - Node ids are int32.  CSR offsets are int32 or int64 (`offset_bits`).
+ *  - Random numbers are Philox4x32-10 blocks keyed by the caller's 64-bit
+ *    seed; the counter is (index low, index high, c2, c3) as stated per call,
+ *    so any sub-range of walks or pairs can be produced on its own and is
+ *    identical to the same range of one big call.
+ *  - slot(r, n) = high 64 bits of the 128-bit product r * n, r = (word0 << 32)
+ *    | word1;  unit(x) = (float)(x >> 8) * 2^-24.
+ */
+#ifndef GS_H_
+#define GS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GS_OK = 0,
+  GS_EINVAL = -1,     /* null / negative / misaligned / unsupported argument      */
+  GS_EWORKSPACE = -2, /* ws_bytes smaller than *_workspace_bytes() reports        */
+  GS_EOVERFLOW = -3,  /* a count does not fit the chosen index type               */
+  GS_EHIP = -4        /* a HIP runtime call failed; see gs_last_hip_error()       */
+} gs_status;
+
+enum { GS_SYMMETRIZE = 1, GS_DROP_SELF_LOOPS = 2, GS_DEDUPE = 4 };
+enum { GS_F32 = 0, GS_BF16 = 1 };
+
+/* Graph topology in CSR form; every row sorted ascending by neighbour id. */
+typedef struct {
+  int64_t num_nodes;
+  int64_t num_entries;   /* directed entries; an undirected edge is two        */
+  const void* offsets;   /* int32[num_nodes+1] or int64[num_nodes+1]           */
+  int32_t offset_bits;   /* 32 or 64                                            */
+  const int32_t* nbrs;   /* int32[num_entries]                                  */
+  const float* weights;  /* float[num_entries] or NULL (unused by the walkers) */
+} gs_csr;
+
+/* Alias table(s).  For walks: one table per CSR row, stored at the row's
+ * offsets, alias[] = position inside the row.  For negatives: one table of
+ * num_nodes entries.  prob == NULL means "uniform". */
+typedef struct {
+  const float* prob;
+  const int32_t* alias;
+} gs_alias;
+
+/* HIP error code of the last GS_EHIP on this thread (0 if none). */
+int32_t gs_last_hip_error(void);
+
+/* --------------------------------------------------------------------------
+ * gs_csr_build -- edge list to CSR (Sec. 3.1: the topology a trainer keeps).
+ *   src, dst  int32[m]; w float[m] or NULL.
+ *   Edges with an endpoint outside [0, num_nodes) are dropped.  flags:
+ *   GS_DROP_SELF_LOOPS drops src == dst; GS_SYMMETRIZE also inserts the
+ *   reverse of every edge; GS_DEDUPE keeps one entry per (src, dst), the one
+ *   from the lowest input index (its weight is kept).  Rows come out sorted by
+ *   neighbour id, equal neighbours in input order.
+ *   offsets_out  int32|int64 [num_nodes+1];  nbrs_out int32[cap], w_out
+ *   float[cap] (required iff w != NULL), cap = m, or 2m with GS_SYMMETRIZE;
+ *   num_entries_out  int64[1] on the device.
+ *   Errors: GS_EOVERFLOW if offset_bits == 32 and cap > INT32_MAX, or
+ *   m >= 2^31.
+ * ------------------------------------------------------------------------ */
+size_t gs_csr_build_workspace_bytes(int64_t m, int64_t num_nodes, uint32_t flags);
+int32_t gs_csr_build(const int32_t* src, const int32_t* dst, const float* w, int64_t m,
+                     int64_t num_nodes, uint32_t flags, int32_t offset_bits,
+                     void* offsets_out, int32_t* nbrs_out, float* w_out,
+                     int64_t* num_entries_out, void* ws, size_t ws_bytes, void* stream);
+
+/* --------------------------------------------------------------------------
+ * gs_alias_build -- alias tables for weighted draws: per-row tables for
+ * weighted walks, or one table over degree^0.75 for the negatives of Sec. 2.2
+ * (the weights are an input; the library does not compute powers).
+ *   seg_offsets int32|int64 [num_segments+1]; segment s covers
+ *   weights[seg_offsets[s] .. seg_offsets[s+1]);  total_entries =
+ *   seg_offsets[num_segments] (host value, used for sizing only).
+ *   Construction (per segment, n entries, fp64 inside): S = sum of weights in
+ *   index order; mass_i = w_i * n; entries with mass < S are "small", others
+ *   "large", both first-in first-out in index order; repeatedly the oldest
+ *   small a and oldest large b give prob[a] = (float)(mass_a / S), alias[a] =
+ *   b, mass_b = (mass_b + mass_a) - S, and b is appended to the list its new
+ *   mass selects; leftovers get prob = 1, alias = self.  alias[] is a position
+ *   inside the segment.  Segments longer than INT32_MAX are unsupported.
+ * ------------------------------------------------------------------------ */
+size_t gs_alias_build_workspace_bytes(int64_t num_segments, int64_t total_entries);
+int32_t gs_alias_build(const void* seg_offsets, int32_t offset_bits, int64_t num_segments,
+                       int64_t total_entries, const float* weights, float* prob_out,
+                       int32_t* alias_out, void* ws, size_t ws_bytes, void* stream);
+
+/* --------------------------------------------------------------------------
+ * gs_random_walk -- first-order walks (Sec. 2.2, DeepWalk; Sec. 3.2 counts
+ * walk_len sampled NODES per source, so a walk makes walk_len - 1 steps).
+ *   g, a: host structs (a == NULL or a->prob == NULL: uniform neighbour).
+ *   starts int32[num_walks]; walks_out int32[num_walks][walk_len], row-major.
+ *   Step t of walk id = walk_id_base + i uses the Philox block with counter
+ *   (id low, id high, t, 0): neighbour slot(r, deg); if weighted and not
+ *   unit(word2) < prob[slot], alias[slot] instead.  A node without out-edges
+ *   (or a start outside [0, num_nodes)) ends the walk: the rest of the row is -1.
+ * ------------------------------------------------------------------------ */
+int32_t gs_random_walk(const gs_csr* g, const gs_alias* a, const int32_t* starts,
+                       int64_t num_walks, uint64_t walk_id_base, int32_t walk_len,
+                       uint64_t seed, int32_t* walks_out, void* stream);
+
+/* --------------------------------------------------------------------------
+ * gs_node2vec_walk -- second-order biased walks (Sec. 2.2, node2vec).
+ *   As gs_random_walk, but from the second step on a candidate x drawn from
+ *   the row of the current node is accepted with probability bias / max_bias:
+ *   bias = 1/p if x is the previous node, 1 if the previous node has an edge
+ *   to x, 1/q otherwise; max_bias = max(1/p, 1, 1/q) (all fp32, computed on
+ *   the host).  Attempt `att` of step t uses counter (id low, id high, t,
+ *   att); accept iff unit(word3) * max_bias < bias.  att runs 0..1023 and the
+ *   candidate of attempt 1023 is taken unconditionally.
+ *   Errors: GS_EINVAL unless p > 0 and q > 0.
+ * ------------------------------------------------------------------------ */
+int32_t gs_node2vec_walk(const gs_csr* g, const gs_alias* a, const int32_t* starts,
+                         int64_t num_walks, uint64_t walk_id_base, int32_t walk_len,
+                         float p, float q, uint64_t seed, int32_t* walks_out, void* stream);
+
+/* --------------------------------------------------------------------------
+ * gs_make_pairs -- skip-gram (centre, context) pairs of Sec. 2.2 with the
+ * paper's "window-size".
+ *   walks int32[num_walks][walk_len] (-1 only as a suffix).  For walk i, then
+ *   position a of its valid prefix, then offset b = -window..window, b != 0,
+ *   with a + b inside the prefix: (walks[i][a], walks[i][a+b]).  Dense output
+ *   in that order; capacity of centers_out / contexts_out:
+ *   num_walks * (2*window*walk_len - window*(window+1)) entries when walk_len
+ *   > window, num_walks * walk_len * (walk_len - 1) otherwise.
+ *   num_pairs_out int64[1] on the device.  walk_len <= 4096.
+ * ------------------------------------------------------------------------ */
+size_t gs_make_pairs_workspace_bytes(int64_t num_walks);
+int32_t gs_make_pairs(const int32_t* walks, int64_t num_walks, int32_t walk_len, int32_t window,
+                      int32_t* centers_out, int32_t* contexts_out, int64_t* num_pairs_out,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* --------------------------------------------------------------------------
+ * gs_sample_negatives -- the "negatively sampled nodes" of Sec. 3.2.
+ *   negs_out int32[num_pairs][k].  Entry (i, j) is an alias draw from the
+ *   single table `noise` of num_nodes entries with counter (idx low, idx
+ *   high, j, 0x80000000), idx = pair_index_base + i.  Draws are independent;
+ *   a negative equal to the centre or context is kept.
+ * ------------------------------------------------------------------------ */
+int32_t gs_sample_negatives(const gs_alias* noise, int64_t num_nodes, int64_t num_pairs,
+                            uint64_t pair_index_base, int32_t k, uint64_t seed,
+                            int32_t* negs_out, void* stream);
+
+/* --------------------------------------------------------------------------
+ * gs_sgns_step -- one training iteration of Sec. 3.2: fetch the batch's rows,
+ * loss and sparse gradient on them, write those rows back; reads see the
+ * tables as they were before the call (the barrier of "Synchronization").
+ *   w_in, w_out  [num_nodes][dim] row-major, float (GS_F32) or bfloat16
+ *   (GS_BF16, fp32 arithmetic), updated in place.
+ *   For pair i: u = w_in[centers[i]], v_0 = w_out[contexts[i]], v_j =
+ *   w_out[negs[i][j-1]], x_j = <u, v_j>; loss_i = softplus(-x_0) + sum_j
+ *   softplus(x_j); g_0 = sigmoid(x_0) - 1, g_j = sigmoid(x_j);
+ *   w_in[c] -= lr * sum g_j v_j;  w_out[row_j] -= lr * g_j u, summed over all
+ *   occurrences in the batch.  loss_sum_out double[1] on the device receives
+ *   the sum of loss_i (overwritten).
+ *   dim must be a multiple of 4 and at most 1024.  Rows that the batch does
+ *   not name are not touched.
+ * ------------------------------------------------------------------------ */
+size_t gs_sgns_step_workspace_bytes(int64_t num_pairs, int32_t k, int32_t dim, int32_t dtype);
+int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int32_t dim, int32_t dtype,
+                     const int32_t* centers, const int32_t* contexts, const int32_t* negs,
+                     int64_t num_pairs, int32_t k, float lr, double* loss_sum_out,
+                     void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GS_H_ */

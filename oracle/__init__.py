@@ -1,0 +1,11 @@
+"""CPU oracle for the walk + SGNS path.  TEST INFRASTRUCTURE ONLY.
+
+Only the tests, the smoke check and the CPU-baseline leg of the benchmark may
+import this package; the product package never does, and this package never
+imports the product package.  See ``gs_oracle.cpp`` for what is computed.
+"""
+from .binding import (  # noqa: F401
+    F32, BF16, SYMMETRIZE, DROP_SELF_LOOPS, DEDUPE,
+    build, philox4x32_10, csr_build, alias_build, random_walk, node2vec_walk,
+    make_pairs, sample_negatives, sgns_step,
+)

@@ -1,0 +1,202 @@
+"""ctypes/numpy wrapper around ``liboracle.so`` (built from ``gs_oracle.cpp``).
+
+TEST INFRASTRUCTURE: marshals numpy arrays into the oracle's C entry points and
+nothing else.  All arithmetic of the method lives in the C++ file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "gs_oracle.cpp")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+F32, BF16 = 0, 1
+SYMMETRIZE, DROP_SELF_LOOPS, DEDUPE = 1, 2, 4
+
+
+class _Csr(C.Structure):
+    _fields_ = [("num_nodes", C.c_int64), ("num_entries", C.c_int64),
+                ("offsets", C.c_void_p), ("offset_bits", C.c_int32),
+                ("nbrs", C.c_void_p), ("weights", C.c_void_p)]
+
+
+class _Alias(C.Structure):
+    _fields_ = [("prob", C.c_void_p), ("alias", C.c_void_p)]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (no fused multiply-add contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["g++", "-std=c++17", "-O2", "-ffp-contract=off", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        for name in ("oracle_csr_build", "oracle_alias_build", "oracle_random_walk",
+                     "oracle_node2vec_walk", "oracle_make_pairs", "oracle_sample_negatives",
+                     "oracle_sgns_step"):
+            getattr(_lib, name).restype = C.c_int32
+        _lib.oracle_philox4x32_10.restype = None
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else C.c_void_p(a.ctypes.data)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError(f"{what} failed with status {rc}")
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def philox4x32_10(ctr, key):
+    ctr = np.ascontiguousarray(ctr, dtype=np.uint32)
+    key = np.ascontiguousarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    _load().oracle_philox4x32_10(_ptr(ctr), _ptr(key), _ptr(out))
+    return out
+
+
+def csr_build(src, dst, w, num_nodes, flags, offset_bits=32):
+    """Returns (offsets, nbrs, weights-or-None)."""
+    src, dst = _i32(src), _i32(dst)
+    m = int(src.shape[0])
+    if w is not None:
+        w = np.ascontiguousarray(w, dtype=np.float32)
+    cap = max(1, m * (2 if flags & SYMMETRIZE else 1))
+    offsets = np.zeros(num_nodes + 1, dtype=np.int64 if offset_bits == 64 else np.int32)
+    nbrs = np.zeros(cap, dtype=np.int32)
+    w_out = np.zeros(cap, dtype=np.float32) if w is not None else None
+    ne = C.c_int64(0)
+    rc = _load().oracle_csr_build(_ptr(src), _ptr(dst), _ptr(w), C.c_int64(m),
+                                  C.c_int64(num_nodes), C.c_uint32(flags), C.c_int32(offset_bits),
+                                  _ptr(offsets), _ptr(nbrs), _ptr(w_out), C.byref(ne))
+    _check(rc, "oracle_csr_build")
+    n = ne.value
+    return offsets, nbrs[:n].copy(), (None if w_out is None else w_out[:n].copy())
+
+
+def alias_build(seg_offsets, weights):
+    """Returns (prob, alias) for the segments delimited by seg_offsets."""
+    seg_offsets = np.ascontiguousarray(seg_offsets)
+    assert seg_offsets.dtype in (np.int32, np.int64)
+    bits = 64 if seg_offsets.dtype == np.int64 else 32
+    weights = np.ascontiguousarray(weights, dtype=np.float32)
+    prob = np.zeros(max(1, weights.shape[0]), dtype=np.float32)
+    alias = np.zeros(max(1, weights.shape[0]), dtype=np.int32)
+    rc = _load().oracle_alias_build(_ptr(seg_offsets), C.c_int32(bits),
+                                    C.c_int64(seg_offsets.shape[0] - 1), _ptr(weights),
+                                    _ptr(prob), _ptr(alias))
+    _check(rc, "oracle_alias_build")
+    return prob[:weights.shape[0]], alias[:weights.shape[0]]
+
+
+def _csr_struct(offsets, nbrs, weights=None):
+    offsets = np.ascontiguousarray(offsets)
+    assert offsets.dtype in (np.int32, np.int64)
+    nbrs = _i32(nbrs)
+    keep = [offsets, nbrs, weights]
+    s = _Csr(offsets.shape[0] - 1, nbrs.shape[0], offsets.ctypes.data,
+             64 if offsets.dtype == np.int64 else 32, nbrs.ctypes.data,
+             None if weights is None else weights.ctypes.data)
+    return s, keep
+
+
+def _alias_struct(alias):
+    if alias is None:
+        return None, []
+    prob, al = alias
+    prob = np.ascontiguousarray(prob, dtype=np.float32)
+    al = _i32(al)
+    return _Alias(prob.ctypes.data, al.ctypes.data), [prob, al]
+
+
+def random_walk(offsets, nbrs, starts, walk_len, seed, alias=None, walk_id_base=0):
+    g, keep = _csr_struct(offsets, nbrs)
+    a, keep2 = _alias_struct(alias)
+    starts = _i32(starts)
+    nw = int(starts.shape[0])
+    out = np.zeros((nw, walk_len), dtype=np.int32)
+    rc = _load().oracle_random_walk(C.byref(g), None if a is None else C.byref(a), _ptr(starts),
+                                    C.c_int64(nw), C.c_uint64(walk_id_base), C.c_int32(walk_len),
+                                    C.c_uint64(seed), _ptr(out))
+    _check(rc, "oracle_random_walk")
+    del keep, keep2
+    return out
+
+
+def node2vec_walk(offsets, nbrs, starts, walk_len, p, q, seed, alias=None, walk_id_base=0):
+    g, keep = _csr_struct(offsets, nbrs)
+    a, keep2 = _alias_struct(alias)
+    starts = _i32(starts)
+    nw = int(starts.shape[0])
+    out = np.zeros((nw, walk_len), dtype=np.int32)
+    rc = _load().oracle_node2vec_walk(C.byref(g), None if a is None else C.byref(a), _ptr(starts),
+                                      C.c_int64(nw), C.c_uint64(walk_id_base),
+                                      C.c_int32(walk_len), C.c_float(p), C.c_float(q),
+                                      C.c_uint64(seed), _ptr(out))
+    _check(rc, "oracle_node2vec_walk")
+    del keep, keep2
+    return out
+
+
+def make_pairs(walks, window):
+    walks = _i32(walks)
+    nw, walk_len = walks.shape
+    cap = max(1, nw * walk_len * 2 * window)
+    centers = np.zeros(cap, dtype=np.int32)
+    contexts = np.zeros(cap, dtype=np.int32)
+    n = C.c_int64(0)
+    rc = _load().oracle_make_pairs(_ptr(walks), C.c_int64(nw), C.c_int32(walk_len),
+                                   C.c_int32(window), _ptr(centers), _ptr(contexts), C.byref(n))
+    _check(rc, "oracle_make_pairs")
+    return centers[:n.value].copy(), contexts[:n.value].copy()
+
+
+def sample_negatives(noise_alias, num_nodes, num_pairs, k, seed, pair_index_base=0):
+    a, keep = _alias_struct(noise_alias)
+    out = np.zeros((num_pairs, k), dtype=np.int32)
+    rc = _load().oracle_sample_negatives(None if a is None else C.byref(a), C.c_int64(num_nodes),
+                                         C.c_int64(num_pairs), C.c_uint64(pair_index_base),
+                                         C.c_int32(k), C.c_uint64(seed), _ptr(out))
+    _check(rc, "oracle_sample_negatives")
+    del keep
+    return out
+
+
+def sgns_step(w_in, w_out, centers, contexts, negs, lr, dtype=F32):
+    """Updates w_in / w_out (numpy, C-contiguous, float32 or uint16 bf16 bits) in place.
+
+    Returns the summed loss of the batch.
+    """
+    want = np.float32 if dtype == F32 else np.uint16
+    assert w_in.dtype == want and w_out.dtype == want
+    assert w_in.flags.c_contiguous and w_out.flags.c_contiguous and w_in.shape == w_out.shape
+    centers, contexts = _i32(centers), _i32(contexts)
+    negs = _i32(negs)
+    num_pairs = int(centers.shape[0])
+    k = int(negs.shape[1]) if negs.ndim == 2 else 0
+    loss = C.c_double(0.0)
+    rc = _load().oracle_sgns_step(_ptr(w_in), _ptr(w_out), C.c_int64(w_in.shape[0]),
+                                  C.c_int32(w_in.shape[1]), C.c_int32(dtype), _ptr(centers),
+                                  _ptr(contexts), _ptr(negs), C.c_int64(num_pairs), C.c_int32(k),
+                                  C.c_float(lr), C.byref(loss))
+    _check(rc, "oracle_sgns_step")
+    return loss.value

@@ -1,0 +1,183 @@
+"""Pins for the oracle's SGNS iteration.
+
+Closed form at the initial state, a hand-computed one-dimensional case, central
+finite differences of the loss, dense autograd (the "same result as training
+the whole matrix" property of GraphScale §3.2/§4.2), untouched rows, batch
+order invariance, and the bf16 storage rule.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+
+def _batch(rng, n, b, k):
+    return (rng.integers(0, n, b).astype(np.int32), rng.integers(0, n, b).astype(np.int32),
+            rng.integers(0, n, (b, k)).astype(np.int32))
+
+
+def _dense_loss(w_in, w_out, c, o, neg):
+    """SGNS loss written with torch ops on the full tables (fp64)."""
+    u = w_in[torch.as_tensor(c, dtype=torch.long)]
+    vp = w_out[torch.as_tensor(o, dtype=torch.long)]
+    vn = w_out[torch.as_tensor(neg, dtype=torch.long)]
+    pos = torch.nn.functional.softplus(-(u * vp).sum(-1))
+    negl = torch.nn.functional.softplus((u[:, None, :] * vn).sum(-1))
+    return pos.sum() + negl.sum()
+
+
+def test_closed_form_at_initial_state(oracle):
+    rng = np.random.default_rng(0)
+    n, d, b, k, lr = 50, 8, 400, 5, 0.025
+    w_in = ((rng.random((n, d)) - 0.5) / d).astype(np.float32)
+    w_out = np.zeros((n, d), dtype=np.float32)
+    c, o, neg = _batch(rng, n, b, k)
+    w_in0 = w_in.copy()
+    loss = oracle.sgns_step(w_in, w_out, c, o, neg, lr)
+    assert loss == pytest.approx(b * (k + 1) * math.log(2.0), rel=1e-12)
+    np.testing.assert_array_equal(w_in, w_in0)          # all context rows were zero
+    want = np.zeros((n, d))
+    for i in range(b):
+        want[o[i]] += 0.5 * lr32(lr) * w_in0[c[i]].astype(np.float64)
+        for j in range(k):
+            want[neg[i, j]] -= 0.5 * lr32(lr) * w_in0[c[i]].astype(np.float64)
+    np.testing.assert_allclose(w_out, want.astype(np.float32), rtol=0, atol=1e-9)
+
+
+def lr32(lr):
+    return float(np.float32(lr))
+
+
+def test_hand_case_one_dimension(oracle):
+    # u = 2, v_ctx = 0.5, v_neg = -1: x0 = 1, x1 = -2
+    w_in = np.array([[2.0], [0.0], [0.0]], dtype=np.float32)
+    w_out = np.array([[0.0], [0.5], [-1.0]], dtype=np.float32)
+    lr = 0.5
+    loss = oracle.sgns_step(w_in, w_out, [0], [1], [[2]], lr)
+    s = lambda z: 1 / (1 + math.exp(-z))  # noqa: E731
+    g0, g1 = s(1.0) - 1, s(-2.0)
+    assert loss == pytest.approx(math.log1p(math.exp(-1.0)) + math.log1p(math.exp(-2.0)), rel=1e-14)
+    assert w_in[0, 0] == np.float32(2.0 - lr * (g0 * 0.5 + g1 * -1.0))
+    assert w_out[1, 0] == np.float32(0.5 - lr * g0 * 2.0)
+    assert w_out[2, 0] == np.float32(-1.0 - lr * g1 * 2.0)
+    assert w_in[1, 0] == 0 and w_in[2, 0] == 0 and w_out[0, 0] == 0
+
+
+def test_gradient_matches_finite_differences(oracle):
+    rng = np.random.default_rng(1)
+    n, d, b, k = 6, 3, 7, 2
+    base_in = rng.normal(0, 0.7, (n, d)).astype(np.float32)
+    base_out = rng.normal(0, 0.7, (n, d)).astype(np.float32)
+    c, o, neg = _batch(rng, n, b, k)
+
+    def loss_at(wi, wo):
+        # lr = 0: the call only evaluates the loss
+        return oracle.sgns_step(wi.copy(), wo.copy(), c, o, neg, 0.0)
+
+    lr = 1.0
+    wi, wo = base_in.copy(), base_out.copy()
+    oracle.sgns_step(wi, wo, c, o, neg, lr)
+    grad_in = (base_in.astype(np.float64) - wi) / lr     # analytic gradient (fp32-rounded)
+    grad_out = (base_out.astype(np.float64) - wo) / lr
+    h = 2.0 ** -7                                        # exactly representable perturbation
+    for table, grad in ((0, grad_in), (1, grad_out)):
+        for r in range(n):
+            for e in range(d):
+                plus = [base_in.copy(), base_out.copy()]
+                minus = [base_in.copy(), base_out.copy()]
+                plus[table][r, e] += np.float32(h)
+                minus[table][r, e] -= np.float32(h)
+                step = float(plus[table][r, e]) - float(minus[table][r, e])
+                fd = (loss_at(*plus) - loss_at(*minus)) / step
+                assert grad[r, e] == pytest.approx(fd, abs=2e-4), (table, r, e)
+
+
+def test_matches_dense_autograd_and_leaves_other_rows_alone(oracle):
+    rng = np.random.default_rng(2)
+    n, d, b, k, lr = 40, 16, 64, 5, 0.025
+    w_in = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    w_out = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    c, o, neg = _batch(rng, 25, b, k)                    # rows 25..39 never named
+    ti = torch.tensor(w_in, dtype=torch.float64, requires_grad=True)
+    to = torch.tensor(w_out, dtype=torch.float64, requires_grad=True)
+    dense = _dense_loss(ti, to, c, o, neg)
+    dense.backward()
+    before_in, before_out = w_in.copy(), w_out.copy()
+    loss = oracle.sgns_step(w_in, w_out, c, o, neg, lr)
+    assert loss == pytest.approx(dense.item(), rel=1e-12)
+    want_in = (before_in.astype(np.float64) - lr32(lr) * ti.grad.numpy()).astype(np.float32)
+    want_out = (before_out.astype(np.float64) - lr32(lr) * to.grad.numpy()).astype(np.float32)
+    # identical up to the order of fp64 additions before the single fp32 rounding
+    np.testing.assert_allclose(w_in, want_in, rtol=0, atol=1e-7)
+    np.testing.assert_allclose(w_out, want_out, rtol=0, atol=1e-7)
+    assert (ti.grad[25:] == 0).all() and (to.grad[25:] == 0).all()
+    np.testing.assert_array_equal(w_in[25:], before_in[25:])
+    np.testing.assert_array_equal(w_out[25:], before_out[25:])
+    touched_in = np.zeros(n, bool)
+    touched_in[c] = True
+    np.testing.assert_array_equal(w_in[~touched_in], before_in[~touched_in])
+
+
+def test_reads_see_pre_step_values(oracle):
+    # the same row is centre of one pair and context of another, and is hit twice:
+    # a sequential (pair-by-pair) update would give a different answer
+    w_in = np.array([[1.0, 0.5], [0.25, -1.0]], dtype=np.float32)
+    w_out = np.array([[0.5, 0.5], [-0.5, 1.0]], dtype=np.float32)
+    c = np.array([0, 1, 0], dtype=np.int32)
+    o = np.array([1, 0, 1], dtype=np.int32)
+    neg = np.array([[0], [1], [0]], dtype=np.int32)
+    ti = torch.tensor(w_in, dtype=torch.float64, requires_grad=True)
+    to = torch.tensor(w_out, dtype=torch.float64, requires_grad=True)
+    _dense_loss(ti, to, c, o, neg).backward()
+    a, b = w_in.copy(), w_out.copy()
+    oracle.sgns_step(a, b, c, o, neg, 0.5)
+    np.testing.assert_allclose(a, w_in - 0.5 * ti.grad.numpy(), atol=1e-7)
+    np.testing.assert_allclose(b, w_out - 0.5 * to.grad.numpy(), atol=1e-7)
+
+
+def test_batch_order_does_not_matter(oracle):
+    rng = np.random.default_rng(3)
+    n, d, b, k = 30, 8, 200, 3
+    w_in = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    w_out = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    c, o, neg = _batch(rng, n, b, k)
+    a_in, a_out = w_in.copy(), w_out.copy()
+    la = oracle.sgns_step(a_in, a_out, c, o, neg, 0.025)
+    perm = rng.permutation(b)
+    b_in, b_out = w_in.copy(), w_out.copy()
+    lb = oracle.sgns_step(b_in, b_out, c[perm], o[perm], neg[perm], 0.025)
+    assert la == pytest.approx(lb, rel=1e-13)
+    np.testing.assert_allclose(a_in, b_in, rtol=0, atol=1e-7)
+    np.testing.assert_allclose(a_out, b_out, rtol=0, atol=1e-7)
+
+
+def test_empty_batch_and_zero_negatives(oracle):
+    w_in = np.ones((3, 4), dtype=np.float32)
+    w_out = np.ones((3, 4), dtype=np.float32)
+    e = np.zeros(0, dtype=np.int32)
+    assert oracle.sgns_step(w_in, w_out, e, e, np.zeros((0, 5), dtype=np.int32), 0.1) == 0.0
+    assert (w_in == 1).all() and (w_out == 1).all()
+    loss = oracle.sgns_step(w_in, w_out, [0], [1], np.zeros((1, 0), dtype=np.int32), 0.1)
+    assert loss == pytest.approx(math.log1p(math.exp(-4.0)), rel=1e-14)
+
+
+def test_bf16_tables_round_to_nearest_even_once(oracle):
+    rng = np.random.default_rng(4)
+    n, d, b, k, lr = 20, 8, 100, 4, 0.05
+    f_in = torch.tensor(rng.normal(0, 0.5, (n, d)), dtype=torch.float32).to(torch.bfloat16)
+    f_out = torch.tensor(rng.normal(0, 0.5, (n, d)), dtype=torch.float32).to(torch.bfloat16)
+    c, o, neg = _batch(rng, n, b, k)
+    bits_in = f_in.view(torch.int16).numpy().view(np.uint16).copy()
+    bits_out = f_out.view(torch.int16).numpy().view(np.uint16).copy()
+    # the same step on exactly widened fp32 copies
+    w_in = f_in.to(torch.float32).numpy().copy()
+    w_out = f_out.to(torch.float32).numpy().copy()
+    l32 = oracle.sgns_step(w_in, w_out, c, o, neg, lr)
+    l16 = oracle.sgns_step(bits_in, bits_out, c, o, neg, lr, dtype=oracle.BF16)
+    assert l16 == l32                                    # reads widen exactly
+    want_in = torch.tensor(w_in).to(torch.bfloat16)      # torch rounds to nearest even
+    want_out = torch.tensor(w_out).to(torch.bfloat16)
+    got_in = torch.from_numpy(bits_in.view(np.int16)).view(torch.bfloat16)
+    got_out = torch.from_numpy(bits_out.view(np.int16)).view(torch.bfloat16)
+    assert torch.equal(got_in, want_in) and torch.equal(got_out, want_out)
