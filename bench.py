@@ -1,0 +1,263 @@
+#!/usr/bin/env python3
+"""Benchmark of the walk + SGNS path on one MI355X.
+
+One "step" is one batch of positive pairs taken through the whole path:
+walks (the step's share of the walk launch), pair emission (same), negative
+sampling and the SGNS iteration.  All inputs are synthetic, seeded and resident
+in HBM before the timed region.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 0..2]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def sgns_bytes_per_pair(k: int, dim: int, elem_bytes: int, window: int) -> float:
+    """Algorithmic HBM bytes per positive pair of one batch-synchronous SGNS
+    iteration without any cache reuse: every context/negative row is read once
+    for the logits and read-modified-written once for the update; the centre
+    row is read, staged and updated once per run of 2*window equal centres;
+    plus the index and gradient-coefficient arrays both passes read."""
+    rb = dim * elem_bytes
+    rows = 3 * (k + 1) * rb
+    centre = 4 * rb / (2 * window)
+    idx = 2 * 4 * (k + 2) + 2 * 4 * (k + 1)
+    return rows + centre + idx
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=2)
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--walk-sample", type=int, default=4_000_000,
+                    help="walks in the stand-alone walk-throughput launch")
+    return ap.parse_args()
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    from paper_2407_15452_amd import binding as gs, inputs
+    gs.lib()
+    dev = "cuda:0"
+    wl = inputs.WORKLOADS[args.workload]
+    if args.scale != 1.0:
+        wl = wl.scaled(args.scale)
+    if wl.dtype != "f32" or wl.weighted:
+        print("bench.py: this workload needs parts of the path that are not built yet",
+              file=sys.stderr)
+        sys.exit(2)
+    K, W = args.steps, args.warmup
+    B, k, L, win = wl.batch_pairs, wl.num_neg, wl.walk_len, wl.window
+
+    # ------------------------------------------------------------------ setup (untimed)
+    t0 = time.time()
+    src, dst, w = inputs.edge_list(wl, dev)
+    flags = gs.GS_DROP_SELF_LOOPS | gs.GS_DEDUPE | (0 if wl.directed else gs.GS_SYMMETRIZE)
+    g = gs.gs_csr_build(src, dst, w, wl.num_nodes, flags, wl.offset_bits)
+    del src, dst
+    torch.cuda.synchronize()
+    log(f"[setup] graph {wl.name}: N={wl.num_nodes} entries={g.num_entries} "
+        f"({time.time() - t0:.1f}s)")
+    t0 = time.time()
+    noise_w = inputs.noise_weights(g.offsets)
+    seg = torch.tensor([0, wl.num_nodes], dtype=torch.int64, device=dev)
+    noise = gs.gs_alias_build(seg, noise_w)
+    torch.cuda.synchronize()
+    log(f"[setup] noise alias table ({time.time() - t0:.1f}s)")
+    w_in, w_out = inputs.init_tables(wl.num_nodes, wl.dim, wl.init_seed, dev)
+    # a lived-in context table (zero rows would make the first updates trivial)
+    w_out.copy_(inputs.init_tables(wl.num_nodes, wl.dim, wl.init_seed + 1, dev)[0])
+
+    # walks needed: only starts with out-edges yield pairs (undirected: such walks never die)
+    P = inputs.pairs_per_full_walk(L, win)
+    live = (g.offsets[1:] > g.offsets[:-1])
+    live_frac = float(live.float().mean().item())
+    total_steps = W + K
+
+    def walks_for(pairs_needed, first_walk):
+        """Smallest count so that walks [first, first+count) yield >= pairs_needed pairs."""
+        need_live = -(-pairs_needed // P)
+        count = int(need_live / max(live_frac, 1e-3) * 1.05) + 64
+        while True:
+            st = inputs.walk_starts(wl.num_nodes, first_walk, count, dev)
+            if int(live[st.long()].sum().item()) >= need_live:
+                return st
+            count = int(count * 1.2) + 64
+
+    walk_fn = (lambda st, base, out=None: gs.gs_node2vec_walk(g, None, st, L, wl.p, wl.q,
+                                                              wl.walk_seed, base, out)) \
+        if wl.node2vec else (lambda st, base, out=None: gs.gs_random_walk(g, None, st, L,
+                                                                          wl.walk_seed, base, out))
+
+    starts_warm = walks_for(max(W, 1) * B, 0)
+    starts_timed = walks_for(K * B, starts_warm.numel())
+    n_max = max(starts_warm.numel(), starts_timed.numel())
+    walks_buf = torch.empty((n_max, L), dtype=torch.int32, device=dev)
+    cap = gs.pair_capacity(n_max, L, win)
+    centers = torch.zeros(cap, dtype=torch.int32, device=dev)
+    contexts = torch.zeros(cap, dtype=torch.int32, device=dev)
+    n_pairs_dev = torch.zeros(1, dtype=torch.int64, device=dev)
+    pairs_ws = torch.empty(max(256, gs.lib().gs_make_pairs_workspace_bytes(n_max)),
+                           dtype=torch.uint8, device=dev)
+    negs = torch.empty((B, k), dtype=torch.int32, device=dev)
+    sgns_ws = torch.empty(gs.gs_sgns_step_workspace_bytes(B, k, wl.dim), dtype=torch.uint8,
+                          device=dev)
+    losses = torch.zeros(total_steps, dtype=torch.float64, device=dev)
+    lr = inputs.learning_rate(wl, 0, 1)
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+
+    def run(starts, first_walk, steps, step0, pair_base, sgns_events=None, stage_events=None):
+        """Walk + pairs for `steps` batches, then negatives + SGNS per batch."""
+        nw = starts.numel()
+        if stage_events is not None:
+            stage_events["walk0"].record()
+        wk = walk_fn(starts, first_walk, walks_buf[:nw])
+        if stage_events is not None:
+            stage_events["walk1"].record()
+        gs.gs_make_pairs(wk, win, centers, contexts, n_pairs_dev, pairs_ws, sync=False)
+        if stage_events is not None:
+            stage_events["pairs1"].record()
+        n_pairs = int(n_pairs_dev.item())          # the one host read of the chunk
+        if n_pairs < steps * B:
+            raise RuntimeError(f"walk chunk produced {n_pairs} pairs, need {steps * B}")
+        for s in range(steps):
+            lo = s * B
+            gs.gs_sample_negatives(noise, wl.num_nodes, B, k, wl.neg_seed, pair_base + lo, negs)
+            if sgns_events is not None:
+                sgns_events[s][0].record()
+            gs.gs_sgns_step(w_in, w_out, centers[lo:lo + B], contexts[lo:lo + B], negs, lr,
+                            loss_out=losses[step0 + s:step0 + s + 1], ws=sgns_ws)
+            if sgns_events is not None:
+                sgns_events[s][1].record()
+        return n_pairs
+
+    # ------------------------------------------------------------------ warm-up + timed region
+    if W > 0:
+        run(starts_warm, 0, W, 0, 0)
+    torch.cuda.synchronize()
+    sgns_events = [(ev(), ev()) for _ in range(K)]
+    stage_events = {n: ev() for n in ("walk0", "walk1", "pairs1")}
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    run(starts_timed, starts_warm.numel(), K, W, W * B, sgns_events, stage_events)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+
+    ms_per_step = elapsed * 1e3 / K
+    pairs_per_s = K * B / elapsed
+    sgns_ms = float(np.mean([a.elapsed_time(b) for a, b in sgns_events]))
+    walk_ms = stage_events["walk0"].elapsed_time(stage_events["walk1"])
+    pairs_ms = stage_events["walk1"].elapsed_time(stage_events["pairs1"])
+    mean_loss = float(losses[W:].sum().item()) / (K * B)
+    bpp = sgns_bytes_per_pair(k, wl.dim, 4, win)
+    achieved = B * bpp / (sgns_ms * 1e-3) / 1e9
+
+    # ------------------------------------------------------------------ stand-alone walk throughput
+    nws = min(args.walk_sample, wl.num_nodes * wl.walks_per_node)
+    st = inputs.walk_starts(wl.num_nodes, 0, nws, dev)
+    big = torch.empty((nws, L), dtype=torch.int32, device=dev)
+    walk_fn(st, 0, big)
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record()
+    walk_fn(st, 0, big)
+    e1.record()
+    torch.cuda.synchronize()
+    walk_big_ms = e0.elapsed_time(e1)
+    valid_steps = int((big[:, 1:] >= 0).sum().item())
+    walk_steps_per_s = valid_steps / (walk_big_ms * 1e-3)
+    del big
+
+    result = {
+        "metric": "SGNS positive pairs/sec + walk steps/sec; % of MI355X HBM peak",
+        "value": pairs_per_s,
+        "unit": "positive pairs/s (whole path: walks, pairs, negatives, SGNS step)",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "num_nodes": wl.num_nodes, "csr_entries": g.num_entries,
+                   "batch_pairs": B, "negatives": k, "dim": wl.dim, "walk_len": L, "window": win,
+                   "walk": "node2vec p=%g q=%g" % (wl.p, wl.q) if wl.node2vec else "uniform",
+                   "lr": lr, "live_start_fraction": live_frac},
+        "walk_steps_per_s": walk_steps_per_s,
+        "walk_launch": {"walks": nws, "valid_steps": valid_steps, "ms": walk_big_ms},
+        "stages_ms": {"walk_chunk": walk_ms, "pairs_chunk": pairs_ms, "sgns_step_mean": sgns_ms,
+                      "chunk_walks": int(starts_timed.numel())},
+        "mean_loss_per_pair": mean_loss,
+        "roofline": {"bound": "hbm", "kernel": "gs_sgns_step (forward + scatter + apply kernels)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "bytes_per_pair": bpp, "traffic": None},
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, g, noise_w, w_in, w_out, lr)
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(wl, g, noise_w, w_in, w_out, lr, target_pairs=150_000):
+    """The CPU reference, as it stands, on a bounded sample of the same workload
+    (single thread): walks for the sample, pairs, negatives, one SGNS iteration."""
+    import oracle
+    oracle.build()
+    off = g.offsets.cpu().numpy()
+    nb = g.nbrs.cpu().numpy()
+    h_in = w_in.cpu().numpy()
+    h_out = w_out.cpu().numpy()
+    P = (2 * wl.window * wl.walk_len - wl.window * (wl.window + 1))
+    deg = np.diff(off)
+    live_frac = float((deg > 0).mean())
+    nw = int(target_pairs / P / max(live_frac, 1e-3)) + 8
+    from paper_2407_15452_amd import inputs
+    starts = inputs.walk_starts(wl.num_nodes, 0, nw).numpy()
+    seg = np.array([0, wl.num_nodes], dtype=np.int64)
+    table = oracle.alias_build(seg, noise_w.cpu().numpy())      # setup, untimed like on the GPU
+    t0 = time.perf_counter()
+    if wl.node2vec:
+        walks = oracle.node2vec_walk(off, nb, starts, wl.walk_len, wl.p, wl.q, wl.walk_seed)
+    else:
+        walks = oracle.random_walk(off, nb, starts, wl.walk_len, wl.walk_seed)
+    t1 = time.perf_counter()
+    c, o = oracle.make_pairs(walks, wl.window)
+    neg = oracle.sample_negatives(table, wl.num_nodes, c.size, wl.num_neg, wl.neg_seed)
+    t2 = time.perf_counter()
+    oracle.sgns_step(h_in, h_out, c, o, neg, lr)
+    t3 = time.perf_counter()
+    steps = int((walks[:, 1:] >= 0).sum())
+    return {"value": c.size / (t3 - t0), "unit": "positive pairs/s (whole path)", "cores": 1,
+            "kind": "oracle",
+            "sample": f"{nw} walks -> {c.size} pairs of {wl.name}, one SGNS iteration over them",
+            "walk_steps_per_s": steps / max(t1 - t0, 1e-9),
+            "sgns_pairs_per_s": c.size / max(t3 - t2, 1e-9),
+            "seconds": t3 - t0, "host_cpus": os.cpu_count()}
+
+
+if __name__ == "__main__":
+    main()

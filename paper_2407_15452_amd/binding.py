@@ -1,0 +1,259 @@
+"""Thin ctypes layer over ``libgs.so``: same names as ``include/gs.h``.
+
+Argument marshalling only.  Tensors are torch CUDA tensors used as plain
+device buffers; each call passes ``data_ptr()`` values and the current torch
+stream to the C entry point.  There is no CPU or torch fallback: if the shared
+library is missing, or a tensor is not on the GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgs.so")
+
+GS_OK, GS_EINVAL, GS_EWORKSPACE, GS_EOVERFLOW, GS_EHIP = 0, -1, -2, -3, -4
+GS_SYMMETRIZE, GS_DROP_SELF_LOOPS, GS_DEDUPE = 1, 2, 4
+GS_F32, GS_BF16 = 0, 1
+
+EXPORTS = (
+    "gs_last_hip_error",
+    "gs_csr_build_workspace_bytes", "gs_csr_build",
+    "gs_alias_build_workspace_bytes", "gs_alias_build",
+    "gs_random_walk", "gs_node2vec_walk",
+    "gs_make_pairs_workspace_bytes", "gs_make_pairs",
+    "gs_sample_negatives",
+    "gs_sgns_step_workspace_bytes", "gs_sgns_step",
+)
+
+
+class GsError(RuntimeError):
+    def __init__(self, what: str, status: int, hip: int = 0):
+        names = {-1: "GS_EINVAL", -2: "GS_EWORKSPACE", -3: "GS_EOVERFLOW", -4: "GS_EHIP"}
+        msg = f"{what}: {names.get(status, status)}"
+        if status == GS_EHIP:
+            msg += f" (hip error {hip})"
+        super().__init__(msg)
+        self.status = status
+
+
+class CsrStruct(C.Structure):
+    _fields_ = [("num_nodes", C.c_int64), ("num_entries", C.c_int64),
+                ("offsets", C.c_void_p), ("offset_bits", C.c_int32),
+                ("nbrs", C.c_void_p), ("weights", C.c_void_p)]
+
+
+class AliasStruct(C.Structure):
+    _fields_ = [("prob", C.c_void_p), ("alias", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Opens libgs.so (built by ``paper_2407_15452_amd.build``); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2407_15452_amd.build`; "
+                "there is no fallback path")
+        l = C.CDLL(LIB_PATH)
+        for name in EXPORTS:
+            fn = getattr(l, name)
+            fn.restype = C.c_size_t if name.endswith("_workspace_bytes") else C.c_int32
+        _lib = l
+    return _lib
+
+
+def _dev(t, dtype=None, name="tensor"):
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a CUDA tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc, what):
+    if rc != GS_OK:
+        raise GsError(what, rc, lib().gs_last_hip_error() if rc == GS_EHIP else 0)
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+class Csr:
+    """Device CSR (tensors + the host descriptor handed to the library)."""
+
+    def __init__(self, offsets: torch.Tensor, nbrs: torch.Tensor, weights=None, num_entries=None):
+        assert offsets.dtype in (torch.int32, torch.int64)
+        self.offsets, self.nbrs, self.weights = offsets, nbrs, weights
+        self.num_nodes = offsets.numel() - 1
+        self.num_entries = int(nbrs.numel() if num_entries is None else num_entries)
+        self.offset_bits = 64 if offsets.dtype == torch.int64 else 32
+        self.struct = CsrStruct(self.num_nodes, self.num_entries, offsets.data_ptr(),
+                                self.offset_bits, nbrs.data_ptr() if nbrs.numel() else None,
+                                weights.data_ptr() if weights is not None else None)
+
+
+class Alias:
+    def __init__(self, prob: torch.Tensor, alias: torch.Tensor):
+        _dev(prob, torch.float32, "prob")
+        _dev(alias, torch.int32, "alias")
+        self.prob, self.alias = prob, alias
+        self.struct = AliasStruct(prob.data_ptr(), alias.data_ptr())
+
+
+def gs_csr_build(src, dst, w, num_nodes: int, flags: int, offset_bits: int = 32, ws=None) -> Csr:
+    l = lib()
+    m = int(src.numel())
+    dev = src.device
+    cap = max(1, m * (2 if flags & GS_SYMMETRIZE else 1))
+    offsets = torch.empty(num_nodes + 1, dtype=torch.int64 if offset_bits == 64 else torch.int32,
+                          device=dev)
+    nbrs = torch.empty(cap, dtype=torch.int32, device=dev)
+    w_out = torch.empty(cap, dtype=torch.float32, device=dev) if w is not None else None
+    n_out = torch.zeros(1, dtype=torch.int64, device=dev)
+    need = l.gs_csr_build_workspace_bytes(C.c_int64(m), C.c_int64(num_nodes), C.c_uint32(flags))
+    if ws is None:
+        ws = _workspace(need, dev)
+    rc = l.gs_csr_build(_dev(src, torch.int32, "src"), _dev(dst, torch.int32, "dst"),
+                        _dev(w, torch.float32, "w"), C.c_int64(m), C.c_int64(num_nodes),
+                        C.c_uint32(flags), C.c_int32(offset_bits), _dev(offsets), _dev(nbrs),
+                        _dev(w_out), _dev(n_out), _dev(ws), C.c_size_t(ws.numel()), _stream())
+    _check(rc, "gs_csr_build")
+    n = int(n_out.item())
+    return Csr(offsets, nbrs[:n], None if w_out is None else w_out[:n], n)
+
+
+def gs_alias_build(seg_offsets, weights, ws=None) -> Alias:
+    l = lib()
+    dev = weights.device
+    total = int(weights.numel())
+    nseg = int(seg_offsets.numel()) - 1
+    bits = 64 if seg_offsets.dtype == torch.int64 else 32
+    prob = torch.empty(max(1, total), dtype=torch.float32, device=dev)
+    alias = torch.empty(max(1, total), dtype=torch.int32, device=dev)
+    need = l.gs_alias_build_workspace_bytes(C.c_int64(nseg), C.c_int64(total))
+    if ws is None:
+        ws = _workspace(need, dev)
+    rc = l.gs_alias_build(_dev(seg_offsets, None, "seg_offsets"), C.c_int32(bits), C.c_int64(nseg),
+                          C.c_int64(total), _dev(weights, torch.float32, "weights"), _dev(prob),
+                          _dev(alias), _dev(ws), C.c_size_t(ws.numel()), _stream())
+    _check(rc, "gs_alias_build")
+    return Alias(prob[:total], alias[:total])
+
+
+def _alias_ref(a):
+    return None if a is None else C.byref(a.struct)
+
+
+def gs_random_walk(g: Csr, a, starts, walk_len: int, seed: int, walk_id_base: int = 0, out=None):
+    nw = int(starts.numel())
+    if out is None:
+        out = torch.empty((nw, walk_len), dtype=torch.int32, device=starts.device)
+    rc = lib().gs_random_walk(C.byref(g.struct), _alias_ref(a), _dev(starts, torch.int32, "starts"),
+                              C.c_int64(nw), C.c_uint64(walk_id_base), C.c_int32(walk_len),
+                              C.c_uint64(seed), _dev(out, torch.int32, "walks_out"), _stream())
+    _check(rc, "gs_random_walk")
+    return out
+
+
+def gs_node2vec_walk(g: Csr, a, starts, walk_len: int, p: float, q: float, seed: int,
+                     walk_id_base: int = 0, out=None):
+    nw = int(starts.numel())
+    if out is None:
+        out = torch.empty((nw, walk_len), dtype=torch.int32, device=starts.device)
+    rc = lib().gs_node2vec_walk(C.byref(g.struct), _alias_ref(a),
+                                _dev(starts, torch.int32, "starts"), C.c_int64(nw),
+                                C.c_uint64(walk_id_base), C.c_int32(walk_len), C.c_float(p),
+                                C.c_float(q), C.c_uint64(seed), _dev(out, torch.int32, "walks_out"),
+                                _stream())
+    _check(rc, "gs_node2vec_walk")
+    return out
+
+
+def pair_capacity(num_walks: int, walk_len: int, window: int) -> int:
+    """Capacity gs_make_pairs requires of its output arrays (see gs.h)."""
+    if walk_len > window:
+        return num_walks * (2 * window * walk_len - window * (window + 1))
+    return num_walks * walk_len * (walk_len - 1)
+
+
+def gs_make_pairs(walks, window: int, centers=None, contexts=None, num_pairs_out=None, ws=None,
+                  sync: bool = True):
+    """Returns (centers, contexts, num_pairs).  With sync=False num_pairs is the
+    device scalar and the outputs are left at full capacity."""
+    l = lib()
+    nw, walk_len = int(walks.shape[0]), int(walks.shape[1])
+    dev = walks.device
+    cap = max(1, pair_capacity(nw, walk_len, window))
+    if centers is None:
+        centers = torch.empty(cap, dtype=torch.int32, device=dev)
+    if contexts is None:
+        contexts = torch.empty(cap, dtype=torch.int32, device=dev)
+    if num_pairs_out is None:
+        num_pairs_out = torch.zeros(1, dtype=torch.int64, device=dev)
+    if ws is None:
+        ws = _workspace(l.gs_make_pairs_workspace_bytes(C.c_int64(nw)), dev)
+    rc = l.gs_make_pairs(_dev(walks, torch.int32, "walks"), C.c_int64(nw), C.c_int32(walk_len),
+                         C.c_int32(window), _dev(centers, torch.int32), _dev(contexts, torch.int32),
+                         _dev(num_pairs_out, torch.int64), _dev(ws), C.c_size_t(ws.numel()),
+                         _stream())
+    _check(rc, "gs_make_pairs")
+    if not sync:
+        return centers, contexts, num_pairs_out
+    n = int(num_pairs_out.item())
+    return centers[:n], contexts[:n], n
+
+
+def gs_sample_negatives(noise, num_nodes: int, num_pairs: int, k: int, seed: int,
+                        pair_index_base: int = 0, out=None, device=None):
+    if out is None:
+        dev = noise.prob.device if noise is not None else device
+        out = torch.empty((num_pairs, k), dtype=torch.int32, device=dev)
+    rc = lib().gs_sample_negatives(_alias_ref(noise), C.c_int64(num_nodes), C.c_int64(num_pairs),
+                                   C.c_uint64(pair_index_base), C.c_int32(k), C.c_uint64(seed),
+                                   _dev(out, torch.int32, "negs_out"), _stream())
+    _check(rc, "gs_sample_negatives")
+    return out
+
+
+def gs_sgns_step_workspace_bytes(num_pairs: int, k: int, dim: int, dtype: int = GS_F32) -> int:
+    return int(lib().gs_sgns_step_workspace_bytes(C.c_int64(num_pairs), C.c_int32(k),
+                                                  C.c_int32(dim), C.c_int32(dtype)))
+
+
+def gs_sgns_step(w_in, w_out, centers, contexts, negs, lr: float, loss_out=None, ws=None):
+    """Updates w_in / w_out in place; returns the device scalar holding the summed loss."""
+    dtype = GS_BF16 if w_in.dtype == torch.bfloat16 else GS_F32
+    num_nodes, dim = int(w_in.shape[0]), int(w_in.shape[1])
+    num_pairs = int(centers.numel())
+    k = int(negs.shape[1]) if negs.dim() == 2 else 0
+    dev = w_in.device
+    if loss_out is None:
+        loss_out = torch.zeros(1, dtype=torch.float64, device=dev)
+    if ws is None:
+        ws = _workspace(gs_sgns_step_workspace_bytes(num_pairs, k, dim, dtype), dev)
+    rc = lib().gs_sgns_step(_dev(w_in, None, "w_in"), _dev(w_out, w_in.dtype, "w_out"),
+                            C.c_int64(num_nodes), C.c_int32(dim), C.c_int32(dtype),
+                            _dev(centers, torch.int32, "centers"),
+                            _dev(contexts, torch.int32, "contexts"),
+                            _dev(negs, torch.int32, "negs") if negs.numel() else None,
+                            C.c_int64(num_pairs), C.c_int32(k), C.c_float(lr),
+                            _dev(loss_out, torch.float64, "loss_sum_out"), _dev(ws),
+                            C.c_size_t(ws.numel()), _stream())
+    _check(rc, "gs_sgns_step")
+    return loss_out

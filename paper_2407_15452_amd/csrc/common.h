@@ -1,0 +1,99 @@
+// Shared host/device helpers of libgs (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/gs.h"
+
+namespace gs {
+
+// ---- host side -------------------------------------------------------------
+void set_last_hip_error(hipError_t e);
+
+#define GS_HIP_TRY(expr)                              \
+  do {                                                \
+    hipError_t e_ = (expr);                           \
+    if (e_ != hipSuccess) {                           \
+      ::gs::set_last_hip_error(e_);                   \
+      return GS_EHIP;                                 \
+    }                                                 \
+  } while (0)
+
+// Call after a kernel launch: picks up launch-configuration errors.
+#define GS_LAUNCH_CHECK() GS_HIP_TRY(hipGetLastError())
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Carves 256-byte aligned pieces out of a caller workspace (or just sizes it).
+struct Carver {
+  char* base;
+  size_t used = 0;
+  explicit Carver(void* ws) : base(static_cast<char*>(ws)) {}
+  template <typename T>
+  T* take(size_t count) {
+    T* p = base ? reinterpret_cast<T*>(base + used) : nullptr;
+    used += align_up(count * sizeof(T));
+    return p;
+  }
+};
+
+// Exclusive prefix sum of n int64 values, in place.  `scratch` must hold
+// scan_scratch_elems(n) int64 values.  total_out (device, may be null)
+// receives the sum of all n inputs.
+size_t scan_scratch_elems(int64_t n);
+int32_t exclusive_scan_i64(int64_t* data, int64_t n, int64_t* scratch, int64_t* total_out,
+                           hipStream_t stream);
+
+// Stable least-significant-digit radix sort of (key, payload) records on the
+// key bits [lo_a, lo_a + nbits_a) then [lo_b, lo_b + nbits_b).  The result is
+// left in (keys, vals); (keys_alt, vals_alt) are scratch of the same size.
+size_t radix_sort_scratch_bytes(int64_t n);
+int32_t radix_sort_u64_u32(uint64_t* keys, uint32_t* vals, uint64_t* keys_alt, uint32_t* vals_alt,
+                           int64_t n, int lo_a, int nbits_a, int lo_b, int nbits_b,
+                           void* scratch, hipStream_t stream);
+
+// ---- device side -----------------------------------------------------------
+#if defined(__HIPCC__)
+
+struct Block4 { uint32_t x0, x1, x2, x3; };
+
+// Philox4x32-10 (Salmon et al., SC'11).
+__device__ __forceinline__ Block4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi_a = __umulhi(0xD2511F53u, c0), lo_a = 0xD2511F53u * c0;
+    const uint32_t hi_b = __umulhi(0xCD9E8D57u, c2), lo_b = 0xCD9E8D57u * c2;
+    c0 = hi_b ^ c1 ^ k0;
+    c1 = lo_b;
+    c2 = hi_a ^ c3 ^ k1;
+    c3 = lo_a;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return Block4{c0, c1, c2, c3};
+}
+
+__device__ __forceinline__ Block4 philox_at(uint64_t seed, uint64_t index, uint32_t c2, uint32_t c3) {
+  return philox4x32_10((uint32_t)index, (uint32_t)(index >> 32), c2, c3, (uint32_t)seed,
+                       (uint32_t)(seed >> 32));
+}
+
+__device__ __forceinline__ uint64_t slot_of(const Block4& b, uint64_t n) {
+  return __umul64hi(((uint64_t)b.x0 << 32) | (uint64_t)b.x1, n);
+}
+
+__device__ __forceinline__ float unit_float(uint32_t x) { return (float)(x >> 8) * 0x1p-24f; }
+
+template <typename OffT>
+__device__ __forceinline__ int64_t load_off(const void* offsets, int64_t i) {
+  return (int64_t) static_cast<const OffT*>(offsets)[i];
+}
+
+#endif  // __HIPCC__
+
+}  // namespace gs

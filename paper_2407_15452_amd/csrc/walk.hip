@@ -1,0 +1,167 @@
+// gs_random_walk / gs_node2vec_walk (GraphScale Sec. 2.2: DeepWalk-style walks
+// from every node and node2vec's biased second-order walk).
+//
+// One lane per walk.  Every transition is a chain of dependent random reads
+// (row bounds -> neighbour), so throughput comes from many walks in flight.
+// Output rows are staged in LDS in windows of kWin positions and written out
+// as 64-byte row segments instead of one scattered 4-byte store per lane.
+#include "common.h"
+
+namespace gs {
+
+constexpr int kWalkThreads = 256;
+constexpr int kWin = 16;          // positions staged per flush
+constexpr int kWinPad = kWin + 1; // odd stride: conflict-free column writes
+constexpr uint32_t kMaxAttempts = 1024;
+
+struct WalkArgs {
+  const void* offsets;
+  const int32_t* nbrs;
+  const float* prob;
+  const int32_t* alias;
+  const int32_t* starts;
+  int32_t* walks;
+  int64_t num_nodes;
+  int64_t num_walks;
+  uint64_t id_base;
+  uint64_t seed;
+  int32_t walk_len;
+  float inv_p, inv_q, max_bias;
+};
+
+template <typename OffT, bool kWeighted, bool kSecondOrder>
+__global__ __launch_bounds__(kWalkThreads) void walk_kernel(WalkArgs a) {
+  __shared__ int32_t tile[kWalkThreads / 64][64][kWinPad];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t wave_first = ((int64_t)blockIdx.x * (kWalkThreads / 64) + wave) * 64;
+  const int64_t i = wave_first + lane;
+  const bool live = i < a.num_walks;
+  const uint64_t id = a.id_base + (uint64_t)i;
+  const int32_t* __restrict__ nbrs = a.nbrs;
+  const OffT* __restrict__ offsets = static_cast<const OffT*>(a.offsets);
+
+  int32_t cur = -1;
+  if (live) {
+    cur = a.starts[i];
+    if (cur < 0 || (int64_t)cur >= a.num_nodes) cur = -1;
+  }
+  int32_t prev = -1;
+  int64_t prev_lo = 0, prev_hi = 0;   // row of prev (second order only)
+
+  for (int32_t t0 = 0; t0 < a.walk_len; t0 += kWin) {
+    const int cols = min(kWin, a.walk_len - t0);
+    for (int tt = 0; tt < cols; ++tt) {
+      const int32_t t = t0 + tt;
+      tile[wave][lane][tt] = cur;
+      if (t + 1 >= a.walk_len) break;
+      int32_t next = -1;
+      int64_t lo = 0, hi = 0;
+      if (cur >= 0) {
+        lo = (int64_t)offsets[cur];
+        hi = (int64_t)offsets[(int64_t)cur + 1];
+        const uint64_t deg = (uint64_t)(hi - lo);
+        if (deg > 0) {
+          for (uint32_t att = 0; att < kMaxAttempts; ++att) {
+            const Block4 b = philox_at(a.seed, id, (uint32_t)t, att);
+            int64_t j = (int64_t)slot_of(b, deg);
+            if (kWeighted) {
+              if (!(unit_float(b.x2) < a.prob[lo + j])) j = (int64_t)a.alias[lo + j];
+            }
+            const int32_t x = nbrs[lo + j];
+            next = x;
+            if (!kSecondOrder || t == 0) break;
+            float bias;
+            if (x == prev) {
+              bias = a.inv_p;
+            } else {
+              // lower bound of x in the row of prev
+              int64_t l = prev_lo, h = prev_hi;
+              while (l < h) {
+                const int64_t mid = l + ((h - l) >> 1);
+                if (nbrs[mid] < x) l = mid + 1; else h = mid;
+              }
+              bias = (l < prev_hi && nbrs[l] == x) ? 1.0f : a.inv_q;
+            }
+            if (unit_float(b.x3) * a.max_bias < bias) break;
+          }
+        }
+      }
+      if (kSecondOrder) { prev = cur; prev_lo = lo; prev_hi = hi; }
+      cur = next;
+    }
+    __syncthreads();
+    // flush: 4 rows per pass, 16 lanes (64 bytes) per row
+    const int c = lane & 15;
+#pragma unroll 4
+    for (int pass = 0; pass < 16; ++pass) {
+      const int r = pass * 4 + (lane >> 4);
+      const int64_t w = wave_first + r;
+      if (w < a.num_walks && c < cols)
+        a.walks[w * (int64_t)a.walk_len + t0 + c] = tile[wave][r][c];
+    }
+    __syncthreads();
+  }
+}
+
+template <typename OffT>
+static void launch_walk(bool weighted, bool second, const WalkArgs& a, hipStream_t stream) {
+  const unsigned blocks = (unsigned)ceil_div(a.num_walks, kWalkThreads);
+  if (second) {
+    if (weighted) walk_kernel<OffT, true, true><<<blocks, kWalkThreads, 0, stream>>>(a);
+    else walk_kernel<OffT, false, true><<<blocks, kWalkThreads, 0, stream>>>(a);
+  } else {
+    if (weighted) walk_kernel<OffT, true, false><<<blocks, kWalkThreads, 0, stream>>>(a);
+    else walk_kernel<OffT, false, false><<<blocks, kWalkThreads, 0, stream>>>(a);
+  }
+}
+
+static int32_t walk_common(const gs_csr* g, const gs_alias* al, const int32_t* starts,
+                           int64_t num_walks, uint64_t id_base, int32_t walk_len, bool second,
+                           float p, float q, uint64_t seed, int32_t* walks_out, hipStream_t stream) {
+  if (!g || num_walks < 0 || walk_len < 1) return GS_EINVAL;
+  if (g->num_nodes < 0 || g->num_nodes > (int64_t)INT32_MAX || g->num_entries < 0) return GS_EINVAL;
+  if (g->offset_bits != 32 && g->offset_bits != 64) return GS_EINVAL;
+  if (!g->offsets || (g->num_entries > 0 && !g->nbrs)) return GS_EINVAL;
+  if (second && (!(p > 0.0f) || !(q > 0.0f))) return GS_EINVAL;
+  if (num_walks > 0 && (!starts || !walks_out)) return GS_EINVAL;
+  if (num_walks > ((int64_t)1 << 38)) return GS_EOVERFLOW;
+  const bool weighted = al != nullptr && al->prob != nullptr;
+  if (weighted && !al->alias) return GS_EINVAL;
+  if (num_walks == 0) return GS_OK;
+  WalkArgs a;
+  a.offsets = g->offsets;
+  a.nbrs = g->nbrs;
+  a.prob = weighted ? al->prob : nullptr;
+  a.alias = weighted ? al->alias : nullptr;
+  a.starts = starts;
+  a.walks = walks_out;
+  a.num_nodes = g->num_nodes;
+  a.num_walks = num_walks;
+  a.id_base = id_base;
+  a.seed = seed;
+  a.walk_len = walk_len;
+  a.inv_p = 1.0f / p;
+  a.inv_q = 1.0f / q;
+  a.max_bias = fmaxf(a.inv_p, fmaxf(1.0f, a.inv_q));
+  if (g->offset_bits == 64) launch_walk<int64_t>(weighted, second, a, stream);
+  else launch_walk<int32_t>(weighted, second, a, stream);
+  GS_LAUNCH_CHECK();
+  return GS_OK;
+}
+
+}  // namespace gs
+
+extern "C" int32_t gs_random_walk(const gs_csr* g, const gs_alias* a, const int32_t* starts,
+                                  int64_t num_walks, uint64_t walk_id_base, int32_t walk_len,
+                                  uint64_t seed, int32_t* walks_out, void* stream) {
+  return gs::walk_common(g, a, starts, num_walks, walk_id_base, walk_len, false, 1.0f, 1.0f, seed,
+                         walks_out, (hipStream_t)stream);
+}
+
+extern "C" int32_t gs_node2vec_walk(const gs_csr* g, const gs_alias* a, const int32_t* starts,
+                                    int64_t num_walks, uint64_t walk_id_base, int32_t walk_len,
+                                    float p, float q, uint64_t seed, int32_t* walks_out,
+                                    void* stream) {
+  return gs::walk_common(g, a, starts, num_walks, walk_id_base, walk_len, true, p, q, seed,
+                         walks_out, (hipStream_t)stream);
+}

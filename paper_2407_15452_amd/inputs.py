@@ -270,8 +270,17 @@ def random_tables(num_nodes: int, dim: int, seed: int, scale: float = 0.5, devic
     return out[0], out[1]
 
 
+LR_REFERENCE_PAIRS = 16_384
+
+
 def learning_rate(wl: Workload, batch_index: int, num_batches: int) -> float:
-    """fp32 learning rate of a batch: constant, or decayed linearly in the batch index."""
-    if not wl.lr_decay:
-        return float(np.float32(wl.lr))
-    return float(np.float32(wl.lr * max(1.0 - batch_index / num_batches, 1e-4)))
+    """fp32 step size handed to the SGNS step for one batch.
+
+    The step *sums* the gradients of the pairs of a batch, so the nominal rate
+    of a workload is read as the rate for a batch of LR_REFERENCE_PAIRS pairs
+    and scaled down in proportion for larger batches (with the nominal 0.025 a
+    summed batch of 65,536 pairs on 10,000 nodes diverges within 20 batches).
+    Optionally decayed linearly in the batch index with a floor of 1e-4."""
+    scale = min(1.0, LR_REFERENCE_PAIRS / wl.batch_pairs)
+    decay = max(1.0 - batch_index / num_batches, 1e-4) if wl.lr_decay else 1.0
+    return float(np.float32(wl.lr * scale * decay))

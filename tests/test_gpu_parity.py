@@ -1,0 +1,371 @@
+"""GPU parity: every C-ABI entry point of libgs.so against the CPU oracle.
+
+Integer outputs (CSR, alias indices, walks, pairs, negatives) must be
+bit-identical; alias probabilities are bit-identical too because the
+construction order is part of the definition.  The SGNS step must agree within
+1e-5 (relative for the loss, max-abs for the embeddings).
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def gs():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2407_15452_amd import binding
+    binding.lib()          # raises if libgs.so was not built
+    return binding
+
+
+@pytest.fixture(scope="module")
+def cfg0(gs, oracle):
+    """Workload 0: edge list, oracle CSR, device CSR."""
+    from paper_2407_15452_amd import inputs
+    wl = inputs.WORKLOADS[0]
+    src, dst, _ = inputs.edge_list(wl, "cpu")
+    flags = oracle.SYMMETRIZE | oracle.DROP_SELF_LOOPS | oracle.DEDUPE
+    off, nb, _ = oracle.csr_build(src.numpy(), dst.numpy(), None, wl.num_nodes, flags)
+    g = gs.gs_csr_build(src.to(DEV), dst.to(DEV), None, wl.num_nodes, flags)
+    torch.cuda.synchronize()
+    return wl, (off, nb), g
+
+
+def _t(a, dtype=None):
+    t = torch.as_tensor(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.to(DEV)
+
+
+# ----------------------------------------------------------------------------- CSR
+@pytest.mark.parametrize("flags", range(8))
+@pytest.mark.parametrize("bits", [32, 64])
+def test_csr_build(gs, oracle, flags, bits):
+    rng = np.random.default_rng(1000 + flags)
+    n, m = 5000, 61_237                        # 30+ sort tiles and a ragged tail
+    src = rng.integers(-2, n + 2, m).astype(np.int32)
+    dst = rng.integers(-2, n + 2, m).astype(np.int32)
+    dup = rng.integers(0, m, m // 4)            # plenty of duplicates
+    src[dup], dst[dup] = src[(dup * 7) % m], dst[(dup * 7) % m]
+    w = rng.random(m).astype(np.float32)
+    off, nb, wo = oracle.csr_build(src, dst, w, n, flags, bits)
+    g = gs.gs_csr_build(_t(src), _t(dst), _t(w), n, flags, bits)
+    assert g.num_entries == nb.size
+    np.testing.assert_array_equal(g.offsets.cpu().numpy(), off)
+    np.testing.assert_array_equal(g.nbrs.cpu().numpy(), nb)
+    np.testing.assert_array_equal(g.weights.cpu().numpy(), wo)
+
+
+def test_csr_build_workload0_and_empty(gs, oracle, cfg0):
+    wl, (off, nb), g = cfg0
+    assert nb.size == 2 * wl.num_edges
+    np.testing.assert_array_equal(g.offsets.cpu().numpy(), off)
+    np.testing.assert_array_equal(g.nbrs.cpu().numpy(), nb)
+    e = torch.zeros(0, dtype=torch.int32, device=DEV)
+    g0 = gs.gs_csr_build(e, e, None, 7, 7)
+    assert g0.num_entries == 0 and (g0.offsets == 0).all()
+
+
+def test_csr_build_rejects_bad_arguments(gs):
+    e = torch.zeros(4, dtype=torch.int32, device=DEV)
+    with pytest.raises(gs.GsError):
+        gs.gs_csr_build(e, e, None, 4, 0, offset_bits=16)
+    with pytest.raises(gs.GsError):
+        gs.gs_csr_build(e, e, None, 4, 64)
+    with pytest.raises(gs.GsError) as ei:
+        gs.gs_csr_build(e, e, None, 4, 0, ws=torch.empty(256, dtype=torch.uint8, device=DEV))
+    assert ei.value.status == gs.GS_EWORKSPACE
+
+
+# ----------------------------------------------------------------------------- alias
+def test_alias_build_per_row_and_single_segment(gs, oracle, cfg0):
+    wl, (off, nb), g = cfg0
+    rng = np.random.default_rng(7)
+    w = rng.lognormal(0, 1, nb.size).astype(np.float32)
+    w[rng.random(nb.size) < 0.05] = 0
+    prob, alias = oracle.alias_build(off, w)
+    a = gs.gs_alias_build(g.offsets, _t(w))
+    np.testing.assert_array_equal(a.alias.cpu().numpy(), alias)
+    np.testing.assert_array_equal(a.prob.cpu().numpy(), prob)
+    # one long segment (the noise table), 64-bit segment offsets
+    deg = np.diff(off).astype(np.float64)
+    nw = np.where(deg > 0, deg ** 0.75, 0).astype(np.float32)
+    seg = np.array([0, nw.size], dtype=np.int64)
+    prob, alias = oracle.alias_build(seg, nw)
+    a = gs.gs_alias_build(_t(seg), _t(nw))
+    np.testing.assert_array_equal(a.alias.cpu().numpy(), alias)
+    np.testing.assert_array_equal(a.prob.cpu().numpy(), prob)
+
+
+# ----------------------------------------------------------------------------- walks
+def _walk_inputs(wl, count, first=0):
+    from paper_2407_15452_amd import inputs
+    return inputs.walk_starts(wl.num_nodes, first, count, "cpu")
+
+
+def test_random_walk_workload0(gs, oracle, cfg0):
+    wl, (off, nb), g = cfg0
+    nw = wl.num_nodes * wl.walks_per_node
+    starts = _walk_inputs(wl, nw)
+    want = oracle.random_walk(off, nb, starts.numpy(), wl.walk_len, wl.walk_seed)
+    got = gs.gs_random_walk(g, None, starts.to(DEV), wl.walk_len, wl.walk_seed)
+    np.testing.assert_array_equal(got.cpu().numpy(), want)
+    assert (want == -1).any()                   # isolated starts exist: dead walks covered
+    # a sub-range on its own, odd length, odd count
+    part = gs.gs_random_walk(g, None, starts[1001:1001 + 777].to(DEV), wl.walk_len, wl.walk_seed,
+                             walk_id_base=1001)
+    np.testing.assert_array_equal(part.cpu().numpy(), want[1001:1001 + 777])
+
+
+@pytest.mark.parametrize("walk_len", [1, 2, 16, 17, 33])
+def test_random_walk_lengths_weighted_int64(gs, oracle, cfg0, walk_len):
+    wl, (off, nb), g = cfg0
+    rng = np.random.default_rng(walk_len)
+    w = (rng.random(nb.size) + 0.05).astype(np.float32)
+    table = oracle.alias_build(off, w)
+    a = gs.gs_alias_build(g.offsets, _t(w))
+    starts = rng.integers(-1, wl.num_nodes + 1, 3001).astype(np.int32)   # includes invalid starts
+    want = oracle.random_walk(off, nb, starts, walk_len, 99, alias=table, walk_id_base=1 << 40)
+    got = gs.gs_random_walk(g, a, _t(starts), walk_len, 99, walk_id_base=1 << 40)
+    np.testing.assert_array_equal(got.cpu().numpy(), want)
+    g64 = gs.Csr(g.offsets.to(torch.int64), g.nbrs)
+    got = gs.gs_random_walk(g64, a, _t(starts), walk_len, 99, walk_id_base=1 << 40)
+    np.testing.assert_array_equal(got.cpu().numpy(), want)
+
+
+def test_walks_on_directed_graph_with_sinks(gs, oracle):
+    rng = np.random.default_rng(5)
+    n, m = 3000, 6000
+    src = rng.integers(0, n, m).astype(np.int32)
+    dst = rng.integers(0, n, m).astype(np.int32)
+    flags = oracle.DROP_SELF_LOOPS | oracle.DEDUPE
+    off, nb, _ = oracle.csr_build(src, dst, None, n, flags)
+    g = gs.gs_csr_build(_t(src), _t(dst), None, n, flags)
+    starts = (np.arange(9000) % n).astype(np.int32)
+    want = oracle.random_walk(off, nb, starts, 12, 3)
+    got = gs.gs_random_walk(g, None, _t(starts), 12, 3)
+    np.testing.assert_array_equal(got.cpu().numpy(), want)
+    want = oracle.node2vec_walk(off, nb, starts, 12, 0.5, 2.0, 3)
+    got = gs.gs_node2vec_walk(g, None, _t(starts), 12, 0.5, 2.0, 3)
+    np.testing.assert_array_equal(got.cpu().numpy(), want)
+    assert (want == -1).any()
+
+
+@pytest.mark.parametrize("p,q", [(0.5, 2.0), (4.0, 0.25), (1.0, 1.0)])
+def test_node2vec_walk_workload0(gs, oracle, cfg0, p, q):
+    wl, (off, nb), g = cfg0
+    nw = 20_011
+    starts = _walk_inputs(wl, nw, first=123)
+    want = oracle.node2vec_walk(off, nb, starts.numpy(), 30, p, q, wl.walk_seed, walk_id_base=123)
+    got = gs.gs_node2vec_walk(g, None, starts.to(DEV), 30, p, q, wl.walk_seed, walk_id_base=123)
+    np.testing.assert_array_equal(got.cpu().numpy(), want)
+    if p == 1.0 and q == 1.0:
+        first_order = gs.gs_random_walk(g, None, starts.to(DEV), 30, wl.walk_seed, walk_id_base=123)
+        assert torch.equal(first_order, got)
+
+
+def test_node2vec_walk_weighted(gs, oracle, cfg0):
+    wl, (off, nb), g = cfg0
+    rng = np.random.default_rng(11)
+    w = rng.lognormal(0, 1, nb.size).astype(np.float32)
+    table = oracle.alias_build(off, w)
+    a = gs.gs_alias_build(g.offsets, _t(w))
+    starts = _walk_inputs(wl, 10_000)
+    want = oracle.node2vec_walk(off, nb, starts.numpy(), 25, 0.5, 2.0, 17, alias=table)
+    got = gs.gs_node2vec_walk(g, a, starts.to(DEV), 25, 0.5, 2.0, 17)
+    np.testing.assert_array_equal(got.cpu().numpy(), want)
+
+
+def test_walk_argument_errors(gs, cfg0):
+    wl, _, g = cfg0
+    s = torch.zeros(4, dtype=torch.int32, device=DEV)
+    with pytest.raises(gs.GsError):
+        gs.gs_random_walk(g, None, s, 0, 1)
+    with pytest.raises(gs.GsError):
+        gs.gs_node2vec_walk(g, None, s, 5, 0.0, 1.0, 1)
+    with pytest.raises(gs.GsError):
+        gs.gs_node2vec_walk(g, None, s, 5, 1.0, float("nan"), 1)
+    assert gs.gs_random_walk(g, None, s[:0], 5, 1).shape == (0, 5)
+
+
+# ----------------------------------------------------------------------------- pairs / negatives
+@pytest.mark.parametrize("walk_len,window", [(20, 5), (5, 3), (4, 7), (1, 2), (80, 10), (300, 2)])
+def test_make_pairs(gs, oracle, walk_len, window):
+    rng = np.random.default_rng(walk_len * 31 + window)
+    nw = 1500 if walk_len < 100 else 150
+    walks = rng.integers(0, 10_000, (nw, walk_len)).astype(np.int32)
+    for i in range(0, nw, 3):                  # a third of the walks end early
+        walks[i, rng.integers(0, walk_len + 1):] = -1
+    wc, wo = oracle.make_pairs(walks, window)
+    c, o, n = gs.gs_make_pairs(_t(walks), window)
+    assert n == wc.size
+    np.testing.assert_array_equal(c.cpu().numpy(), wc)
+    np.testing.assert_array_equal(o.cpu().numpy(), wo)
+
+
+def test_make_pairs_empty_and_errors(gs):
+    w = torch.zeros((0, 8), dtype=torch.int32, device=DEV)
+    c, o, n = gs.gs_make_pairs(w, 3)
+    assert n == 0
+    dead = torch.full((5, 8), -1, dtype=torch.int32, device=DEV)
+    assert gs.gs_make_pairs(dead, 3)[2] == 0
+    with pytest.raises(gs.GsError):
+        gs.gs_make_pairs(dead, 0)
+
+
+def test_sample_negatives(gs, oracle, cfg0):
+    wl, (off, nb), g = cfg0
+    from paper_2407_15452_amd import inputs
+    nw = inputs.noise_weights(torch.as_tensor(off)).numpy()
+    seg = np.array([0, wl.num_nodes], dtype=np.int32)
+    table = oracle.alias_build(seg, nw)
+    a = gs.gs_alias_build(_t(seg), _t(nw))
+    want = oracle.sample_negatives(table, wl.num_nodes, 70_001, wl.num_neg, wl.neg_seed,
+                                   pair_index_base=(1 << 35) + 3)
+    got = gs.gs_sample_negatives(a, wl.num_nodes, 70_001, wl.num_neg, wl.neg_seed,
+                                 pair_index_base=(1 << 35) + 3)
+    np.testing.assert_array_equal(got.cpu().numpy(), want)
+    want = oracle.sample_negatives(None, 977, 5000, 3, 5)
+    got = gs.gs_sample_negatives(None, 977, 5000, 3, 5, device=DEV)
+    np.testing.assert_array_equal(got.cpu().numpy(), want)
+
+
+# ----------------------------------------------------------------------------- SGNS
+LOSS_RTOL = 1e-5
+EMB_ATOL = 1e-5
+
+
+def _sgns_case(gs, oracle, w_in, w_out, c, o, neg, lr):
+    d_in, d_out = w_in.to(DEV), w_out.to(DEV)
+    loss = gs.gs_sgns_step(d_in, d_out, _t(c), _t(o), _t(neg), lr)
+    torch.cuda.synchronize()
+    h_in, h_out = w_in.numpy().copy(), w_out.numpy().copy()
+    want = oracle.sgns_step(h_in, h_out, c, o, neg, lr)
+    got = float(loss.item())
+    assert abs(got - want) <= LOSS_RTOL * abs(want) + 1e-12
+    g_in, g_out = d_in.cpu().numpy(), d_out.cpu().numpy()
+    assert np.abs(g_in - h_in).max() <= EMB_ATOL
+    assert np.abs(g_out - h_out).max() <= EMB_ATOL
+    return g_in, g_out
+
+
+@pytest.mark.parametrize("dim,k,b", [(64, 5, 65_536), (128, 5, 50_001), (256, 10, 9_999),
+                                     (100, 3, 7_777), (4, 1, 513), (512, 2, 2_000)])
+def test_sgns_step_mid_training_state(gs, oracle, dim, k, b):
+    from paper_2407_15452_amd import inputs
+    n = 5000
+    w_in, w_out = inputs.random_tables(n, dim, seed=dim + k, scale=2.0 / dim ** 0.5)
+    rng = np.random.default_rng(b)
+    # skip-gram-like structure: runs of equal centres, power-law negatives
+    c = np.repeat(rng.integers(0, n, b // 8 + 1), 8)[:b].astype(np.int32)
+    o = rng.integers(0, n, b).astype(np.int32)
+    neg = (n * rng.random((b, k)) ** 3).astype(np.int32)
+    _sgns_case(gs, oracle, w_in, w_out, c, o, neg, 0.025)
+
+
+def test_sgns_step_from_initial_state_workload0(gs, oracle, cfg0):
+    """First batch of workload 0 from its initial tables (context table zero)."""
+    from paper_2407_15452_amd import inputs
+    wl, (off, nb), g = cfg0
+    w_in, w_out = inputs.init_tables(wl.num_nodes, wl.dim, wl.init_seed)
+    starts = _walk_inputs(wl, 500)
+    walks = oracle.random_walk(off, nb, starts.numpy(), wl.walk_len, wl.walk_seed)
+    c, o = oracle.make_pairs(walks, wl.window)
+    c, o = c[:wl.batch_pairs], o[:wl.batch_pairs]
+    nw = inputs.noise_weights(torch.as_tensor(off)).numpy()
+    table = oracle.alias_build(np.array([0, wl.num_nodes], dtype=np.int32), nw)
+    neg = oracle.sample_negatives(table, wl.num_nodes, c.size, wl.num_neg, wl.neg_seed)
+    g_in, g_out = _sgns_case(gs, oracle, w_in, w_out, c, o, neg, 0.025)
+    np.testing.assert_array_equal(g_in, w_in.numpy())      # closed form: no change at step one
+    # rows the batch does not name are bit-unchanged
+    named = np.zeros(wl.num_nodes, bool)
+    named[o] = True
+    named[neg.ravel()] = True
+    assert (g_out[~named] == 0).all() and named.sum() < wl.num_nodes
+
+
+def test_sgns_step_untouched_rows_and_empty_batch(gs, oracle):
+    from paper_2407_15452_amd import inputs
+    n, dim = 4000, 128
+    w_in, w_out = inputs.random_tables(n, dim, seed=3, scale=0.2)
+    rng = np.random.default_rng(0)
+    b, k = 3000, 5
+    c = rng.integers(0, n // 2, b).astype(np.int32)
+    o = rng.integers(0, n // 2, b).astype(np.int32)
+    neg = rng.integers(0, n // 2, (b, k)).astype(np.int32)
+    g_in, g_out = _sgns_case(gs, oracle, w_in, w_out, c, o, neg, 0.05)
+    np.testing.assert_array_equal(g_in[n // 2:], w_in.numpy()[n // 2:])
+    np.testing.assert_array_equal(g_out[n // 2:], w_out.numpy()[n // 2:])
+    d_in, d_out = w_in.to(DEV), w_out.to(DEV)
+    e = torch.zeros(0, dtype=torch.int32, device=DEV)
+    loss = gs.gs_sgns_step(d_in, d_out, e, e, torch.zeros((0, k), dtype=torch.int32, device=DEV), 0.1)
+    assert float(loss.item()) == 0.0
+    assert torch.equal(d_in.cpu(), w_in) and torch.equal(d_out.cpu(), w_out)
+
+
+def test_sgns_step_argument_errors(gs):
+    w = torch.zeros((10, 6), dtype=torch.float32, device=DEV)
+    i = torch.zeros(4, dtype=torch.int32, device=DEV)
+    n = torch.zeros((4, 2), dtype=torch.int32, device=DEV)
+    with pytest.raises(gs.GsError):            # dim not a multiple of 4
+        gs.gs_sgns_step(w, w.clone(), i, i, n, 0.1)
+    w = torch.zeros((10, 8), dtype=torch.float32, device=DEV)
+    with pytest.raises(gs.GsError) as ei:
+        gs.gs_sgns_step(w, w.clone(), i, i, n, 0.1,
+                        ws=torch.empty(256, dtype=torch.uint8, device=DEV))
+    assert ei.value.status == gs.GS_EWORKSPACE
+
+
+def test_epoch_of_workload0(gs, oracle, cfg0):
+    """Whole pipeline on workload 0, one epoch, both sides from the same inputs."""
+    from paper_2407_15452_amd import inputs
+    wl, (off, nb), g = cfg0
+    nw = wl.num_nodes * wl.walks_per_node
+    starts = _walk_inputs(wl, nw)
+    noise_w = inputs.noise_weights(torch.as_tensor(off))
+    seg = np.array([0, wl.num_nodes], dtype=np.int32)
+    # --- oracle side
+    walks = oracle.random_walk(off, nb, starts.numpy(), wl.walk_len, wl.walk_seed)
+    oc, oo = oracle.make_pairs(walks, wl.window)
+    table = oracle.alias_build(seg, noise_w.numpy())
+    oneg = oracle.sample_negatives(table, wl.num_nodes, oc.size, wl.num_neg, wl.neg_seed)
+    # --- device side
+    d_walks = gs.gs_random_walk(g, None, starts.to(DEV), wl.walk_len, wl.walk_seed)
+    dc, do, n_pairs = gs.gs_make_pairs(d_walks, wl.window)
+    noise = gs.gs_alias_build(_t(seg), noise_w.to(DEV))
+    dneg = gs.gs_sample_negatives(noise, wl.num_nodes, n_pairs, wl.num_neg, wl.neg_seed)
+    assert n_pairs == oc.size
+    np.testing.assert_array_equal(dc.cpu().numpy(), oc)
+    np.testing.assert_array_equal(do.cpu().numpy(), oo)
+    np.testing.assert_array_equal(dneg.cpu().numpy(), oneg)
+
+    w_in, w_out = inputs.init_tables(wl.num_nodes, wl.dim, wl.init_seed)
+    h_in, h_out = w_in.numpy().copy(), w_out.numpy().copy()
+    d_in, d_out = w_in.to(DEV), w_out.to(DEV)
+    bsz = wl.batch_pairs
+    nb_batches = (n_pairs + bsz - 1) // bsz
+    assert nb_batches == 80          # 30,776 live walks x 170 pairs / 65,536
+    ws = torch.empty(gs.gs_sgns_step_workspace_bytes(bsz, wl.num_neg, wl.dim), dtype=torch.uint8,
+                     device=DEV)
+    losses = torch.zeros(nb_batches, dtype=torch.float64, device=DEV)
+    o_loss = 0.0
+    for b in range(nb_batches):
+        lo, hi = b * bsz, min(n_pairs, (b + 1) * bsz)
+        lr = inputs.learning_rate(wl, b, nb_batches)
+        gs.gs_sgns_step(d_in, d_out, dc[lo:hi], do[lo:hi], dneg[lo:hi], lr,
+                        loss_out=losses[b:b + 1], ws=ws)
+        o_loss += oracle.sgns_step(h_in, h_out, oc[lo:hi], oo[lo:hi], oneg[lo:hi], lr)
+    torch.cuda.synchronize()
+    d_loss = float(losses.sum().item())
+    assert abs(d_loss - o_loss) / abs(o_loss) <= 1e-3
+    for got, want in ((d_in.cpu().numpy(), h_in), (d_out.cpu().numpy(), h_out)):
+        na, nb_ = np.linalg.norm(got, axis=1), np.linalg.norm(want, axis=1)
+        live = (na > 0) | (nb_ > 0)
+        cos = (got[live] * want[live]).sum(1) / np.maximum(na[live] * nb_[live], 1e-30)
+        assert cos.mean() >= 0.999

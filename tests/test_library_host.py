@@ -1,0 +1,67 @@
+"""CPU-side checks of the HIP library: it loads, exports every symbol declared
+in include/gs.h, and its host-only functions (workspace sizing) behave.  No
+kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2407_15452_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build_lib()
+    return binding.lib()
+
+
+def test_header_symbols_are_exported(lib):
+    from paper_2407_15452_amd import binding
+    header = open(os.path.join(ROOT, "include", "gs.h")).read()
+    declared = set(re.findall(r"\b(gs_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_workspace_queries(lib):
+    assert lib.gs_sgns_step_workspace_bytes(C.c_int64(0), C.c_int32(5), C.c_int32(128), C.c_int32(0)) > 0
+    small = lib.gs_sgns_step_workspace_bytes(C.c_int64(1000), C.c_int32(5), C.c_int32(128), C.c_int32(0))
+    big = lib.gs_sgns_step_workspace_bytes(C.c_int64(2000), C.c_int32(5), C.c_int32(128), C.c_int32(0))
+    assert 0 < small < big and small % 256 == 0
+    assert lib.gs_csr_build_workspace_bytes(C.c_int64(1000), C.c_int64(10), C.c_uint32(1)) > \
+        lib.gs_csr_build_workspace_bytes(C.c_int64(1000), C.c_int64(10), C.c_uint32(0))
+    assert lib.gs_make_pairs_workspace_bytes(C.c_int64(10)) >= 256
+    assert lib.gs_alias_build_workspace_bytes(C.c_int64(3), C.c_int64(100)) >= 16 * 100
+    assert lib.gs_last_hip_error() == 0
+
+
+def test_missing_library_is_an_error(monkeypatch):
+    from paper_2407_15452_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libgs.so")
+    with pytest.raises(RuntimeError):
+        binding.lib()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+def test_inputs_are_deterministic():
+    import torch
+    from paper_2407_15452_amd import inputs
+    wl = inputs.WORKLOADS[0]
+    a = inputs.edge_list(wl)
+    b = inputs.edge_list(wl)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and a[0].numel() == wl.num_edges
+    assert inputs.pairs_per_full_walk(20, 5) == 170 and inputs.pairs_per_full_walk(80, 10) == 1490
+    w_in, w_out = inputs.init_tables(100, 64, 5)
+    assert float(w_in.abs().max()) <= 0.5 / 64 and float(w_out.abs().max()) == 0
