@@ -128,7 +128,7 @@ def main():
     pairs_ws = torch.empty(max(256, gs.lib().gs_make_pairs_workspace_bytes(n_max)),
                            dtype=torch.uint8, device=dev)
     negs = torch.empty((B, k), dtype=torch.int32, device=dev)
-    sgns_ws = torch.empty(gs.gs_sgns_step_workspace_bytes(B, k, wl.dim), dtype=torch.uint8,
+    sgns_ws = torch.empty(gs.gs_sgns_step_workspace_bytes(B, wl.num_nodes, k, wl.dim), dtype=torch.uint8,
                           device=dev)
     losses = torch.zeros(total_steps, dtype=torch.float64, device=dev)
     lr = inputs.learning_rate(wl, 0, 1)

@@ -183,10 +183,13 @@ int32_t gs_sample_negatives(const gs_alias* noise, int64_t num_nodes, int64_t nu
  *   w_in[c] -= lr * sum g_j v_j;  w_out[row_j] -= lr * g_j u, summed over all
  *   occurrences in the batch.  loss_sum_out double[1] on the device receives
  *   the sum of loss_i (overwritten).
- *   dim must be a multiple of 4 and at most 1024.  Rows that the batch does
- *   not name are not touched.
+ *   dim must be a multiple of 4 and at most 1024; num_pairs * (k+1) < 2^31.
+ *   Rows that the batch does not name are not touched.  The workspace holds
+ *   the per-term coefficients, the terms regrouped by destination row, a
+ *   counter per node and the staged centre-row gradients.
  * ------------------------------------------------------------------------ */
-size_t gs_sgns_step_workspace_bytes(int64_t num_pairs, int32_t k, int32_t dim, int32_t dtype);
+size_t gs_sgns_step_workspace_bytes(int64_t num_pairs, int64_t num_nodes, int32_t k, int32_t dim,
+                                    int32_t dtype);
 int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int32_t dim, int32_t dtype,
                      const int32_t* centers, const int32_t* contexts, const int32_t* negs,
                      int64_t num_pairs, int32_t k, float lr, double* loss_sum_out,

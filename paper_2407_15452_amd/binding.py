@@ -231,9 +231,10 @@ def gs_sample_negatives(noise, num_nodes: int, num_pairs: int, k: int, seed: int
     return out
 
 
-def gs_sgns_step_workspace_bytes(num_pairs: int, k: int, dim: int, dtype: int = GS_F32) -> int:
-    return int(lib().gs_sgns_step_workspace_bytes(C.c_int64(num_pairs), C.c_int32(k),
-                                                  C.c_int32(dim), C.c_int32(dtype)))
+def gs_sgns_step_workspace_bytes(num_pairs: int, num_nodes: int, k: int, dim: int,
+                                 dtype: int = GS_F32) -> int:
+    return int(lib().gs_sgns_step_workspace_bytes(C.c_int64(num_pairs), C.c_int64(num_nodes),
+                                                  C.c_int32(k), C.c_int32(dim), C.c_int32(dtype)))
 
 
 def gs_sgns_step(w_in, w_out, centers, contexts, negs, lr: float, loss_out=None, ws=None):
@@ -246,7 +247,7 @@ def gs_sgns_step(w_in, w_out, centers, contexts, negs, lr: float, loss_out=None,
     if loss_out is None:
         loss_out = torch.zeros(1, dtype=torch.float64, device=dev)
     if ws is None:
-        ws = _workspace(gs_sgns_step_workspace_bytes(num_pairs, k, dim, dtype), dev)
+        ws = _workspace(gs_sgns_step_workspace_bytes(num_pairs, num_nodes, k, dim, dtype), dev)
     rc = lib().gs_sgns_step(_dev(w_in, None, "w_in"), _dev(w_out, w_in.dtype, "w_out"),
                             C.c_int64(num_nodes), C.c_int32(dim), C.c_int32(dtype),
                             _dev(centers, torch.int32, "centers"),

@@ -3,12 +3,25 @@
 // the barrier of "Synchronization": all reads see the pre-iteration tables).
 //
 // The batch-synchronous rule is kept by splitting the iteration at kernel
-// boundaries:
-//   forward   read-only on both tables: logits, g = dLoss/dx, loss, and the
-//             centre-row gradients staged per run of equal centres;
-//   scatter   w_out[row] += -lr * g * u   (atomic, reads the unmodified w_in);
-//   apply     w_in[centre] += -lr * staged gradient (atomic);
-//   finish    deterministic sum of the per-block loss partials.
+// boundaries, and the scatter into the context table is done without one
+// atomic per element: float atomics run at ~1/5 of the plain read-modify-write
+// rate on this chip, so the (pair, j) terms are grouped by destination row
+// first and each row is written once.
+//
+//   clear     cnt[0..N] = 0
+//   forward   read-only on both tables: logits, g = dLoss/dx, loss, the
+//             centre-row gradients staged per run of equal centres, and
+//             rank[e] = cnt[row_e]++ (position of term e among the terms of
+//             its destination row)
+//   scan      off = exclusive prefix sum of cnt
+//   place     sorted[off[row_e] + rank[e]] = (row_e, centre_e, -lr * g_e)
+//   update    per destination row: w_out[row] += sum coef * w_in[centre]
+//             (w_in is still unmodified); one plain read-modify-write per row;
+//             rows with more than kLongRow terms are cut into slices whose
+//             partial sums are added atomically
+//   apply     w_in[centre] += -lr * staged gradient (atomic, few rows)
+//   finish    deterministic sum of the per-block loss partials
+//
 // A row is handled by 16 lanes holding float4 pieces (256 contiguous bytes per
 // load instruction); a wave works on four rows at once and a dot product is a
 // 16-lane DPP reduction.  No matrix cores: 0.3 flop per byte moved.
@@ -19,8 +32,19 @@ namespace gs {
 constexpr int kSgnsThreads = 256;
 constexpr int kGroupLanes = 16;
 constexpr int kGroupsPerBlock = kSgnsThreads / kGroupLanes;
-constexpr int kChunkPairs = 16;   // consecutive pairs per 16-lane group
-constexpr int kRowBatch = 3;      // rows whose loads are issued together
+constexpr int kChunkPairs = 16;    // consecutive pairs per 16-lane group in forward
+constexpr int kSlice = 128;        // sorted terms per 16-lane group in update
+constexpr uint32_t kLongRow = 256; // rows with more terms than this are updated slice by slice
+constexpr int kScanThreads = 256;
+constexpr int kScanPerThread = 16;
+constexpr int kScanTile = kScanThreads * kScanPerThread;
+
+struct Term {      // one (pair, j) contribution to a context-table row
+  int32_t row;
+  int32_t center;
+  float coef;      // -lr * g
+  int32_t pad;
+};
 
 struct SgnsArgs {
   float* w_in;
@@ -29,10 +53,16 @@ struct SgnsArgs {
   const int32_t* contexts;
   const int32_t* negs;
   int64_t num_pairs;
+  int64_t num_nodes;
+  int64_t num_terms;        // num_pairs * (k + 1)
   int32_t k;
   int32_t dim;
   float lr;
-  float* g;                 // [num_pairs][k+1]
+  float* g;                 // [num_terms]
+  uint32_t* rank;           // [num_terms]
+  uint32_t* cnt;            // [num_nodes + 1]; after scan: offsets
+  uint32_t* tile_sums;      // scan scratch
+  Term* sorted;             // [num_terms]
   unsigned long long* slot_counter;
   int32_t* stage_center;    // [<= num_pairs]
   float* stage_delta;       // [<= num_pairs][dim]
@@ -71,9 +101,31 @@ __device__ __forceinline__ float dot_partial(const float4 (&a)[VPL], const float
   return s;
 }
 
+template <int VPL>
+__device__ __forceinline__ void axpy(float4 (&acc)[VPL], float c, const float4 (&x)[VPL]) {
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    acc[v].x += c * x[v].x; acc[v].y += c * x[v].y;
+    acc[v].z += c * x[v].z; acc[v].w += c * x[v].w;
+  }
+}
+
+template <int VPL>
+__device__ __forceinline__ void zero(float4 (&a)[VPL]) {
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) a[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
 __device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + expf(-x)); }
 __device__ __forceinline__ float softplusf_(float z) {
   return fmaxf(z, 0.0f) + log1pf(expf(-fabsf(z)));
+}
+
+__global__ void sgns_clear_kernel(uint32_t* __restrict__ cnt, int64_t n,
+                                  unsigned long long* slot_counter) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) cnt[i] = 0u;
+  if (i == 0) *slot_counter = 0ull;
 }
 
 template <int VPL>
@@ -92,7 +144,7 @@ __device__ __forceinline__ void stage_flush(const SgnsArgs& a, int32_t center, i
   }
 }
 
-template <int VPL>
+template <int VPL, int RB>
 __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) {
   __shared__ float loss_s[kGroupsPerBlock];
   const int l16 = threadIdx.x & (kGroupLanes - 1);
@@ -103,8 +155,8 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
   const int K = a.k;
 
   float4 u[VPL], du[VPL];
-#pragma unroll
-  for (int v = 0; v < VPL; ++v) { u[v] = make_float4(0.f, 0.f, 0.f, 0.f); du[v] = u[v]; }
+  zero<VPL>(u);
+  zero<VPL>(du);
   int32_t cur_c = -1;
   float loss = 0.f;
 
@@ -113,34 +165,34 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
     if (c != cur_c) {
       if (cur_c >= 0) stage_flush<VPL>(a, cur_c, l16, du);
       load_row<VPL>(a.w_in, c, a.dim, l16, u);
-#pragma unroll
-      for (int v = 0; v < VPL; ++v) du[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+      zero<VPL>(du);
       cur_c = c;
     }
-    for (int j0 = 0; j0 <= K; j0 += kRowBatch) {
-      float4 vv[kRowBatch][VPL];
+    const int64_t e0 = i * (int64_t)(K + 1);
+    for (int j0 = 0; j0 <= K; j0 += RB) {
+      float4 vv[RB][VPL];
+      int32_t rows[RB];
 #pragma unroll
-      for (int b = 0; b < kRowBatch; ++b) {
+      for (int b = 0; b < RB; ++b) {
         const int j = j0 + b;
         if (j <= K) {
-          const int32_t row = (j == 0) ? a.contexts[i] : a.negs[i * (int64_t)K + (j - 1)];
-          load_row<VPL>(a.w_out, row, a.dim, l16, vv[b]);
+          rows[b] = (j == 0) ? a.contexts[i] : a.negs[i * (int64_t)K + (j - 1)];
+          load_row<VPL>(a.w_out, rows[b], a.dim, l16, vv[b]);
         }
       }
 #pragma unroll
-      for (int b = 0; b < kRowBatch; ++b) {
+      for (int b = 0; b < RB; ++b) {
         const int j = j0 + b;
         if (j <= K) {
+          // position of this term among the terms of its destination row
+          uint32_t rk = 0;
+          if (l16 == 0) rk = atomicAdd(a.cnt + rows[b], 1u);
           const float x = row_sum16(dot_partial<VPL>(u, vv[b]));
           float gj;
           if (j == 0) { gj = sigmoidf_(x) - 1.0f; loss += softplusf_(-x); }
           else        { gj = sigmoidf_(x);        loss += softplusf_(x); }
-#pragma unroll
-          for (int v = 0; v < VPL; ++v) {
-            du[v].x += gj * vv[b][v].x; du[v].y += gj * vv[b][v].y;
-            du[v].z += gj * vv[b][v].z; du[v].w += gj * vv[b][v].w;
-          }
-          if (l16 == 0) a.g[i * (int64_t)(K + 1) + j] = gj;
+          axpy<VPL>(du, gj, vv[b]);
+          if (l16 == 0) { a.g[e0 + j] = gj; a.rank[e0 + j] = rk; }
         }
       }
     }
@@ -157,65 +209,204 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
   }
 }
 
+// ---- exclusive scan of cnt[0..n) (uint32), three kernels ---------------------
+__global__ __launch_bounds__(kScanThreads) void scan_reduce_kernel(const uint32_t* __restrict__ data,
+                                                                   int64_t n,
+                                                                   uint32_t* __restrict__ tile_sums) {
+  __shared__ uint32_t s[kScanThreads / 64];
+  const int64_t base = (int64_t)blockIdx.x * kScanTile;
+  uint32_t acc = 0;
+#pragma unroll
+  for (int k = 0; k < kScanPerThread; ++k) {
+    const int64_t i = base + (int64_t)k * kScanThreads + threadIdx.x;
+    if (i < n) acc += data[i];
+  }
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) acc += __shfl_xor(acc, d, 64);
+  if ((threadIdx.x & 63) == 0) s[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t t = 0;
+#pragma unroll
+    for (int w = 0; w < kScanThreads / 64; ++w) t += s[w];
+    tile_sums[blockIdx.x] = t;
+  }
+}
+
+// single block: exclusive scan of the tile sums in place
+__global__ __launch_bounds__(1024) void scan_tiles_kernel(uint32_t* __restrict__ tile_sums,
+                                                          int64_t tiles) {
+  __shared__ uint32_t wave_tot[16];
+  __shared__ uint32_t carry_s;
+  if (threadIdx.x == 0) carry_s = 0;
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int64_t base = 0; base < tiles; base += 1024) {
+    const int64_t i = base + threadIdx.x;
+    const uint32_t v = (i < tiles) ? tile_sums[i] : 0u;
+    uint32_t incl = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t up = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += up;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    uint32_t before = carry_s, all = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+      if (w < wave) before += wave_tot[w];
+      all += wave_tot[w];
+    }
+    if (i < tiles) tile_sums[i] = before + incl - v;
+    __syncthreads();
+    if (threadIdx.x == 0) carry_s += all;
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(uint32_t* __restrict__ data, int64_t n,
+                                                                  const uint32_t* __restrict__ tile_offsets) {
+  __shared__ uint32_t wave_tot[kScanThreads / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // thread t owns kScanPerThread consecutive values
+  const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanPerThread;
+  uint32_t v[kScanPerThread];
+  uint32_t local = 0;
+#pragma unroll
+  for (int k = 0; k < kScanPerThread; ++k) {
+    v[k] = (base + k < n) ? data[base + k] : 0u;
+    local += v[k];
+  }
+  uint32_t incl = local;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t up = __shfl_up(incl, d, 64);
+    if (lane >= d) incl += up;
+  }
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  uint32_t run = tile_offsets[blockIdx.x] + incl - local;
+#pragma unroll
+  for (int w = 0; w < kScanThreads / 64; ++w)
+    if (w < wave) run += wave_tot[w];
+#pragma unroll
+  for (int k = 0; k < kScanPerThread; ++k) {
+    if (base + k < n) data[base + k] = run;
+    run += v[k];
+  }
+}
+
+// ---- place: scatter the terms into row-major order -----------------------------
+__global__ __launch_bounds__(256) void sgns_place_kernel(SgnsArgs a) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= a.num_terms) return;
+  const int K1 = a.k + 1;
+  const int64_t i = e / K1;
+  const int j = (int)(e - i * K1);
+  const int32_t row = (j == 0) ? a.contexts[i] : a.negs[i * (int64_t)a.k + (j - 1)];
+  const uint32_t pos = a.cnt[row] + a.rank[e];
+  Term t;
+  t.row = row;
+  t.center = a.centers[i];
+  t.coef = -a.lr * a.g[e];
+  t.pad = 0;
+  a.sorted[pos] = t;
+}
+
+// ---- update: one pass over the row-major terms ------------------------------------
 template <int VPL>
-__global__ __launch_bounds__(kSgnsThreads) void sgns_scatter_kernel(SgnsArgs a) {
-  const int l16 = threadIdx.x & (kGroupLanes - 1);
-  const int64_t group = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
-  const int64_t first = group * kChunkPairs;
-  const int64_t last = min(first + kChunkPairs, a.num_pairs);
-  const int K = a.k;
-  const int dim4 = a.dim >> 2;
-  float4 u[VPL];
+__device__ __forceinline__ void row_add_plain(float* __restrict__ table, int64_t row, int dim, int l16,
+                                              const float4 (&acc)[VPL]) {
+  float4* p = reinterpret_cast<float4*>(table + row * (int64_t)dim);
+  const int dim4 = dim >> 2;
 #pragma unroll
-  for (int v = 0; v < VPL; ++v) u[v] = make_float4(0.f, 0.f, 0.f, 0.f);
-  int32_t cur_c = -1;
-  for (int64_t i = first; i < last; ++i) {
-    const int32_t c = a.centers[i];
-    if (c != cur_c) { load_row<VPL>(a.w_in, c, a.dim, l16, u); cur_c = c; }
-    for (int j = 0; j <= K; ++j) {
-      const int32_t row = (j == 0) ? a.contexts[i] : a.negs[i * (int64_t)K + (j - 1)];
-      const float coef = -a.lr * a.g[i * (int64_t)(K + 1) + j];
-      float* dst = a.w_out + row * (int64_t)a.dim;
-#pragma unroll
-      for (int v = 0; v < VPL; ++v) {
-        const int q = v * kGroupLanes + l16;
-        if (q < dim4) {
-          unsafeAtomicAdd(dst + 4 * q + 0, coef * u[v].x);
-          unsafeAtomicAdd(dst + 4 * q + 1, coef * u[v].y);
-          unsafeAtomicAdd(dst + 4 * q + 2, coef * u[v].z);
-          unsafeAtomicAdd(dst + 4 * q + 3, coef * u[v].w);
-        }
-      }
+  for (int v = 0; v < VPL; ++v) {
+    const int q = v * kGroupLanes + l16;
+    if (q < dim4) {
+      float4 x = p[q];
+      x.x += acc[v].x; x.y += acc[v].y; x.z += acc[v].z; x.w += acc[v].w;
+      p[q] = x;
     }
   }
 }
 
 template <int VPL>
+__device__ __forceinline__ void row_add_atomic(float* __restrict__ table, int64_t row, int dim, int l16,
+                                               const float4 (&acc)[VPL]) {
+  float* dst = table + row * (int64_t)dim;
+  const int dim4 = dim >> 2;
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    const int q = v * kGroupLanes + l16;
+    if (q < dim4) {
+      unsafeAtomicAdd(dst + 4 * q + 0, acc[v].x);
+      unsafeAtomicAdd(dst + 4 * q + 1, acc[v].y);
+      unsafeAtomicAdd(dst + 4 * q + 2, acc[v].z);
+      unsafeAtomicAdd(dst + 4 * q + 3, acc[v].w);
+    }
+  }
+}
+
+template <int VPL, int UB>
+__global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
+  const int l16 = threadIdx.x & (kGroupLanes - 1);
+  const int64_t group = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
+  const int64_t slice_begin = group * kSlice;
+  if (slice_begin >= a.num_terms) return;
+  const int64_t slice_end = min(slice_begin + kSlice, a.num_terms);
+  const Term* __restrict__ sorted = a.sorted;
+  const uint32_t* __restrict__ off = a.cnt;
+
+  int64_t p = slice_begin;
+  {
+    // a short row that began in an earlier slice belongs to that slice's group
+    const int32_t row = sorted[p].row;
+    const int64_t begin = off[row], end = off[row + 1];
+    if (begin < slice_begin && (end - begin) <= (int64_t)kLongRow) p = end;
+  }
+  while (p < slice_end) {
+    const int32_t row = sorted[p].row;
+    const int64_t begin = off[row], end = off[row + 1];
+    const bool is_long = (end - begin) > (int64_t)kLongRow;
+    const int64_t stop = is_long ? min(end, slice_end) : end;
+    float4 acc[VPL];
+    zero<VPL>(acc);
+    for (int64_t q = p; q < stop; q += UB) {
+      Term t[UB];
+      float4 u[UB][VPL];
+#pragma unroll
+      for (int b = 0; b < UB; ++b) {
+        if (q + b < stop) {
+          t[b] = sorted[q + b];
+          load_row<VPL>(a.w_in, t[b].center, a.dim, l16, u[b]);
+        }
+      }
+#pragma unroll
+      for (int b = 0; b < UB; ++b)
+        if (q + b < stop) axpy<VPL>(acc, t[b].coef, u[b]);
+    }
+    if (is_long) row_add_atomic<VPL>(a.w_out, row, a.dim, l16, acc);
+    else row_add_plain<VPL>(a.w_out, row, a.dim, l16, acc);
+    p = stop;
+  }
+}
+
+// ---- apply: staged centre-row gradients into w_in ----------------------------------
+// Lane l of a group owns elements l, l+16, ...: each atomic instruction of a
+// group covers 64 contiguous bytes (one request to the L2 instead of four).
 __global__ __launch_bounds__(kSgnsThreads) void sgns_apply_kernel(SgnsArgs a) {
   const int l16 = threadIdx.x & (kGroupLanes - 1);
   const int64_t group = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
   const int64_t stride = (int64_t)gridDim.x * kGroupsPerBlock;
   const int64_t slots = (int64_t)*a.slot_counter;
-  const int dim4 = a.dim >> 2;
   for (int64_t s = group; s < slots; s += stride) {
     const int32_t c = a.stage_center[s];
-    const float4* src = reinterpret_cast<const float4*>(a.stage_delta + s * (int64_t)a.dim);
+    const float* src = a.stage_delta + s * (int64_t)a.dim;
     float* dst = a.w_in + c * (int64_t)a.dim;
-#pragma unroll
-    for (int v = 0; v < VPL; ++v) {
-      const int q = v * kGroupLanes + l16;
-      if (q < dim4) {
-        const float4 d = src[q];
-        unsafeAtomicAdd(dst + 4 * q + 0, -a.lr * d.x);
-        unsafeAtomicAdd(dst + 4 * q + 1, -a.lr * d.y);
-        unsafeAtomicAdd(dst + 4 * q + 2, -a.lr * d.z);
-        unsafeAtomicAdd(dst + 4 * q + 3, -a.lr * d.w);
-      }
-    }
+    for (int e = l16; e < a.dim; e += kGroupLanes) unsafeAtomicAdd(dst + e, -a.lr * src[e]);
   }
 }
-
-__global__ void sgns_init_kernel(unsigned long long* slot_counter) { *slot_counter = 0ull; }
 
 __global__ __launch_bounds__(256) void sgns_finish_kernel(const double* __restrict__ partials,
                                                           int64_t count, double* __restrict__ out) {
@@ -239,35 +430,57 @@ struct SgnsPlan {
   unsigned long long* slot_counter;
   double* loss_partials;
   float* g;
+  uint32_t* rank;
+  uint32_t* cnt;
+  uint32_t* tile_sums;
+  Term* sorted;
   int32_t* stage_center;
   float* stage_delta;
   size_t bytes;
 };
 
-static SgnsPlan plan_sgns(void* ws, int64_t num_pairs, int32_t k, int32_t dim) {
+static SgnsPlan plan_sgns(void* ws, int64_t num_pairs, int64_t num_nodes, int32_t k, int32_t dim) {
   Carver cv(ws);
   SgnsPlan p;
   const size_t b = (size_t)(num_pairs > 0 ? num_pairs : 1);
+  const size_t terms = b * (size_t)(k + 1);
+  const size_t n1 = (size_t)(num_nodes > 0 ? num_nodes : 1) + 1;
   p.slot_counter = cv.take<unsigned long long>(1);
   p.loss_partials = cv.take<double>((size_t)forward_blocks_for((int64_t)b));
-  p.g = cv.take<float>(b * (size_t)(k + 1));
+  p.g = cv.take<float>(terms);
+  p.rank = cv.take<uint32_t>(terms);
+  p.cnt = cv.take<uint32_t>(n1);
+  p.tile_sums = cv.take<uint32_t>((size_t)ceil_div((int64_t)n1, kScanTile));
+  p.sorted = cv.take<Term>(terms);
   p.stage_center = cv.take<int32_t>(b);
   p.stage_delta = cv.take<float>(b * (size_t)dim);
   p.bytes = cv.used;
   return p;
 }
 
-template <int VPL>
+template <int VPL, int RB, int UB>
 static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
+  const int64_t n1 = a.num_nodes + 1;
+  const int64_t tiles = ceil_div(n1, kScanTile);
+  sgns_clear_kernel<<<(unsigned)ceil_div(n1, 256), 256, 0, stream>>>(a.cnt, n1, a.slot_counter);
+  GS_LAUNCH_CHECK();
   const unsigned blocks = (unsigned)a.forward_blocks;
-  sgns_init_kernel<<<1, 1, 0, stream>>>(a.slot_counter);
+  sgns_forward_kernel<VPL, RB><<<blocks, kSgnsThreads, 0, stream>>>(a);
   GS_LAUNCH_CHECK();
-  sgns_forward_kernel<VPL><<<blocks, kSgnsThreads, 0, stream>>>(a);
+  scan_reduce_kernel<<<(unsigned)tiles, kScanThreads, 0, stream>>>(a.cnt, n1, a.tile_sums);
   GS_LAUNCH_CHECK();
-  sgns_scatter_kernel<VPL><<<blocks, kSgnsThreads, 0, stream>>>(a);
+  scan_tiles_kernel<<<1, 1024, 0, stream>>>(a.tile_sums, tiles);
   GS_LAUNCH_CHECK();
-  const unsigned apply_blocks = blocks < 2048u ? blocks : 2048u;
-  sgns_apply_kernel<VPL><<<apply_blocks, kSgnsThreads, 0, stream>>>(a);
+  scan_apply_kernel<<<(unsigned)tiles, kScanThreads, 0, stream>>>(a.cnt, n1, a.tile_sums);
+  GS_LAUNCH_CHECK();
+  sgns_place_kernel<<<(unsigned)ceil_div(a.num_terms, 256), 256, 0, stream>>>(a);
+  GS_LAUNCH_CHECK();
+  const int64_t update_groups = ceil_div(a.num_terms, kSlice);
+  sgns_update_kernel<VPL, UB><<<(unsigned)ceil_div(update_groups, kGroupsPerBlock), kSgnsThreads, 0,
+                            stream>>>(a);
+  GS_LAUNCH_CHECK();
+  const unsigned apply_blocks = blocks < 4096u ? blocks : 4096u;
+  sgns_apply_kernel<<<apply_blocks, kSgnsThreads, 0, stream>>>(a);
   GS_LAUNCH_CHECK();
   sgns_finish_kernel<<<1, 256, 0, stream>>>(a.loss_partials, a.forward_blocks, a.loss_out);
   GS_LAUNCH_CHECK();
@@ -280,11 +493,11 @@ __global__ void zero_double_kernel(double* p) { *p = 0.0; }
 
 using namespace gs;
 
-extern "C" size_t gs_sgns_step_workspace_bytes(int64_t num_pairs, int32_t k, int32_t dim,
-                                               int32_t dtype) {
+extern "C" size_t gs_sgns_step_workspace_bytes(int64_t num_pairs, int64_t num_nodes, int32_t k,
+                                               int32_t dim, int32_t dtype) {
   (void)dtype;
-  if (num_pairs < 0 || k < 0 || dim < 1) return 0;
-  return plan_sgns(nullptr, num_pairs, k, dim).bytes;
+  if (num_pairs < 0 || num_nodes < 0 || k < 0 || dim < 1) return 0;
+  return plan_sgns(nullptr, num_pairs, num_nodes, k, dim).bytes;
 }
 
 extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int32_t dim,
@@ -297,9 +510,10 @@ extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int3
   if (dtype != GS_F32) return GS_EINVAL;   // bf16 tables: not built yet
   if (num_pairs < 0 || k < 0 || !loss_sum_out) return GS_EINVAL;
   if (num_pairs > 0 && (!centers || !contexts || (k > 0 && !negs))) return GS_EINVAL;
+  if (num_pairs * (int64_t)(k + 1) > (int64_t)0x7fffffff) return GS_EOVERFLOW;
   if (!aligned(w_in, 16) || !aligned(w_out, 16)) return GS_EINVAL;
   if (!ws || !aligned(ws, 256)) return GS_EINVAL;
-  SgnsPlan p = plan_sgns(ws, num_pairs, k, dim);
+  SgnsPlan p = plan_sgns(ws, num_pairs, num_nodes, k, dim);
   if (ws_bytes < p.bytes) return GS_EWORKSPACE;
   if (num_pairs == 0) {
     zero_double_kernel<<<1, 1, 0, stream>>>(loss_sum_out);
@@ -313,10 +527,16 @@ extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int3
   a.contexts = contexts;
   a.negs = negs;
   a.num_pairs = num_pairs;
+  a.num_nodes = num_nodes;
+  a.num_terms = num_pairs * (int64_t)(k + 1);
   a.k = k;
   a.dim = dim;
   a.lr = lr;
   a.g = p.g;
+  a.rank = p.rank;
+  a.cnt = p.cnt;
+  a.tile_sums = p.tile_sums;
+  a.sorted = p.sorted;
   a.slot_counter = p.slot_counter;
   a.stage_center = p.stage_center;
   a.stage_delta = p.stage_delta;
@@ -324,9 +544,9 @@ extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int3
   a.forward_blocks = forward_blocks_for(num_pairs);
   a.loss_out = loss_sum_out;
   const int vpl = (dim + 63) / 64;
-  if (vpl <= 1) return launch_sgns<1>(a, stream);
-  if (vpl <= 2) return launch_sgns<2>(a, stream);
-  if (vpl <= 4) return launch_sgns<4>(a, stream);
-  if (vpl <= 8) return launch_sgns<8>(a, stream);
-  return launch_sgns<16>(a, stream);
+  if (vpl <= 1) return launch_sgns<1, 6, 4>(a, stream);
+  if (vpl <= 2) return launch_sgns<2, 6, 4>(a, stream);
+  if (vpl <= 4) return launch_sgns<4, 3, 2>(a, stream);
+  if (vpl <= 8) return launch_sgns<8, 2, 1>(a, stream);
+  return launch_sgns<16, 1, 1>(a, stream);
 }

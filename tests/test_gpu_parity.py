@@ -351,7 +351,7 @@ def test_epoch_of_workload0(gs, oracle, cfg0):
     bsz = wl.batch_pairs
     nb_batches = (n_pairs + bsz - 1) // bsz
     assert nb_batches == 80          # 30,776 live walks x 170 pairs / 65,536
-    ws = torch.empty(gs.gs_sgns_step_workspace_bytes(bsz, wl.num_neg, wl.dim), dtype=torch.uint8,
+    ws = torch.empty(gs.gs_sgns_step_workspace_bytes(bsz, wl.num_nodes, wl.num_neg, wl.dim), dtype=torch.uint8,
                      device=DEV)
     losses = torch.zeros(nb_batches, dtype=torch.float64, device=DEV)
     o_loss = 0.0

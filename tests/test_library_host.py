@@ -28,9 +28,9 @@ def test_header_symbols_are_exported(lib):
 
 
 def test_workspace_queries(lib):
-    assert lib.gs_sgns_step_workspace_bytes(C.c_int64(0), C.c_int32(5), C.c_int32(128), C.c_int32(0)) > 0
-    small = lib.gs_sgns_step_workspace_bytes(C.c_int64(1000), C.c_int32(5), C.c_int32(128), C.c_int32(0))
-    big = lib.gs_sgns_step_workspace_bytes(C.c_int64(2000), C.c_int32(5), C.c_int32(128), C.c_int32(0))
+    assert lib.gs_sgns_step_workspace_bytes(C.c_int64(0), C.c_int64(10), C.c_int32(5), C.c_int32(128), C.c_int32(0)) > 0
+    small = lib.gs_sgns_step_workspace_bytes(C.c_int64(1000), C.c_int64(10), C.c_int32(5), C.c_int32(128), C.c_int32(0))
+    big = lib.gs_sgns_step_workspace_bytes(C.c_int64(2000), C.c_int64(10), C.c_int32(5), C.c_int32(128), C.c_int32(0))
     assert 0 < small < big and small % 256 == 0
     assert lib.gs_csr_build_workspace_bytes(C.c_int64(1000), C.c_int64(10), C.c_uint32(1)) > \
         lib.gs_csr_build_workspace_bytes(C.c_int64(1000), C.c_int64(10), C.c_uint32(0))
