@@ -46,6 +46,8 @@ def parse():
     ap.add_argument("--workload", type=int, default=2)
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for HBM byte counters)")
     ap.add_argument("--walk-sample", type=int, default=4_000_000,
                     help="walks in the stand-alone walk-throughput launch")
     return ap.parse_args()
@@ -159,6 +161,13 @@ def main():
                 sgns_events[s][1].record()
         return n_pairs
 
+    if args.calibration_copy:
+        a_ = torch.zeros(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB
+        b_ = torch.empty_like(a_)
+        b_.copy_(a_)
+        torch.cuda.synchronize()
+        del a_, b_
+
     # ------------------------------------------------------------------ warm-up + timed region
     if W > 0:
         run(starts_warm, 0, W, 0, 0)
@@ -222,7 +231,7 @@ def main():
     print(json.dumps(result), flush=True)
 
 
-def cpu_baseline(wl, g, noise_w, w_in, w_out, lr, target_pairs=150_000):
+def cpu_baseline(wl, g, noise_w, w_in, w_out, lr, target_pairs=2_000_000):
     """The CPU reference, as it stands, on a bounded sample of the same workload
     (single thread): walks for the sample, pairs, negatives, one SGNS iteration."""
     import oracle
