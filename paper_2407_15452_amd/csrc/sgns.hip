@@ -43,7 +43,8 @@ struct Term {      // one (pair, j) contribution to a context-table row
   int32_t row;
   int32_t center;
   float coef;      // -lr * g
-  int32_t pad;
+  uint32_t where;  // low 16 bits: number of terms of this row, high 16: position of this
+                   // term among them; both saturate at 65535 (exact for rows <= kLongRow)
 };
 
 struct SgnsArgs {
@@ -63,11 +64,11 @@ struct SgnsArgs {
   uint32_t* cnt;            // [num_nodes + 1]; after scan: offsets
   uint32_t* tile_sums;      // scan scratch
   Term* sorted;             // [num_terms]
-  unsigned long long* slot_counter;
-  int32_t* stage_center;    // [<= num_pairs]
-  float* stage_delta;       // [<= num_pairs][dim]
+  int32_t* stage_center;    // [num_pairs], -1 = unused slot
+  float* stage_delta;       // [num_pairs][dim]
   double* loss_partials;    // [forward blocks]
   int64_t forward_blocks;
+  int64_t forward_blocks_per_xcd;
   double* loss_out;
 };
 
@@ -116,26 +117,19 @@ __device__ __forceinline__ void zero(float4 (&a)[VPL]) {
   for (int v = 0; v < VPL; ++v) a[v] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
-__device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + expf(-x)); }
-__device__ __forceinline__ float softplusf_(float z) {
-  return fmaxf(z, 0.0f) + log1pf(expf(-fabsf(z)));
-}
-
-__global__ void sgns_clear_kernel(uint32_t* __restrict__ cnt, int64_t n,
-                                  unsigned long long* slot_counter) {
+__global__ void sgns_clear_kernel(uint32_t* __restrict__ cnt, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) cnt[i] = 0u;
-  if (i == 0) *slot_counter = 0ull;
 }
 
+// Staged centre-row gradient of one run of equal centres.  Slot numbers are
+// fixed by position (first pair of the chunk + flush number), so no counter is
+// shared between groups; unused slots of a chunk are marked with centre -1.
 template <int VPL>
-__device__ __forceinline__ void stage_flush(const SgnsArgs& a, int32_t center, int l16,
+__device__ __forceinline__ void stage_flush(const SgnsArgs& a, int64_t slot, int32_t center, int l16,
                                             const float4 (&du)[VPL]) {
-  unsigned long long slot = 0;
-  if (l16 == 0) slot = atomicAdd(a.slot_counter, 1ull);
-  slot = __shfl(slot, 0, kGroupLanes);
   if (l16 == 0) a.stage_center[slot] = center;
-  float4* out = reinterpret_cast<float4*>(a.stage_delta + (int64_t)slot * a.dim);
+  float4* out = reinterpret_cast<float4*>(a.stage_delta + slot * (int64_t)a.dim);
   const int dim4 = a.dim >> 2;
 #pragma unroll
   for (int v = 0; v < VPL; ++v) {
@@ -144,68 +138,102 @@ __device__ __forceinline__ void stage_flush(const SgnsArgs& a, int32_t center, i
   }
 }
 
+// loss and dLoss/dx of one term from its logit: one expf, one log1pf, one divide
+__device__ __forceinline__ void term_grad(float x, bool positive, float& g, float& loss) {
+  const float e = expf(-fabsf(x));
+  const float inv = 1.0f / (1.0f + e);
+  const float sig = (x >= 0.0f) ? inv : e * inv;           // sigmoid(x)
+  const float sig_m1 = (x >= 0.0f) ? -e * inv : -inv;      // sigmoid(x) - 1
+  const float z = positive ? -x : x;
+  loss = fmaxf(z, 0.0f) + log1pf(e);                       // softplus(z), |z| = |x|
+  g = positive ? sig_m1 : sig;
+}
+
+// Blocks are handed to the 8 XCDs round-robin; this maps them so that each XCD
+// works on one contiguous eighth of the batch: neighbouring chunks share
+// centre and context rows, which then stay in that XCD's L2.
+__device__ __forceinline__ int64_t xcd_contiguous_block(int64_t bid, int64_t per_xcd) {
+  return (bid & 7) * per_xcd + (bid >> 3);
+}
+
 template <int VPL, int RB>
 __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) {
+  extern __shared__ int32_t idx_s[];              // per group: centres[16], rows[16][K+1]
   __shared__ float loss_s[kGroupsPerBlock];
   const int l16 = threadIdx.x & (kGroupLanes - 1);
   const int group_in_block = threadIdx.x / kGroupLanes;
-  const int64_t group = (int64_t)blockIdx.x * kGroupsPerBlock + group_in_block;
+  const int64_t block = xcd_contiguous_block(blockIdx.x, a.forward_blocks_per_xcd);
+  const int K = a.k, K1 = a.k + 1;
+  const int64_t group = block * kGroupsPerBlock + group_in_block;
   const int64_t first = group * kChunkPairs;
-  const int64_t last = min(first + kChunkPairs, a.num_pairs);
-  const int K = a.k;
+  const bool block_live = block < a.forward_blocks;
+  const int64_t last = block_live ? min(first + kChunkPairs, a.num_pairs) : first;
+  const int count = (int)max((int64_t)0, last - first);
+
+  int32_t* cen_s = idx_s + group_in_block * (kChunkPairs * (K1 + 1));
+  int32_t* rows_s = cen_s + kChunkPairs;
+  if (l16 < count) cen_s[l16] = a.centers[first + l16];
+  for (int t = l16; t < count * K1; t += kGroupLanes) {
+    const int p = t / K1, j = t - p * K1;
+    rows_s[t] = (j == 0) ? a.contexts[first + p] : a.negs[(first + p) * (int64_t)K + (j - 1)];
+  }
+  __syncthreads();
 
   float4 u[VPL], du[VPL];
   zero<VPL>(u);
   zero<VPL>(du);
   int32_t cur_c = -1;
+  int flushes = 0;
   float loss = 0.f;
 
-  for (int64_t i = first; i < last; ++i) {
-    const int32_t c = a.centers[i];
+  for (int p = 0; p < count; ++p) {
+    const int32_t c = cen_s[p];
     if (c != cur_c) {
-      if (cur_c >= 0) stage_flush<VPL>(a, cur_c, l16, du);
+      if (cur_c >= 0) stage_flush<VPL>(a, first + flushes++, cur_c, l16, du);
       load_row<VPL>(a.w_in, c, a.dim, l16, u);
       zero<VPL>(du);
       cur_c = c;
     }
-    const int64_t e0 = i * (int64_t)(K + 1);
+    const int64_t e0 = (first + p) * (int64_t)K1;
+    const int32_t* prow = rows_s + p * K1;
     for (int j0 = 0; j0 <= K; j0 += RB) {
+      // lane b of the group owns term j0 + b of this block of RB terms
+      const int my_j = j0 + l16;
+      const bool mine = l16 < RB && my_j <= K;
+      uint32_t rk = 0;
+      if (mine) rk = atomicAdd(a.cnt + prow[my_j], 1u);
       float4 vv[RB][VPL];
-      int32_t rows[RB];
+#pragma unroll
+      for (int b = 0; b < RB; ++b)
+        if (j0 + b <= K) load_row<VPL>(a.w_out, prow[j0 + b], a.dim, l16, vv[b]);
+      float x_mine = 0.f;
 #pragma unroll
       for (int b = 0; b < RB; ++b) {
-        const int j = j0 + b;
-        if (j <= K) {
-          rows[b] = (j == 0) ? a.contexts[i] : a.negs[i * (int64_t)K + (j - 1)];
-          load_row<VPL>(a.w_out, rows[b], a.dim, l16, vv[b]);
-        }
-      }
-#pragma unroll
-      for (int b = 0; b < RB; ++b) {
-        const int j = j0 + b;
-        if (j <= K) {
-          // position of this term among the terms of its destination row
-          uint32_t rk = 0;
-          if (l16 == 0) rk = atomicAdd(a.cnt + rows[b], 1u);
+        if (j0 + b <= K) {
           const float x = row_sum16(dot_partial<VPL>(u, vv[b]));
-          float gj;
-          if (j == 0) { gj = sigmoidf_(x) - 1.0f; loss += softplusf_(-x); }
-          else        { gj = sigmoidf_(x);        loss += softplusf_(x); }
-          axpy<VPL>(du, gj, vv[b]);
-          if (l16 == 0) { a.g[e0 + j] = gj; a.rank[e0 + j] = rk; }
+          if (l16 == b) x_mine = x;
         }
       }
+      float g_mine = 0.f, l_mine = 0.f;
+      if (mine) term_grad(x_mine, my_j == 0, g_mine, l_mine);
+      loss += l_mine;
+#pragma unroll
+      for (int b = 0; b < RB; ++b)
+        if (j0 + b <= K) axpy<VPL>(du, __shfl(g_mine, b, kGroupLanes), vv[b]);
+      if (mine) { a.g[e0 + my_j] = g_mine; a.rank[e0 + my_j] = rk; }
     }
   }
-  if (cur_c >= 0) stage_flush<VPL>(a, cur_c, l16, du);
+  if (cur_c >= 0) stage_flush<VPL>(a, first + flushes++, cur_c, l16, du);
+  if (l16 >= flushes && l16 < count) a.stage_center[first + l16] = -1;
 
+  loss = row_sum16(loss);
   if (l16 == 0) loss_s[group_in_block] = loss;
   __syncthreads();
-  if (threadIdx.x == 0) {
+  if (threadIdx.x == 0 && block_live) {
     double s = 0.0;
 #pragma unroll
     for (int gidx = 0; gidx < kGroupsPerBlock; ++gidx) s += (double)loss_s[gidx];
-    a.loss_partials[blockIdx.x] = s;
+    a.loss_partials[block] = s;
   }
 }
 
@@ -305,32 +333,17 @@ __global__ __launch_bounds__(256) void sgns_place_kernel(SgnsArgs a) {
   const int64_t i = e / K1;
   const int j = (int)(e - i * K1);
   const int32_t row = (j == 0) ? a.contexts[i] : a.negs[i * (int64_t)a.k + (j - 1)];
-  const uint32_t pos = a.cnt[row] + a.rank[e];
+  const uint32_t begin = a.cnt[row], len = a.cnt[row + 1] - begin;
+  const uint32_t rk = a.rank[e];
   Term t;
   t.row = row;
   t.center = a.centers[i];
   t.coef = -a.lr * a.g[e];
-  t.pad = 0;
-  a.sorted[pos] = t;
+  t.where = min(len, 65535u) | (min(rk, 65535u) << 16);
+  a.sorted[begin + rk] = t;
 }
 
 // ---- update: one pass over the row-major terms ------------------------------------
-template <int VPL>
-__device__ __forceinline__ void row_add_plain(float* __restrict__ table, int64_t row, int dim, int l16,
-                                              const float4 (&acc)[VPL]) {
-  float4* p = reinterpret_cast<float4*>(table + row * (int64_t)dim);
-  const int dim4 = dim >> 2;
-#pragma unroll
-  for (int v = 0; v < VPL; ++v) {
-    const int q = v * kGroupLanes + l16;
-    if (q < dim4) {
-      float4 x = p[q];
-      x.x += acc[v].x; x.y += acc[v].y; x.z += acc[v].z; x.w += acc[v].w;
-      p[q] = x;
-    }
-  }
-}
-
 template <int VPL>
 __device__ __forceinline__ void row_add_atomic(float* __restrict__ table, int64_t row, int dim, int l16,
                                                const float4 (&acc)[VPL]) {
@@ -348,6 +361,9 @@ __device__ __forceinline__ void row_add_atomic(float* __restrict__ table, int64_
   }
 }
 
+// Ownership: a row with at most kLongRow terms is handled whole by the group
+// whose slice holds its first term (so it is written exactly once, without
+// atomics); longer rows are handled slice by slice and added atomically.
 template <int VPL, int UB>
 __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
   const int l16 = threadIdx.x & (kGroupLanes - 1);
@@ -356,40 +372,76 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
   if (slice_begin >= a.num_terms) return;
   const int64_t slice_end = min(slice_begin + kSlice, a.num_terms);
   const Term* __restrict__ sorted = a.sorted;
-  const uint32_t* __restrict__ off = a.cnt;
 
-  int64_t p = slice_begin;
+  int64_t begin = slice_begin, end = slice_end;
   {
-    // a short row that began in an earlier slice belongs to that slice's group
-    const int32_t row = sorted[p].row;
-    const int64_t begin = off[row], end = off[row + 1];
-    if (begin < slice_begin && (end - begin) <= (int64_t)kLongRow) p = end;
+    const uint32_t w0 = sorted[slice_begin].where;
+    const uint32_t len0 = w0 & 0xffffu, pos0 = w0 >> 16;
+    if (len0 <= kLongRow && pos0 > 0) begin = slice_begin - pos0 + len0;   // owned by an earlier group
+    const uint32_t w1 = sorted[slice_end - 1].where;
+    const uint32_t len1 = w1 & 0xffffu, pos1 = w1 >> 16;
+    if (len1 <= kLongRow) end = (slice_end - 1) - pos1 + len1;             // finish the row we started
   }
-  while (p < slice_end) {
-    const int32_t row = sorted[p].row;
-    const int64_t begin = off[row], end = off[row + 1];
-    const bool is_long = (end - begin) > (int64_t)kLongRow;
-    const int64_t stop = is_long ? min(end, slice_end) : end;
-    float4 acc[VPL];
-    zero<VPL>(acc);
-    for (int64_t q = p; q < stop; q += UB) {
-      Term t[UB];
-      float4 u[UB][VPL];
+
+  float4 acc[VPL], old[VPL];
+  zero<VPL>(acc);
+  zero<VPL>(old);
+  int32_t cur_row = -1;
+  bool cur_long = false;
+  const int dim4 = a.dim >> 2;
+
+  auto flush = [&]() {
+    if (cur_long) {
+      row_add_atomic<VPL>(a.w_out, cur_row, a.dim, l16, acc);
+    } else {
+      float4* p = reinterpret_cast<float4*>(a.w_out + cur_row * (int64_t)a.dim);
 #pragma unroll
-      for (int b = 0; b < UB; ++b) {
-        if (q + b < stop) {
-          t[b] = sorted[q + b];
-          load_row<VPL>(a.w_in, t[b].center, a.dim, l16, u[b]);
+      for (int v = 0; v < VPL; ++v) {
+        const int q = v * kGroupLanes + l16;
+        if (q < dim4)
+          p[q] = make_float4(old[v].x + acc[v].x, old[v].y + acc[v].y, old[v].z + acc[v].z,
+                             old[v].w + acc[v].w);
+      }
+    }
+  };
+
+  for (int64_t q = begin; q < end; q += kGroupLanes) {
+    Term t;
+    t.row = -1; t.center = 0; t.coef = 0.f; t.where = 0;
+    if (q + l16 < end) t = sorted[q + l16];
+    const int n = (int)min((int64_t)kGroupLanes, end - q);
+#pragma unroll
+    for (int b0 = 0; b0 < kGroupLanes; b0 += UB) {
+      if (b0 < n) {
+        float4 u[UB][VPL];
+        int32_t rows[UB];
+        float coefs[UB];
+        uint32_t lens[UB];
+#pragma unroll
+        for (int b = 0; b < UB; ++b) {
+          rows[b] = __shfl(t.row, b0 + b, kGroupLanes);
+          coefs[b] = __shfl(t.coef, b0 + b, kGroupLanes);
+          lens[b] = __shfl(t.where, b0 + b, kGroupLanes) & 0xffffu;
+          const int32_t center = __shfl(t.center, b0 + b, kGroupLanes);
+          if (b0 + b < n) load_row<VPL>(a.w_in, center, a.dim, l16, u[b]);
+        }
+#pragma unroll
+        for (int b = 0; b < UB; ++b) {
+          if (b0 + b < n) {
+            if (rows[b] != cur_row) {
+              if (cur_row >= 0) flush();
+              cur_row = rows[b];
+              cur_long = lens[b] > kLongRow;
+              zero<VPL>(acc);
+              if (!cur_long) load_row<VPL>(a.w_out, cur_row, a.dim, l16, old);
+            }
+            axpy<VPL>(acc, coefs[b], u[b]);
+          }
         }
       }
-#pragma unroll
-      for (int b = 0; b < UB; ++b)
-        if (q + b < stop) axpy<VPL>(acc, t[b].coef, u[b]);
     }
-    if (is_long) row_add_atomic<VPL>(a.w_out, row, a.dim, l16, acc);
-    else row_add_plain<VPL>(a.w_out, row, a.dim, l16, acc);
-    p = stop;
   }
+  if (cur_row >= 0) flush();
 }
 
 // ---- apply: staged centre-row gradients into w_in ----------------------------------
@@ -399,9 +451,9 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_apply_kernel(SgnsArgs a) {
   const int l16 = threadIdx.x & (kGroupLanes - 1);
   const int64_t group = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
   const int64_t stride = (int64_t)gridDim.x * kGroupsPerBlock;
-  const int64_t slots = (int64_t)*a.slot_counter;
-  for (int64_t s = group; s < slots; s += stride) {
+  for (int64_t s = group; s < a.num_pairs; s += stride) {
     const int32_t c = a.stage_center[s];
+    if (c < 0) continue;
     const float* src = a.stage_delta + s * (int64_t)a.dim;
     float* dst = a.w_in + c * (int64_t)a.dim;
     for (int e = l16; e < a.dim; e += kGroupLanes) unsafeAtomicAdd(dst + e, -a.lr * src[e]);
@@ -427,7 +479,6 @@ static int64_t forward_blocks_for(int64_t num_pairs) {
 }
 
 struct SgnsPlan {
-  unsigned long long* slot_counter;
   double* loss_partials;
   float* g;
   uint32_t* rank;
@@ -445,7 +496,6 @@ static SgnsPlan plan_sgns(void* ws, int64_t num_pairs, int64_t num_nodes, int32_
   const size_t b = (size_t)(num_pairs > 0 ? num_pairs : 1);
   const size_t terms = b * (size_t)(k + 1);
   const size_t n1 = (size_t)(num_nodes > 0 ? num_nodes : 1) + 1;
-  p.slot_counter = cv.take<unsigned long long>(1);
   p.loss_partials = cv.take<double>((size_t)forward_blocks_for((int64_t)b));
   p.g = cv.take<float>(terms);
   p.rank = cv.take<uint32_t>(terms);
@@ -462,10 +512,12 @@ template <int VPL, int RB, int UB>
 static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
   const int64_t n1 = a.num_nodes + 1;
   const int64_t tiles = ceil_div(n1, kScanTile);
-  sgns_clear_kernel<<<(unsigned)ceil_div(n1, 256), 256, 0, stream>>>(a.cnt, n1, a.slot_counter);
+  sgns_clear_kernel<<<(unsigned)ceil_div(n1, 256), 256, 0, stream>>>(a.cnt, n1);
   GS_LAUNCH_CHECK();
   const unsigned blocks = (unsigned)a.forward_blocks;
-  sgns_forward_kernel<VPL, RB><<<blocks, kSgnsThreads, 0, stream>>>(a);
+  const size_t idx_lds = (size_t)kGroupsPerBlock * kChunkPairs * (a.k + 2) * sizeof(int32_t);
+  sgns_forward_kernel<VPL, RB><<<(unsigned)(a.forward_blocks_per_xcd * 8), kSgnsThreads, idx_lds,
+                                stream>>>(a);
   GS_LAUNCH_CHECK();
   scan_reduce_kernel<<<(unsigned)tiles, kScanThreads, 0, stream>>>(a.cnt, n1, a.tile_sums);
   GS_LAUNCH_CHECK();
@@ -508,7 +560,7 @@ extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int3
   if (!w_in || !w_out || num_nodes < 1 || num_nodes > (int64_t)INT32_MAX) return GS_EINVAL;
   if (dim < 4 || dim > 1024 || (dim & 3) != 0) return GS_EINVAL;
   if (dtype != GS_F32) return GS_EINVAL;   // bf16 tables: not built yet
-  if (num_pairs < 0 || k < 0 || !loss_sum_out) return GS_EINVAL;
+  if (num_pairs < 0 || k < 0 || k > 60 || !loss_sum_out) return GS_EINVAL;
   if (num_pairs > 0 && (!centers || !contexts || (k > 0 && !negs))) return GS_EINVAL;
   if (num_pairs * (int64_t)(k + 1) > (int64_t)0x7fffffff) return GS_EOVERFLOW;
   if (!aligned(w_in, 16) || !aligned(w_out, 16)) return GS_EINVAL;
@@ -537,16 +589,16 @@ extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int3
   a.cnt = p.cnt;
   a.tile_sums = p.tile_sums;
   a.sorted = p.sorted;
-  a.slot_counter = p.slot_counter;
   a.stage_center = p.stage_center;
   a.stage_delta = p.stage_delta;
   a.loss_partials = p.loss_partials;
   a.forward_blocks = forward_blocks_for(num_pairs);
+  a.forward_blocks_per_xcd = ceil_div(a.forward_blocks, 8);
   a.loss_out = loss_sum_out;
   const int vpl = (dim + 63) / 64;
-  if (vpl <= 1) return launch_sgns<1, 6, 4>(a, stream);
-  if (vpl <= 2) return launch_sgns<2, 6, 4>(a, stream);
-  if (vpl <= 4) return launch_sgns<4, 3, 2>(a, stream);
-  if (vpl <= 8) return launch_sgns<8, 2, 1>(a, stream);
+  if (vpl <= 1) return launch_sgns<1, 6, 8>(a, stream);
+  if (vpl <= 2) return launch_sgns<2, 6, 8>(a, stream);
+  if (vpl <= 4) return launch_sgns<4, 3, 4>(a, stream);
+  if (vpl <= 8) return launch_sgns<8, 2, 2>(a, stream);
   return launch_sgns<16, 1, 1>(a, stream);
 }
