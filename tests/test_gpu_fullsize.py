@@ -1,0 +1,141 @@
+"""Parity at the full size of the benchmark workload (4M nodes, ~70M undirected
+edges, node2vec walks of 80 nodes, 2,000,000-pair batches, dim 128), in the
+launch shapes bench.py times.  Outputs too large to recompute on the CPU are
+checked on samples the oracle computes one by one (walks by id, negatives by
+pair index, pair blocks by walk) or through properties that hold at any size;
+one whole SGNS batch is recomputed by the oracle and compared in full.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def gs():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2407_15452_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def big(gs):
+    from paper_2407_15452_amd import inputs
+    wl = inputs.WORKLOADS[2]
+    src, dst, _ = inputs.edge_list(wl, DEV)
+    flags = gs.GS_SYMMETRIZE | gs.GS_DROP_SELF_LOOPS | gs.GS_DEDUPE
+    g = gs.gs_csr_build(src, dst, None, wl.num_nodes, flags)
+    torch.cuda.synchronize()
+    off = g.offsets.cpu().numpy()
+    nb = g.nbrs.cpu().numpy()
+    return wl, g, off, nb, src, dst
+
+
+def test_csr_properties_and_sampled_rows(gs, big):
+    wl, g, off, nb, src, dst = big
+    n = wl.num_nodes
+    assert off[0] == 0 and off[-1] == nb.size and (np.diff(off) >= 0).all()
+    # number of entries = 2 x distinct undirected edges of the input
+    key = torch.minimum(src, dst).long() * n + torch.maximum(src, dst).long()
+    assert nb.size == 2 * int(torch.unique(key).numel())
+    # rows strictly ascending, no self loops, ids in range
+    rows = np.repeat(np.arange(n, dtype=np.int64), np.diff(off))
+    same_row = rows[1:] == rows[:-1]
+    assert (nb[1:][same_row] > nb[:-1][same_row]).all()
+    assert (nb != rows).all() and nb.min() >= 0 and nb.max() < n
+    # sampled rows against the definition, straight from the edge list
+    rng = np.random.default_rng(0)
+    deg = np.diff(off)
+    sample = np.concatenate([rng.integers(0, n, 40), np.argsort(deg)[-3:]])
+    for v in sample:
+        v = int(v)
+        want = torch.unique(torch.cat([dst[src == v], src[dst == v]])).cpu().numpy()
+        np.testing.assert_array_equal(nb[off[v]:off[v + 1]], want)
+    # symmetry on a sample of entries: (a, b) present => (b, a) present
+    for e in rng.integers(0, nb.size, 200):
+        a, b = int(rows[e]), int(nb[e])
+        r = nb[off[b]:off[b + 1]]
+        i = np.searchsorted(r, a)
+        assert i < r.size and r[i] == a
+
+
+def test_node2vec_walks_sampled(gs, oracle, big):
+    wl, g, off, nb, _, _ = big
+    from paper_2407_15452_amd import inputs
+    rng = np.random.default_rng(1)
+    # the chunk shape bench.py walks for 20 batches, and one round over all nodes
+    for first, count in ((4_000_123, 46_960), (0, 4_000_000)):
+        starts = inputs.walk_starts(wl.num_nodes, first, count, DEV)
+        walks = gs.gs_node2vec_walk(g, None, starts, wl.walk_len, wl.p, wl.q, wl.walk_seed,
+                                    walk_id_base=first)
+        pick = np.sort(rng.choice(count, 400, replace=False))
+        got = walks[torch.as_tensor(pick, device=DEV)].cpu().numpy()
+        st = starts[torch.as_tensor(pick, device=DEV)].cpu().numpy()
+        for i, s, row in zip(pick, st, got):
+            want = oracle.node2vec_walk(off, nb, np.array([s], dtype=np.int32), wl.walk_len,
+                                        wl.p, wl.q, wl.walk_seed, walk_id_base=first + int(i))
+            np.testing.assert_array_equal(row, want[0])
+        # property over the whole launch: a walk from a node with edges never dies
+        live = torch.as_tensor(np.diff(off) > 0, device=DEV)[starts.long()]
+        assert bool((walks[live] >= 0).all())
+        assert bool((walks[~live][:, 1:] == -1).all())
+        del walks
+
+
+def test_pairs_negatives_and_sgns_batch(gs, oracle, big):
+    wl, g, off, nb, _, _ = big
+    from paper_2407_15452_amd import inputs
+    B, K, L, W = wl.batch_pairs, wl.num_neg, wl.walk_len, wl.window
+    first, count = 0, 4000
+    starts = inputs.walk_starts(wl.num_nodes, first, count, DEV)
+    walks = gs.gs_node2vec_walk(g, None, starts, L, wl.p, wl.q, wl.walk_seed)
+    centers, contexts, n_pairs = gs.gs_make_pairs(walks, W)
+    h_walks = walks.cpu().numpy()
+    lens = (h_walks >= 0).sum(1)
+    per = np.where(lens > W, 2 * W * lens - W * (W + 1), lens * (lens - 1))
+    assert n_pairs == per.sum() and n_pairs >= B
+    base = np.concatenate([[0], np.cumsum(per)])
+    rng = np.random.default_rng(2)
+    hc, ho = centers.cpu().numpy(), contexts.cpu().numpy()
+    for i in rng.choice(count, 60, replace=False):
+        wc, wo = oracle.make_pairs(h_walks[i:i + 1], W)
+        np.testing.assert_array_equal(hc[base[i]:base[i + 1]], wc)
+        np.testing.assert_array_equal(ho[base[i]:base[i + 1]], wo)
+
+    # negatives of one full batch, sampled by pair index
+    noise_w = inputs.noise_weights(g.offsets)
+    seg = torch.tensor([0, wl.num_nodes], dtype=torch.int64, device=DEV)
+    noise = gs.gs_alias_build(seg, noise_w)
+    pair_base = 37 * B
+    negs = gs.gs_sample_negatives(noise, wl.num_nodes, B, K, wl.neg_seed, pair_index_base=pair_base)
+    table = (noise.prob.cpu().numpy(), noise.alias.cpu().numpy())
+    # the table itself against the oracle's construction (bit-exact, 4M entries)
+    o_prob, o_alias = oracle.alias_build(np.array([0, wl.num_nodes], dtype=np.int64),
+                                         noise_w.cpu().numpy())
+    np.testing.assert_array_equal(table[1], o_alias)
+    np.testing.assert_array_equal(table[0], o_prob)
+    h_negs = negs.cpu().numpy()
+    for i in rng.choice(B, 300, replace=False):
+        want = oracle.sample_negatives(table, wl.num_nodes, 1, K, wl.neg_seed,
+                                       pair_index_base=pair_base + int(i))
+        np.testing.assert_array_equal(h_negs[i], want[0])
+    assert h_negs.min() >= 0 and h_negs.max() < wl.num_nodes
+    assert (np.diff(off)[h_negs.ravel()[:200_000]] > 0).all()     # never a zero-weight node
+
+    # one whole 2,000,000-pair SGNS iteration against the oracle
+    w_in, w_out = inputs.random_tables(wl.num_nodes, wl.dim, seed=5, scale=0.15, device=DEV)
+    h_in, h_out = w_in.cpu().numpy(), w_out.cpu().numpy()
+    c, o = centers[:B], contexts[:B]
+    lr = 0.025
+    loss = gs.gs_sgns_step(w_in, w_out, c, o, negs, lr)
+    torch.cuda.synchronize()
+    want = oracle.sgns_step(h_in, h_out, hc[:B], ho[:B], h_negs, lr)
+    got = float(loss.item())
+    assert abs(got - want) <= 1e-5 * abs(want)
+    assert np.abs(w_in.cpu().numpy() - h_in).max() <= 1e-5
+    assert np.abs(w_out.cpu().numpy() - h_out).max() <= 1e-5
