@@ -70,19 +70,22 @@ __global__ __launch_bounds__(kWalkThreads) void walk_kernel(WalkArgs a) {
             const int32_t x = nbrs[lo + j];
             next = x;
             if (!kSecondOrder || t == 0) break;
-            float bias;
+            // accept iff s < bias(x).  For x != prev the bias is 1 or 1/q, so the
+            // membership search is only needed when s falls between the two.
+            const float s = unit_float(b.x3) * a.max_bias;
             if (x == prev) {
-              bias = a.inv_p;
-            } else {
-              // lower bound of x in the row of prev
-              int64_t l = prev_lo, h = prev_hi;
-              while (l < h) {
-                const int64_t mid = l + ((h - l) >> 1);
-                if (nbrs[mid] < x) l = mid + 1; else h = mid;
-              }
-              bias = (l < prev_hi && nbrs[l] == x) ? 1.0f : a.inv_q;
+              if (s < a.inv_p) break;
+              continue;
             }
-            if (unit_float(b.x3) * a.max_bias < bias) break;
+            if (s < fminf(1.0f, a.inv_q)) break;
+            if (!(s < fmaxf(1.0f, a.inv_q))) continue;
+            int64_t l = prev_lo, h = prev_hi;   // lower bound of x in the row of prev
+            while (l < h) {
+              const int64_t mid = l + ((h - l) >> 1);
+              if (nbrs[mid] < x) l = mid + 1; else h = mid;
+            }
+            const float bias = (l < prev_hi && nbrs[l] == x) ? 1.0f : a.inv_q;
+            if (s < bias) break;
           }
         }
       }
