@@ -183,10 +183,13 @@ int32_t gs_sample_negatives(const gs_alias* noise, int64_t num_nodes, int64_t nu
  *   w_in[c] -= lr * sum g_j v_j;  w_out[row_j] -= lr * g_j u, summed over all
  *   occurrences in the batch.  loss_sum_out double[1] on the device receives
  *   the sum of loss_i (overwritten).
- *   dim must be a multiple of 4 and at most 1024; k <= 60; num_pairs * (k+1) < 2^31.
- *   Rows that the batch does not name are not touched.  The workspace holds
- *   the per-term coefficients, the terms regrouped by destination row, a
- *   counter per node and the staged centre-row gradients.
+ *   Every touched element is written once, as round(old + delta) with delta
+ *   summed in fp32 (bf16: round to nearest even).
+ *   dim must be a multiple of 4 (fp32) or 8 (bf16) and at most 1024; k <= 60;
+ *   num_pairs * (k+1) < 2^31.  Rows that the batch does not name are not
+ *   touched.  The workspace holds the per-term coefficients, the terms
+ *   regrouped by destination row, a counter per node, an fp32 side buffer for
+ *   rows with many terms and the staged centre-row gradients.
  * ------------------------------------------------------------------------ */
 size_t gs_sgns_step_workspace_bytes(int64_t num_pairs, int64_t num_nodes, int32_t k, int32_t dim,
                                     int32_t dtype);

@@ -3,26 +3,30 @@
 // the barrier of "Synchronization": all reads see the pre-iteration tables).
 //
 // The batch-synchronous rule is kept by splitting the iteration at kernel
-// boundaries, and the scatter into the context table is done without one
-// atomic per element: float atomics run at ~1/5 of the plain read-modify-write
-// rate on this chip, so the (pair, j) terms are grouped by destination row
-// first and each row is written once.
+// boundaries, and no atomic ever touches an embedding table: float atomics run
+// at ~1/5 of the plain read-modify-write rate on this chip (and do not exist
+// for a "round once" bf16 update), so contributions are first brought together
+// per destination row and every touched row is written exactly once, as
+// round(old + delta) with delta accumulated in fp32.
 //
-//   clear     cnt[0..N] = 0
-//   forward   read-only on both tables: logits, g = dLoss/dx, loss, the
-//             centre-row gradients staged per run of equal centres, and
-//             rank[e] = cnt[row_e]++ (position of term e among the terms of
-//             its destination row)
-//   scan      off = exclusive prefix sum of cnt
-//   place     sorted[off[row_e] + rank[e]] = (row_e, centre_e, -lr * g_e)
-//   update    per destination row: w_out[row] += sum coef * w_in[centre]
-//             (w_in is still unmodified); one plain read-modify-write per row;
-//             rows with more than kLongRow terms are cut into slices whose
-//             partial sums are added atomically
-//   apply     w_in[centre] += -lr * staged gradient (atomic, few rows)
-//   finish    deterministic sum of the per-block loss partials
+//   clear      cnt[0..N] = 0
+//   forward    read-only on both tables: logits, g = dLoss/dx, loss, the
+//              centre-row gradients staged per run of equal centres, and
+//              rank[e] = cnt[row_e]++ (position of term e among the terms of
+//              its destination row)
+//   scan       off = exclusive prefix sum of cnt
+//   place      sorted[off[row_e] + rank[e]] = (row_e, centre_e, -lr * g_e)
+//   update     per destination row: delta = sum coef * w_in[centre] (w_in is
+//              still unmodified).  Rows with at most kLongRow terms are
+//              handled whole by one 16-lane group and written once; longer
+//              rows are summed slice by slice into an fp32 side buffer
+//   long_rows  w_out[row] = round(old + side buffer) for the long rows
+//   owners     owner[centre] = lowest staging slot holding that centre
+//   merge      staged gradients of the other slots are added into the owner's
+//   apply      w_in[centre] = round(old - lr * merged gradient)
+//   finish     deterministic sum of the per-block loss partials
 //
-// A row is handled by 16 lanes holding float4 pieces (256 contiguous bytes per
+// A row is handled by 16 lanes holding 16-byte pieces (256 contiguous bytes per
 // load instruction); a wave works on four rows at once and a dot product is a
 // 16-lane DPP reduction.  No matrix cores: 0.3 flop per byte moved.
 #include "common.h"
@@ -34,10 +38,14 @@ constexpr int kGroupLanes = 16;
 constexpr int kGroupsPerBlock = kSgnsThreads / kGroupLanes;
 constexpr int kChunkPairs = 16;    // consecutive pairs per 16-lane group in forward
 constexpr int kSlice = 128;        // sorted terms per 16-lane group in update
-constexpr uint32_t kLongRow = 256; // rows with more terms than this are updated slice by slice
+constexpr uint32_t kLongRow = 256; // rows with more terms than this go through the side buffer
+constexpr int kLongShift = 8;      // log2(kLongRow): side-buffer slot = first term position >> 8
 constexpr int kScanThreads = 256;
 constexpr int kScanPerThread = 16;
 constexpr int kScanTile = kScanThreads * kScanPerThread;
+constexpr uint32_t kNoOwner = 0xffffffffu;
+
+typedef uint16_t bf16_t;           // bfloat16 storage
 
 struct Term {      // one (pair, j) contribution to a context-table row
   int32_t row;
@@ -48,30 +56,33 @@ struct Term {      // one (pair, j) contribution to a context-table row
 };
 
 struct SgnsArgs {
-  float* w_in;
-  float* w_out;
+  void* w_in;
+  void* w_out;
   const int32_t* centers;
   const int32_t* contexts;
   const int32_t* negs;
   int64_t num_pairs;
   int64_t num_nodes;
   int64_t num_terms;        // num_pairs * (k + 1)
+  int64_t long_slots;       // (num_terms >> kLongShift) + 1
   int32_t k;
   int32_t dim;
   float lr;
   float* g;                 // [num_terms]
   uint32_t* rank;           // [num_terms]
-  uint32_t* cnt;            // [num_nodes + 1]; after scan: offsets
+  uint32_t* cnt;            // [num_nodes + 1]; after scan: offsets; later: owner slot per centre
   uint32_t* tile_sums;      // scan scratch
   Term* sorted;             // [num_terms]
+  float* long_acc;          // [long_slots][dim] fp32 sums of the long rows
   int32_t* stage_center;    // [num_pairs], -1 = unused slot
-  float* stage_delta;       // [num_pairs][dim]
+  float* stage_delta;       // [num_pairs][dim], natural element order
   double* loss_partials;    // [forward blocks]
   int64_t forward_blocks;
   int64_t forward_blocks_per_xcd;
   double* loss_out;
 };
 
+// ---- small device helpers ---------------------------------------------------------
 // sum over the 16 lanes of a DPP row; every lane gets the total
 __device__ __forceinline__ float row_sum16(float x) {
   x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
@@ -79,6 +90,36 @@ __device__ __forceinline__ float row_sum16(float x) {
   x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));  // row_half_mirror
   x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true));  // row_mirror
   return x;
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+// round-to-nearest-even fp32 -> bf16 bits (finite inputs)
+__device__ __forceinline__ uint32_t to_bf16(float f) {
+  const uint32_t b = __float_as_uint(f);
+  return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  return to_bf16(lo) | (to_bf16(hi) << 16);
+}
+
+// Register image of a row: VPL float4 per lane.  Register v of lane l holds the
+// elements [4q, 4q+4) with q = natural_q(v, l):
+//   fp32 rows   one float4 per 16-byte load,  q = v*16 + l
+//   bf16 rows   two float4 per 16-byte load (8 elements), q = 2*((v/2)*16 + l) + (v&1)
+template <typename T>
+__device__ __forceinline__ int natural_q(int v, int l16);
+template <>
+__device__ __forceinline__ int natural_q<float>(int v, int l16) { return v * kGroupLanes + l16; }
+template <>
+__device__ __forceinline__ int natural_q<bf16_t>(int v, int l16) {
+  return 2 * ((v >> 1) * kGroupLanes + l16) + (v & 1);
+}
+
+template <int VPL>
+__device__ __forceinline__ void zero(float4 (&a)[VPL]) {
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) a[v] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
 template <int VPL>
@@ -90,6 +131,60 @@ __device__ __forceinline__ void load_row(const float* __restrict__ table, int64_
   for (int v = 0; v < VPL; ++v) {
     const int q = v * kGroupLanes + l16;
     r[v] = (q < dim4) ? p[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+}
+
+template <int VPL>
+__device__ __forceinline__ void load_row(const bf16_t* __restrict__ table, int64_t row, int dim,
+                                         int l16, float4 (&r)[VPL]) {
+  static_assert(VPL % 2 == 0, "bf16 rows are held as pairs of float4");
+  const uint4* p = reinterpret_cast<const uint4*>(table + row * (int64_t)dim);
+  const int chunks = dim >> 3;
+#pragma unroll
+  for (int w = 0; w < VPL / 2; ++w) {
+    const int c = w * kGroupLanes + l16;
+    if (c < chunks) {
+      const uint4 x = p[c];
+      r[2 * w] = make_float4(bf16_lo(x.x), bf16_hi(x.x), bf16_lo(x.y), bf16_hi(x.y));
+      r[2 * w + 1] = make_float4(bf16_lo(x.z), bf16_hi(x.z), bf16_lo(x.w), bf16_hi(x.w));
+    } else {
+      r[2 * w] = make_float4(0.f, 0.f, 0.f, 0.f);
+      r[2 * w + 1] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+}
+
+// table[row] = round(old + delta), both given as register images
+template <int VPL>
+__device__ __forceinline__ void store_row_sum(float* __restrict__ table, int64_t row, int dim, int l16,
+                                              const float4 (&old)[VPL], const float4 (&d)[VPL]) {
+  float4* p = reinterpret_cast<float4*>(table + row * (int64_t)dim);
+  const int dim4 = dim >> 2;
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    const int q = v * kGroupLanes + l16;
+    if (q < dim4)
+      p[q] = make_float4(old[v].x + d[v].x, old[v].y + d[v].y, old[v].z + d[v].z, old[v].w + d[v].w);
+  }
+}
+
+template <int VPL>
+__device__ __forceinline__ void store_row_sum(bf16_t* __restrict__ table, int64_t row, int dim, int l16,
+                                              const float4 (&old)[VPL], const float4 (&d)[VPL]) {
+  uint4* p = reinterpret_cast<uint4*>(table + row * (int64_t)dim);
+  const int chunks = dim >> 3;
+#pragma unroll
+  for (int w = 0; w < VPL / 2; ++w) {
+    const int c = w * kGroupLanes + l16;
+    if (c < chunks) {
+      const float4 a = old[2 * w], b = old[2 * w + 1], da = d[2 * w], db = d[2 * w + 1];
+      uint4 x;
+      x.x = pack_bf16(a.x + da.x, a.y + da.y);
+      x.y = pack_bf16(a.z + da.z, a.w + da.w);
+      x.z = pack_bf16(b.x + db.x, b.y + db.y);
+      x.w = pack_bf16(b.z + db.z, b.w + db.w);
+      p[c] = x;
+    }
   }
 }
 
@@ -111,33 +206,6 @@ __device__ __forceinline__ void axpy(float4 (&acc)[VPL], float c, const float4 (
   }
 }
 
-template <int VPL>
-__device__ __forceinline__ void zero(float4 (&a)[VPL]) {
-#pragma unroll
-  for (int v = 0; v < VPL; ++v) a[v] = make_float4(0.f, 0.f, 0.f, 0.f);
-}
-
-__global__ void sgns_clear_kernel(uint32_t* __restrict__ cnt, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) cnt[i] = 0u;
-}
-
-// Staged centre-row gradient of one run of equal centres.  Slot numbers are
-// fixed by position (first pair of the chunk + flush number), so no counter is
-// shared between groups; unused slots of a chunk are marked with centre -1.
-template <int VPL>
-__device__ __forceinline__ void stage_flush(const SgnsArgs& a, int64_t slot, int32_t center, int l16,
-                                            const float4 (&du)[VPL]) {
-  if (l16 == 0) a.stage_center[slot] = center;
-  float4* out = reinterpret_cast<float4*>(a.stage_delta + slot * (int64_t)a.dim);
-  const int dim4 = a.dim >> 2;
-#pragma unroll
-  for (int v = 0; v < VPL; ++v) {
-    const int q = v * kGroupLanes + l16;
-    if (q < dim4) out[q] = du[v];
-  }
-}
-
 // loss and dLoss/dx of one term from its logit: one expf, one log1pf, one divide
 __device__ __forceinline__ void term_grad(float x, bool positive, float& g, float& loss) {
   const float e = expf(-fabsf(x));
@@ -151,15 +219,47 @@ __device__ __forceinline__ void term_grad(float x, bool positive, float& g, floa
 
 // Blocks are handed to the 8 XCDs round-robin; this maps them so that each XCD
 // works on one contiguous eighth of the batch: neighbouring chunks share
-// centre and context rows, which then stay in that XCD's L2.
+// centre and context rows, which then stay in that XCD's L2.  Performance only:
+// any block-to-XCD assignment gives the same result.
 __device__ __forceinline__ int64_t xcd_contiguous_block(int64_t bid, int64_t per_xcd) {
   return (bid & 7) * per_xcd + (bid >> 3);
 }
 
-template <int VPL, int RB>
+// ---- clear / fill ---------------------------------------------------------------------
+__global__ void fill_u32_kernel(uint32_t* __restrict__ p, int64_t n, uint32_t value) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = value;
+}
+
+__global__ void fill_f32x4_kernel(float4* __restrict__ p, int64_t n4) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n4) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// ---- forward ------------------------------------------------------------------------------
+// Staged centre-row gradient of one run of equal centres, in natural element
+// order.  Slot numbers are fixed by position (first pair of the chunk + flush
+// number), so no counter is shared between groups; unused slots of a chunk are
+// marked with centre -1.
+template <typename T, int VPL>
+__device__ __forceinline__ void stage_flush(const SgnsArgs& a, int64_t slot, int32_t center, int l16,
+                                            const float4 (&du)[VPL]) {
+  if (l16 == 0) a.stage_center[slot] = center;
+  float4* out = reinterpret_cast<float4*>(a.stage_delta + slot * (int64_t)a.dim);
+  const int dim4 = a.dim >> 2;
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    const int q = natural_q<T>(v, l16);
+    if (q < dim4) out[q] = du[v];
+  }
+}
+
+template <typename T, int VPL, int RB>
 __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) {
   extern __shared__ int32_t idx_s[];              // per group: centres[16], rows[16][K+1]
   __shared__ float loss_s[kGroupsPerBlock];
+  const T* __restrict__ w_in = static_cast<const T*>(a.w_in);
+  const T* __restrict__ w_out = static_cast<const T*>(a.w_out);
   const int l16 = threadIdx.x & (kGroupLanes - 1);
   const int group_in_block = threadIdx.x / kGroupLanes;
   const int64_t block = xcd_contiguous_block(blockIdx.x, a.forward_blocks_per_xcd);
@@ -189,8 +289,8 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
   for (int p = 0; p < count; ++p) {
     const int32_t c = cen_s[p];
     if (c != cur_c) {
-      if (cur_c >= 0) stage_flush<VPL>(a, first + flushes++, cur_c, l16, du);
-      load_row<VPL>(a.w_in, c, a.dim, l16, u);
+      if (cur_c >= 0) stage_flush<T, VPL>(a, first + flushes++, cur_c, l16, du);
+      load_row<VPL>(w_in, c, a.dim, l16, u);
       zero<VPL>(du);
       cur_c = c;
     }
@@ -205,7 +305,7 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
       float4 vv[RB][VPL];
 #pragma unroll
       for (int b = 0; b < RB; ++b)
-        if (j0 + b <= K) load_row<VPL>(a.w_out, prow[j0 + b], a.dim, l16, vv[b]);
+        if (j0 + b <= K) load_row<VPL>(w_out, prow[j0 + b], a.dim, l16, vv[b]);
       float x_mine = 0.f;
 #pragma unroll
       for (int b = 0; b < RB; ++b) {
@@ -223,7 +323,7 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
       if (mine) { a.g[e0 + my_j] = g_mine; a.rank[e0 + my_j] = rk; }
     }
   }
-  if (cur_c >= 0) stage_flush<VPL>(a, first + flushes++, cur_c, l16, du);
+  if (cur_c >= 0) stage_flush<T, VPL>(a, first + flushes++, cur_c, l16, du);
   if (l16 >= flushes && l16 < count) a.stage_center[first + l16] = -1;
 
   loss = row_sum16(loss);
@@ -344,28 +444,15 @@ __global__ __launch_bounds__(256) void sgns_place_kernel(SgnsArgs a) {
 }
 
 // ---- update: one pass over the row-major terms ------------------------------------
-template <int VPL>
-__device__ __forceinline__ void row_add_atomic(float* __restrict__ table, int64_t row, int dim, int l16,
-                                               const float4 (&acc)[VPL]) {
-  float* dst = table + row * (int64_t)dim;
-  const int dim4 = dim >> 2;
-#pragma unroll
-  for (int v = 0; v < VPL; ++v) {
-    const int q = v * kGroupLanes + l16;
-    if (q < dim4) {
-      unsafeAtomicAdd(dst + 4 * q + 0, acc[v].x);
-      unsafeAtomicAdd(dst + 4 * q + 1, acc[v].y);
-      unsafeAtomicAdd(dst + 4 * q + 2, acc[v].z);
-      unsafeAtomicAdd(dst + 4 * q + 3, acc[v].w);
-    }
-  }
-}
-
 // Ownership: a row with at most kLongRow terms is handled whole by the group
-// whose slice holds its first term (so it is written exactly once, without
-// atomics); longer rows are handled slice by slice and added atomically.
-template <int VPL, int UB>
+// whose slice holds its first term, which writes it once.  Longer rows are
+// handled slice by slice; their partial sums meet in the fp32 side buffer at
+// slot (position of the row's first term) >> kLongShift, which no two long rows
+// can share because each of them spans more than 2^kLongShift positions.
+template <typename T, int VPL, int UB>
 __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
+  const T* __restrict__ w_in = static_cast<const T*>(a.w_in);
+  T* w_out = static_cast<T*>(a.w_out);
   const int l16 = threadIdx.x & (kGroupLanes - 1);
   const int64_t group = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
   const int64_t slice_begin = group * kSlice;
@@ -392,16 +479,19 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
 
   auto flush = [&]() {
     if (cur_long) {
-      row_add_atomic<VPL>(a.w_out, cur_row, a.dim, l16, acc);
-    } else {
-      float4* p = reinterpret_cast<float4*>(a.w_out + cur_row * (int64_t)a.dim);
+      float* dst = a.long_acc + (int64_t)(a.cnt[cur_row] >> kLongShift) * a.dim;
 #pragma unroll
       for (int v = 0; v < VPL; ++v) {
-        const int q = v * kGroupLanes + l16;
-        if (q < dim4)
-          p[q] = make_float4(old[v].x + acc[v].x, old[v].y + acc[v].y, old[v].z + acc[v].z,
-                             old[v].w + acc[v].w);
+        const int q = natural_q<T>(v, l16);
+        if (q < dim4) {
+          unsafeAtomicAdd(dst + 4 * q + 0, acc[v].x);
+          unsafeAtomicAdd(dst + 4 * q + 1, acc[v].y);
+          unsafeAtomicAdd(dst + 4 * q + 2, acc[v].z);
+          unsafeAtomicAdd(dst + 4 * q + 3, acc[v].w);
+        }
       }
+    } else {
+      store_row_sum<VPL>(w_out, cur_row, a.dim, l16, old, acc);
     }
   };
 
@@ -423,7 +513,7 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
           coefs[b] = __shfl(t.coef, b0 + b, kGroupLanes);
           lens[b] = __shfl(t.where, b0 + b, kGroupLanes) & 0xffffu;
           const int32_t center = __shfl(t.center, b0 + b, kGroupLanes);
-          if (b0 + b < n) load_row<VPL>(a.w_in, center, a.dim, l16, u[b]);
+          if (b0 + b < n) load_row<VPL>(w_in, center, a.dim, l16, u[b]);
         }
 #pragma unroll
         for (int b = 0; b < UB; ++b) {
@@ -433,7 +523,7 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
               cur_row = rows[b];
               cur_long = lens[b] > kLongRow;
               zero<VPL>(acc);
-              if (!cur_long) load_row<VPL>(a.w_out, cur_row, a.dim, l16, old);
+              if (!cur_long) load_row<VPL>(static_cast<const T*>(w_out), cur_row, a.dim, l16, old);
             }
             axpy<VPL>(acc, coefs[b], u[b]);
           }
@@ -444,19 +534,85 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
   if (cur_row >= 0) flush();
 }
 
-// ---- apply: staged centre-row gradients into w_in ----------------------------------
-// Lane l of a group owns elements l, l+16, ...: each atomic instruction of a
-// group covers 64 contiguous bytes (one request to the L2 instead of four).
-__global__ __launch_bounds__(kSgnsThreads) void sgns_apply_kernel(SgnsArgs a) {
+// element-wise row helpers for the small follow-up kernels (natural order)
+__device__ __forceinline__ float elem_load(const float* row, int e) { return row[e]; }
+__device__ __forceinline__ float elem_load(const bf16_t* row, int e) {
+  return __uint_as_float((uint32_t)row[e] << 16);
+}
+__device__ __forceinline__ void elem_store(float* row, int e, float v) { row[e] = v; }
+__device__ __forceinline__ void elem_store(bf16_t* row, int e, float v) { row[e] = (bf16_t)to_bf16(v); }
+
+// ---- long_rows: w_out[row] = round(old + side buffer) --------------------------------------
+// Side-buffer slot s belongs to the long row whose first term lies in
+// [s << kLongShift, (s+1) << kLongShift): that row then also owns the last
+// position of the window.
+template <typename T>
+__global__ __launch_bounds__(kSgnsThreads) void sgns_long_rows_kernel(SgnsArgs a) {
+  T* w_out = static_cast<T*>(a.w_out);
+  const int l16 = threadIdx.x & (kGroupLanes - 1);
+  const int64_t s = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
+  const int64_t last_pos = ((s + 1) << kLongShift) - 1;
+  if (last_pos >= a.num_terms) return;
+  const Term t = a.sorted[last_pos];
+  if ((t.where & 0xffffu) <= kLongRow) return;
+  const int64_t first_pos = (int64_t)a.cnt[t.row];
+  if ((first_pos >> kLongShift) != s) return;
+  const float* src = a.long_acc + s * (int64_t)a.dim;
+  T* dst = w_out + t.row * (int64_t)a.dim;
+  for (int e = l16; e < a.dim; e += kGroupLanes) elem_store(dst, e, elem_load(dst, e) + src[e]);
+}
+
+// ---- owners / merge / apply: staged centre-row gradients into w_in -----------------------
+__global__ void sgns_owner_kernel(SgnsArgs a) {
+  const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= a.num_pairs) return;
+  const int32_t c = a.stage_center[s];
+  if (c >= 0) atomicMin(a.cnt + c, (uint32_t)s);
+}
+
+// Every staged slot that does not own its centre adds its gradient into the
+// owner's slot (fp32 atomics on the staging buffer, 64 contiguous bytes per
+// instruction of a group).  A group looks at 16 slots at once, one per lane,
+// and then walks only the slots that have work.
+__global__ __launch_bounds__(kSgnsThreads) void sgns_merge_kernel(SgnsArgs a) {
   const int l16 = threadIdx.x & (kGroupLanes - 1);
   const int64_t group = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
-  const int64_t stride = (int64_t)gridDim.x * kGroupsPerBlock;
-  for (int64_t s = group; s < a.num_pairs; s += stride) {
-    const int32_t c = a.stage_center[s];
+  const int64_t s_mine = group * kGroupLanes + l16;
+  int64_t owner_mine = -1;                    // >= 0: this lane's slot must be merged into owner
+  if (s_mine < a.num_pairs) {
+    const int32_t c = a.stage_center[s_mine];
+    if (c >= 0) {
+      const int64_t owner = (int64_t)a.cnt[c];
+      if (owner != s_mine) owner_mine = owner;
+    }
+  }
+  for (int b = 0; b < kGroupLanes; ++b) {
+    const int64_t owner = __shfl(owner_mine, b, kGroupLanes);
+    if (owner < 0) continue;
+    const float* src = a.stage_delta + (group * kGroupLanes + b) * (int64_t)a.dim;
+    float* dst = a.stage_delta + owner * (int64_t)a.dim;
+    for (int e = l16; e < a.dim; e += kGroupLanes) unsafeAtomicAdd(dst + e, src[e]);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kSgnsThreads) void sgns_apply_kernel(SgnsArgs a) {
+  T* w_in = static_cast<T*>(a.w_in);
+  const int l16 = threadIdx.x & (kGroupLanes - 1);
+  const int64_t group = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
+  const int64_t s_mine = group * kGroupLanes + l16;
+  int32_t center_mine = -1;                   // >= 0: this lane's slot owns that centre
+  if (s_mine < a.num_pairs) {
+    const int32_t c = a.stage_center[s_mine];
+    if (c >= 0 && (int64_t)a.cnt[c] == s_mine) center_mine = c;
+  }
+  for (int b = 0; b < kGroupLanes; ++b) {
+    const int32_t c = __shfl(center_mine, b, kGroupLanes);
     if (c < 0) continue;
-    const float* src = a.stage_delta + s * (int64_t)a.dim;
-    float* dst = a.w_in + c * (int64_t)a.dim;
-    for (int e = l16; e < a.dim; e += kGroupLanes) unsafeAtomicAdd(dst + e, -a.lr * src[e]);
+    const float* src = a.stage_delta + (group * kGroupLanes + b) * (int64_t)a.dim;
+    T* dst = w_in + c * (int64_t)a.dim;
+    for (int e = l16; e < a.dim; e += kGroupLanes)
+      elem_store(dst, e, elem_load(dst, e) - a.lr * src[e]);
   }
 }
 
@@ -474,6 +630,7 @@ __global__ __launch_bounds__(256) void sgns_finish_kernel(const double* __restri
   if (threadIdx.x == 0) *out = s[0];
 }
 
+// ---- host side -----------------------------------------------------------------------------
 static int64_t forward_blocks_for(int64_t num_pairs) {
   return ceil_div(ceil_div(num_pairs, kChunkPairs), kGroupsPerBlock);
 }
@@ -485,8 +642,10 @@ struct SgnsPlan {
   uint32_t* cnt;
   uint32_t* tile_sums;
   Term* sorted;
+  float* long_acc;
   int32_t* stage_center;
   float* stage_delta;
+  int64_t long_slots;
   size_t bytes;
 };
 
@@ -496,28 +655,32 @@ static SgnsPlan plan_sgns(void* ws, int64_t num_pairs, int64_t num_nodes, int32_
   const size_t b = (size_t)(num_pairs > 0 ? num_pairs : 1);
   const size_t terms = b * (size_t)(k + 1);
   const size_t n1 = (size_t)(num_nodes > 0 ? num_nodes : 1) + 1;
+  p.long_slots = (int64_t)(terms >> kLongShift) + 1;
   p.loss_partials = cv.take<double>((size_t)forward_blocks_for((int64_t)b));
   p.g = cv.take<float>(terms);
   p.rank = cv.take<uint32_t>(terms);
   p.cnt = cv.take<uint32_t>(n1);
   p.tile_sums = cv.take<uint32_t>((size_t)ceil_div((int64_t)n1, kScanTile));
   p.sorted = cv.take<Term>(terms);
+  p.long_acc = cv.take<float>((size_t)p.long_slots * (size_t)dim);
   p.stage_center = cv.take<int32_t>(b);
   p.stage_delta = cv.take<float>(b * (size_t)dim);
   p.bytes = cv.used;
   return p;
 }
 
-template <int VPL, int RB, int UB>
+template <typename T, int VPL, int RB, int UB>
 static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
   const int64_t n1 = a.num_nodes + 1;
   const int64_t tiles = ceil_div(n1, kScanTile);
-  sgns_clear_kernel<<<(unsigned)ceil_div(n1, 256), 256, 0, stream>>>(a.cnt, n1);
+  fill_u32_kernel<<<(unsigned)ceil_div(n1, 256), 256, 0, stream>>>(a.cnt, n1, 0u);
   GS_LAUNCH_CHECK();
-  const unsigned blocks = (unsigned)a.forward_blocks;
+  const int64_t long4 = a.long_slots * (int64_t)(a.dim >> 2);
+  fill_f32x4_kernel<<<(unsigned)ceil_div(long4, 256), 256, 0, stream>>>((float4*)a.long_acc, long4);
+  GS_LAUNCH_CHECK();
   const size_t idx_lds = (size_t)kGroupsPerBlock * kChunkPairs * (a.k + 2) * sizeof(int32_t);
-  sgns_forward_kernel<VPL, RB><<<(unsigned)(a.forward_blocks_per_xcd * 8), kSgnsThreads, idx_lds,
-                                stream>>>(a);
+  sgns_forward_kernel<T, VPL, RB><<<(unsigned)(a.forward_blocks_per_xcd * 8), kSgnsThreads, idx_lds,
+                                   stream>>>(a);
   GS_LAUNCH_CHECK();
   scan_reduce_kernel<<<(unsigned)tiles, kScanThreads, 0, stream>>>(a.cnt, n1, a.tile_sums);
   GS_LAUNCH_CHECK();
@@ -528,11 +691,22 @@ static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
   sgns_place_kernel<<<(unsigned)ceil_div(a.num_terms, 256), 256, 0, stream>>>(a);
   GS_LAUNCH_CHECK();
   const int64_t update_groups = ceil_div(a.num_terms, kSlice);
-  sgns_update_kernel<VPL, UB><<<(unsigned)ceil_div(update_groups, kGroupsPerBlock), kSgnsThreads, 0,
+  sgns_update_kernel<T, VPL, UB><<<(unsigned)ceil_div(update_groups, kGroupsPerBlock), kSgnsThreads, 0,
+                                  stream>>>(a);
+  GS_LAUNCH_CHECK();
+  sgns_long_rows_kernel<T><<<(unsigned)ceil_div(a.long_slots, kGroupsPerBlock), kSgnsThreads, 0,
                             stream>>>(a);
   GS_LAUNCH_CHECK();
-  const unsigned apply_blocks = blocks < 4096u ? blocks : 4096u;
-  sgns_apply_kernel<<<apply_blocks, kSgnsThreads, 0, stream>>>(a);
+  // the offsets are no longer needed: the same array now records, per centre,
+  // the lowest staging slot that holds it
+  fill_u32_kernel<<<(unsigned)ceil_div(n1, 256), 256, 0, stream>>>(a.cnt, n1, kNoOwner);
+  GS_LAUNCH_CHECK();
+  sgns_owner_kernel<<<(unsigned)ceil_div(a.num_pairs, 256), 256, 0, stream>>>(a);
+  GS_LAUNCH_CHECK();
+  const unsigned slot_blocks = (unsigned)ceil_div(a.num_pairs, kSgnsThreads);   // a slot per lane
+  sgns_merge_kernel<<<slot_blocks, kSgnsThreads, 0, stream>>>(a);
+  GS_LAUNCH_CHECK();
+  sgns_apply_kernel<T><<<slot_blocks, kSgnsThreads, 0, stream>>>(a);
   GS_LAUNCH_CHECK();
   sgns_finish_kernel<<<1, 256, 0, stream>>>(a.loss_partials, a.forward_blocks, a.loss_out);
   GS_LAUNCH_CHECK();
@@ -558,8 +732,9 @@ extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int3
                                 double* loss_sum_out, void* ws, size_t ws_bytes, void* stream_) {
   hipStream_t stream = (hipStream_t)stream_;
   if (!w_in || !w_out || num_nodes < 1 || num_nodes > (int64_t)INT32_MAX) return GS_EINVAL;
-  if (dim < 4 || dim > 1024 || (dim & 3) != 0) return GS_EINVAL;
-  if (dtype != GS_F32) return GS_EINVAL;   // bf16 tables: not built yet
+  if (dtype != GS_F32 && dtype != GS_BF16) return GS_EINVAL;
+  const int granule = (dtype == GS_BF16) ? 8 : 4;   // elements per 16-byte piece
+  if (dim < granule || dim > 1024 || (dim % granule) != 0) return GS_EINVAL;
   if (num_pairs < 0 || k < 0 || k > 60 || !loss_sum_out) return GS_EINVAL;
   if (num_pairs > 0 && (!centers || !contexts || (k > 0 && !negs))) return GS_EINVAL;
   if (num_pairs * (int64_t)(k + 1) > (int64_t)0x7fffffff) return GS_EOVERFLOW;
@@ -573,14 +748,15 @@ extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int3
     return GS_OK;
   }
   SgnsArgs a;
-  a.w_in = (float*)w_in;
-  a.w_out = (float*)w_out;
+  a.w_in = w_in;
+  a.w_out = w_out;
   a.centers = centers;
   a.contexts = contexts;
   a.negs = negs;
   a.num_pairs = num_pairs;
   a.num_nodes = num_nodes;
   a.num_terms = num_pairs * (int64_t)(k + 1);
+  a.long_slots = p.long_slots;
   a.k = k;
   a.dim = dim;
   a.lr = lr;
@@ -589,16 +765,25 @@ extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int3
   a.cnt = p.cnt;
   a.tile_sums = p.tile_sums;
   a.sorted = p.sorted;
+  a.long_acc = p.long_acc;
   a.stage_center = p.stage_center;
   a.stage_delta = p.stage_delta;
   a.loss_partials = p.loss_partials;
   a.forward_blocks = forward_blocks_for(num_pairs);
   a.forward_blocks_per_xcd = ceil_div(a.forward_blocks, 8);
   a.loss_out = loss_sum_out;
+  // float4 registers per lane for one row: 16 lanes x 4 floats = 64 elements each
   const int vpl = (dim + 63) / 64;
-  if (vpl <= 1) return launch_sgns<1, 6, 8>(a, stream);
-  if (vpl <= 2) return launch_sgns<2, 6, 8>(a, stream);
-  if (vpl <= 4) return launch_sgns<4, 3, 4>(a, stream);
-  if (vpl <= 8) return launch_sgns<8, 2, 2>(a, stream);
-  return launch_sgns<16, 1, 1>(a, stream);
+  if (dtype == GS_F32) {
+    if (vpl <= 1) return launch_sgns<float, 1, 6, 8>(a, stream);
+    if (vpl <= 2) return launch_sgns<float, 2, 6, 8>(a, stream);
+    if (vpl <= 4) return launch_sgns<float, 4, 3, 4>(a, stream);
+    if (vpl <= 8) return launch_sgns<float, 8, 2, 2>(a, stream);
+    return launch_sgns<float, 16, 1, 1>(a, stream);
+  }
+  // bf16: a 16-byte piece is 8 elements = two float4, so the register count is even
+  if (vpl <= 2) return launch_sgns<bf16_t, 2, 6, 8>(a, stream);
+  if (vpl <= 4) return launch_sgns<bf16_t, 4, 3, 4>(a, stream);
+  if (vpl <= 8) return launch_sgns<bf16_t, 8, 2, 2>(a, stream);
+  return launch_sgns<bf16_t, 16, 1, 1>(a, stream);
 }

@@ -369,3 +369,59 @@ def test_epoch_of_workload0(gs, oracle, cfg0):
         live = (na > 0) | (nb_ > 0)
         cos = (got[live] * want[live]).sum(1) / np.maximum(na[live] * nb_[live], 1e-30)
         assert cos.mean() >= 0.999
+
+
+# ----------------------------------------------------------------------------- SGNS, bf16 tables
+def _bf16_bits(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16).copy()
+
+
+@pytest.mark.parametrize("dim,k,b", [(256, 10, 30_011), (128, 5, 50_001), (64, 5, 9_999),
+                                     (192, 3, 5_000), (8, 1, 513)])
+def test_sgns_step_bf16_tables(gs, oracle, dim, k, b):
+    """bf16 storage, fp32 accumulation, one rounding per written element.
+
+    The oracle sums in fp64 and the kernels in fp32, so a sum that lands within
+    fp32 error of a bf16 rounding boundary may round the other way: all
+    elements must agree to within one bf16 step (or 1e-5 absolute where the
+    sum cancels), and all but a small fraction (1e-3) must be bit-identical."""
+    from paper_2407_15452_amd import inputs
+    n = 5000
+    f_in, f_out = inputs.random_tables(n, dim, seed=dim + k, scale=2.0 / dim ** 0.5)
+    b_in, b_out = f_in.to(torch.bfloat16), f_out.to(torch.bfloat16)
+    rng = np.random.default_rng(b)
+    c = np.repeat(rng.integers(0, n, b // 8 + 1), 8)[:b].astype(np.int32)
+    o = rng.integers(0, n, b).astype(np.int32)
+    neg = (n * rng.random((b, k)) ** 3).astype(np.int32)      # hub rows get thousands of terms
+    h_in, h_out = _bf16_bits(b_in), _bf16_bits(b_out)
+    before_in, before_out = h_in.copy(), h_out.copy()
+    want = oracle.sgns_step(h_in, h_out, c, o, neg, 0.025, dtype=oracle.BF16)
+    d_in, d_out = b_in.to(DEV), b_out.to(DEV)
+    loss = gs.gs_sgns_step(d_in, d_out, _t(c), _t(o), _t(neg), 0.025)
+    torch.cuda.synchronize()
+    assert abs(float(loss.item()) - want) <= LOSS_RTOL * abs(want)
+    for got_t, want_bits, before in ((d_in, h_in, before_in), (d_out, h_out, before_out)):
+        got_bits = _bf16_bits(got_t)
+        touched = want_bits != before
+        assert touched.any()
+        diff = got_bits != want_bits
+        assert diff.mean() <= 1e-3
+        # a differing element is the neighbouring bf16 value, or (after cancellation to a
+        # value far smaller than the operands) within the fp32 bound of 1e-5
+        gi, wi = got_bits.astype(np.int32), want_bits.astype(np.int32)
+        gv = (got_bits.astype(np.uint32) << 16).view(np.float32)
+        wv = (want_bits.astype(np.uint32) << 16).view(np.float32)
+        assert ((np.abs(gi - wi) <= 1) | (np.abs(gv - wv) <= EMB_ATOL))[diff].all()
+        # rows the batch does not name keep their bits
+        named = np.zeros(n, bool)
+        named[c] = True
+        named[o] = True
+        named[neg.ravel()] = True
+        np.testing.assert_array_equal(got_bits[~named], before[~named])
+
+
+def test_sgns_step_bf16_rejects_odd_dims(gs):
+    w = torch.zeros((10, 12), dtype=torch.bfloat16, device=DEV)
+    i = torch.zeros(4, dtype=torch.int32, device=DEV)
+    with pytest.raises(gs.GsError):
+        gs.gs_sgns_step(w, w.clone(), i, i, torch.zeros((4, 2), dtype=torch.int32, device=DEV), 0.1)
