@@ -6,11 +6,12 @@ walks (the step's share of the walk launch), pair emission (same), negative
 sampling and the SGNS iteration.  All inputs are synthetic, seeded and resident
 in HBM before the timed region.  Prints one JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 0..2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 0..4]
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -23,6 +24,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "sgns_step_hbm_traffic.json")
+SGNS_SOURCE = os.path.join(ROOT, "paper_2407_15452_amd", "csrc", "sgns.hip")
 
 
 def sgns_bytes_per_pair(k: int, dim: int, elem_bytes: int, window: int) -> float:
@@ -36,6 +39,18 @@ def sgns_bytes_per_pair(k: int, dim: int, elem_bytes: int, window: int) -> float
     centre = 4 * rb / (2 * window)
     idx = 2 * 4 * (k + 2) + 2 * 4 * (k + 1)
     return rows + centre + idx
+
+
+def measured_traffic(workload_name: str):
+    """HBM bytes per gs_sgns_step call from the committed rocprofv3 counter runs,
+    or None when there is none for this workload or the kernels have changed
+    since the counters were taken."""
+    try:
+        rec = json.load(open(TRAFFIC_FILE))[workload_name]
+        sha = hashlib.sha256(open(SGNS_SOURCE, "rb").read()).hexdigest()
+        return rec["hbm_bytes_per_call"] if rec["sgns_hip_sha256"] == sha else None
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def parse():
@@ -72,52 +87,62 @@ def main():
     wl = inputs.WORKLOADS[args.workload]
     if args.scale != 1.0:
         wl = wl.scaled(args.scale)
-    if wl.dtype != "f32" or wl.weighted:
-        print("bench.py: this workload needs parts of the path that are not built yet",
-              file=sys.stderr)
-        sys.exit(2)
     K, W = args.steps, args.warmup
     B, k, L, win = wl.batch_pairs, wl.num_neg, wl.walk_len, wl.window
+    elem_bytes = 2 if wl.dtype == "bf16" else 4
 
     # ------------------------------------------------------------------ setup (untimed)
     t0 = time.time()
     src, dst, w = inputs.edge_list(wl, dev)
     flags = gs.GS_DROP_SELF_LOOPS | gs.GS_DEDUPE | (0 if wl.directed else gs.GS_SYMMETRIZE)
     g = gs.gs_csr_build(src, dst, w, wl.num_nodes, flags, wl.offset_bits)
-    del src, dst
+    del src, dst, w
     torch.cuda.synchronize()
+    torch.cuda.empty_cache()
     log(f"[setup] graph {wl.name}: N={wl.num_nodes} entries={g.num_entries} "
         f"({time.time() - t0:.1f}s)")
     t0 = time.time()
+    row_alias = gs.gs_alias_build(g.offsets, g.weights) if wl.weighted else None
     noise_w = inputs.noise_weights(g.offsets)
     seg = torch.tensor([0, wl.num_nodes], dtype=torch.int64, device=dev)
     noise = gs.gs_alias_build(seg, noise_w)
     torch.cuda.synchronize()
-    log(f"[setup] noise alias table ({time.time() - t0:.1f}s)")
-    w_in, w_out = inputs.init_tables(wl.num_nodes, wl.dim, wl.init_seed, dev)
+    torch.cuda.empty_cache()
+    log(f"[setup] alias tables ({time.time() - t0:.1f}s)")
     # a lived-in context table (zero rows would make the first updates trivial)
-    w_out.copy_(inputs.init_tables(wl.num_nodes, wl.dim, wl.init_seed + 1, dev)[0])
+    w_in, w_out = inputs.init_tables(wl.num_nodes, wl.dim, wl.init_seed, dev, wl.dtype,
+                                     context_seed=wl.init_seed + 1)
+    torch.cuda.empty_cache()
 
-    # walks needed: only starts with out-edges yield pairs (undirected: such walks never die)
+    if wl.node2vec:
+        def walk_fn(st, base, out=None):
+            return gs.gs_node2vec_walk(g, row_alias, st, L, wl.p, wl.q, wl.walk_seed, base, out)
+    else:
+        def walk_fn(st, base, out=None):
+            return gs.gs_random_walk(g, row_alias, st, L, wl.walk_seed, base, out)
+
+    # Walks needed per batch.  Undirected: a walk from a node with edges never
+    # dies, so the yield is exact.  Directed: measured on a probe launch.
     P = inputs.pairs_per_full_walk(L, win)
     live = (g.offsets[1:] > g.offsets[:-1])
     live_frac = float(live.float().mean().item())
+    if wl.directed:
+        probe = inputs.walk_starts(wl.num_nodes, 0, 200_000, dev)
+        _, _, n_probe = gs.gs_make_pairs(walk_fn(probe, 0), win)
+        pairs_per_walk = max(n_probe / probe.numel(), 1e-3)
+        del probe
+    else:
+        pairs_per_walk = P * live_frac
     total_steps = W + K
 
     def walks_for(pairs_needed, first_walk):
-        """Smallest count so that walks [first, first+count) yield >= pairs_needed pairs."""
-        need_live = -(-pairs_needed // P)
-        count = int(need_live / max(live_frac, 1e-3) * 1.05) + 64
+        """Starts of a walk range that yields at least `pairs_needed` pairs."""
+        count = int(pairs_needed / pairs_per_walk * 1.05) + 64
         while True:
             st = inputs.walk_starts(wl.num_nodes, first_walk, count, dev)
-            if int(live[st.long()].sum().item()) >= need_live:
+            if wl.directed or int(live[st.long()].sum().item()) * P >= pairs_needed:
                 return st
-            count = int(count * 1.2) + 64
-
-    walk_fn = (lambda st, base, out=None: gs.gs_node2vec_walk(g, None, st, L, wl.p, wl.q,
-                                                              wl.walk_seed, base, out)) \
-        if wl.node2vec else (lambda st, base, out=None: gs.gs_random_walk(g, None, st, L,
-                                                                          wl.walk_seed, base, out))
+            count = int(count * 1.3) + 64
 
     starts_warm = walks_for(max(W, 1) * B, 0)
     starts_timed = walks_for(K * B, starts_warm.numel())
@@ -130,8 +155,9 @@ def main():
     pairs_ws = torch.empty(max(256, gs.lib().gs_make_pairs_workspace_bytes(n_max)),
                            dtype=torch.uint8, device=dev)
     negs = torch.empty((B, k), dtype=torch.int32, device=dev)
-    sgns_ws = torch.empty(gs.gs_sgns_step_workspace_bytes(B, wl.num_nodes, k, wl.dim), dtype=torch.uint8,
-                          device=dev)
+    sgns_dtype = gs.GS_BF16 if wl.dtype == "bf16" else gs.GS_F32
+    sgns_ws = torch.empty(gs.gs_sgns_step_workspace_bytes(B, wl.num_nodes, k, wl.dim, sgns_dtype),
+                          dtype=torch.uint8, device=dev)
     losses = torch.zeros(total_steps, dtype=torch.float64, device=dev)
     lr = inputs.learning_rate(wl, 0, 1)
     ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
@@ -186,7 +212,7 @@ def main():
     walk_ms = stage_events["walk0"].elapsed_time(stage_events["walk1"])
     pairs_ms = stage_events["walk1"].elapsed_time(stage_events["pairs1"])
     mean_loss = float(losses[W:].sum().item()) / (K * B)
-    bpp = sgns_bytes_per_pair(k, wl.dim, 4, win)
+    bpp = sgns_bytes_per_pair(k, wl.dim, elem_bytes, win)
     achieved = B * bpp / (sgns_ms * 1e-3) / 1e9
 
     # ------------------------------------------------------------------ stand-alone walk throughput
@@ -205,67 +231,85 @@ def main():
     walk_steps_per_s = valid_steps / (walk_big_ms * 1e-3)
     del big
 
+    walk_kind = ("node2vec p=%g q=%g" % (wl.p, wl.q)) if wl.node2vec else "first-order"
+    walk_kind += ", alias-weighted" if wl.weighted else ", uniform"
     result = {
         "metric": "SGNS positive pairs/sec + walk steps/sec; % of MI355X HBM peak",
         "value": pairs_per_s,
         "unit": "positive pairs/s (whole path: walks, pairs, negatives, SGNS step)",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32" if wl.dtype == "f32" else "bf16 storage, f32 arithmetic",
+        "data": "synthetic",
         "config": {"workload": wl.name, "num_nodes": wl.num_nodes, "csr_entries": g.num_entries,
-                   "batch_pairs": B, "negatives": k, "dim": wl.dim, "walk_len": L, "window": win,
-                   "walk": "node2vec p=%g q=%g" % (wl.p, wl.q) if wl.node2vec else "uniform",
-                   "lr": lr, "live_start_fraction": live_frac},
+                   "offset_bits": wl.offset_bits, "batch_pairs": B, "negatives": k, "dim": wl.dim,
+                   "walk_len": L, "window": win, "walk": walk_kind, "lr": lr,
+                   "live_start_fraction": live_frac},
         "walk_steps_per_s": walk_steps_per_s,
         "walk_launch": {"walks": nws, "valid_steps": valid_steps, "ms": walk_big_ms},
         "stages_ms": {"walk_chunk": walk_ms, "pairs_chunk": pairs_ms, "sgns_step_mean": sgns_ms,
                       "chunk_walks": int(starts_timed.numel())},
         "mean_loss_per_pair": mean_loss,
-        "roofline": {"bound": "hbm", "kernel": "gs_sgns_step (forward + scatter + apply kernels)",
+        "roofline": {"bound": "hbm", "kernel": "gs_sgns_step (all kernels of one call)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "bytes_per_pair": bpp, "traffic": None},
+                     "frac": achieved / HBM_PEAK_GBS, "bytes_per_pair": bpp,
+                     "traffic": measured_traffic(wl.name)},
     }
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, g, noise_w, w_in, w_out, lr)
+        result["cpu_baseline"] = cpu_baseline(wl, g, row_alias, noise, w_in, w_out, lr)
     print(json.dumps(result), flush=True)
 
 
-def cpu_baseline(wl, g, noise_w, w_in, w_out, lr, target_pairs=2_000_000):
+def cpu_baseline(wl, g, row_alias, noise, w_in, w_out, lr, target_pairs=2_000_000):
     """The CPU reference, as it stands, on a bounded sample of the same workload
-    (single thread): walks for the sample, pairs, negatives, one SGNS iteration."""
+    (single thread): walks for the sample, pairs, negatives, one SGNS iteration.
+    The SGNS iteration runs on a compacted copy of the rows the sample names
+    (an iteration touches no other row), so the tables need not fit on the host."""
     import oracle
     oracle.build()
+    from paper_2407_15452_amd import inputs
     off = g.offsets.cpu().numpy()
     nb = g.nbrs.cpu().numpy()
-    h_in = w_in.cpu().numpy()
-    h_out = w_out.cpu().numpy()
-    P = (2 * wl.window * wl.walk_len - wl.window * (wl.window + 1))
-    deg = np.diff(off)
-    live_frac = float((deg > 0).mean())
+    table = None if row_alias is None else (row_alias.prob.cpu().numpy(),
+                                            row_alias.alias.cpu().numpy())
+    noise_t = (noise.prob.cpu().numpy(), noise.alias.cpu().numpy())
+    P = inputs.pairs_per_full_walk(wl.walk_len, wl.window)
+    live_frac = float((np.diff(off) > 0).mean())
     nw = int(target_pairs / P / max(live_frac, 1e-3)) + 8
-    from paper_2407_15452_amd import inputs
     starts = inputs.walk_starts(wl.num_nodes, 0, nw).numpy()
-    seg = np.array([0, wl.num_nodes], dtype=np.int64)
-    table = oracle.alias_build(seg, noise_w.cpu().numpy())      # setup, untimed like on the GPU
     t0 = time.perf_counter()
     if wl.node2vec:
-        walks = oracle.node2vec_walk(off, nb, starts, wl.walk_len, wl.p, wl.q, wl.walk_seed)
+        walks = oracle.node2vec_walk(off, nb, starts, wl.walk_len, wl.p, wl.q, wl.walk_seed,
+                                     alias=table)
     else:
-        walks = oracle.random_walk(off, nb, starts, wl.walk_len, wl.walk_seed)
+        walks = oracle.random_walk(off, nb, starts, wl.walk_len, wl.walk_seed, alias=table)
     t1 = time.perf_counter()
     c, o = oracle.make_pairs(walks, wl.window)
-    neg = oracle.sample_negatives(table, wl.num_nodes, c.size, wl.num_neg, wl.neg_seed)
+    neg = oracle.sample_negatives(noise_t, wl.num_nodes, c.size, wl.num_neg, wl.neg_seed)
     t2 = time.perf_counter()
-    oracle.sgns_step(h_in, h_out, c, o, neg, lr)
+    # compact the named rows (untimed: it stands for tables that are already resident)
+    ids, inv = np.unique(np.concatenate([c, o, neg.ravel()]), return_inverse=True)
+    inv = inv.astype(np.int32)
+    cc, oo, nn = inv[:c.size], inv[c.size:2 * c.size], inv[2 * c.size:].reshape(neg.shape)
+    sel = torch.as_tensor(ids, dtype=torch.long, device=w_in.device)
+    if wl.dtype == "bf16":
+        h_in = w_in[sel].view(torch.int16).cpu().numpy().view(np.uint16).copy()
+        h_out = w_out[sel].view(torch.int16).cpu().numpy().view(np.uint16).copy()
+        dt = oracle.BF16
+    else:
+        h_in, h_out, dt = w_in[sel].cpu().numpy(), w_out[sel].cpu().numpy(), oracle.F32
     t3 = time.perf_counter()
+    oracle.sgns_step(h_in, h_out, cc, oo, nn, lr, dtype=dt)
+    t4 = time.perf_counter()
     steps = int((walks[:, 1:] >= 0).sum())
-    return {"value": c.size / (t3 - t0), "unit": "positive pairs/s (whole path)", "cores": 1,
+    secs = (t2 - t0) + (t4 - t3)
+    return {"value": c.size / secs, "unit": "positive pairs/s (whole path)", "cores": 1,
             "kind": "oracle",
             "sample": f"{nw} walks -> {c.size} pairs of {wl.name}, one SGNS iteration over them",
             "walk_steps_per_s": steps / max(t1 - t0, 1e-9),
-            "sgns_pairs_per_s": c.size / max(t3 - t2, 1e-9),
-            "seconds": t3 - t0, "host_cpus": os.cpu_count()}
+            "sgns_pairs_per_s": c.size / max(t4 - t3, 1e-9),
+            "seconds": secs, "host_cpus": os.cpu_count()}
 
 
 if __name__ == "__main__":

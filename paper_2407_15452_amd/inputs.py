@@ -170,12 +170,14 @@ def rmat_edge_list(wl: Workload, device="cpu", chunk: int = 1 << 24):
         cnt = min(chunk, want - first)
         s, d = rmat_candidates(n, first, cnt, wl.graph_seed, device)
         ok = (s < n) & (d < n) & (s != d)
-        srcs.append(s[ok])
-        dsts.append(d[ok])
+        srcs.append(perm[s[ok]].to(torch.int32))
+        dsts.append(perm[d[ok]].to(torch.int32))
     s = torch.cat(srcs)
+    del srcs
     d = torch.cat(dsts)
+    del dsts
     if exact:
-        key = torch.minimum(s, d) * n + torch.maximum(s, d)
+        key = torch.minimum(s, d).long() * n + torch.maximum(s, d).long()
         uniq, inv = torch.unique(key, return_inverse=True)
         pos = torch.arange(key.numel(), dtype=torch.int64, device=key.device)
         first_pos = torch.full((uniq.numel(),), key.numel(), dtype=torch.int64, device=key.device)
@@ -184,7 +186,7 @@ def rmat_edge_list(wl: Workload, device="cpu", chunk: int = 1 << 24):
         if keep.numel() < wl.num_edges:
             raise RuntimeError("not enough distinct R-MAT edges; raise the candidate factor")
         s, d = s[keep], d[keep]
-    return perm[s].to(torch.int32), perm[d].to(torch.int32)
+    return s, d
 
 
 def _zipf_rank(u: torch.Tensor, n: int, s: float) -> torch.Tensor:
@@ -196,26 +198,39 @@ def _zipf_rank(u: torch.Tensor, n: int, s: float) -> torch.Tensor:
     return torch.clamp(x.floor().to(torch.int64) - 1, 0, n - 1)
 
 
-def bipartite_edge_list(wl: Workload, device="cpu", chunk: int = 1 << 24):
+def bipartite_edge_list(wl: Workload, device="cpu", chunk: int = 1 << 24, max_rounds: int = 8):
     """Weighted user-item interactions: endpoints drawn independently with
-    Zipf(1.1) user ranks and Zipf(0.9) item ranks, weights lognormal(0, 1).
-    Users are nodes [0, num_users), items [num_users, num_nodes); both id
-    ranges are relabelled.  Duplicates are left in for CSR construction."""
+    Zipf(1.1) user ranks and Zipf(0.9) item ranks.  The product of two Zipf laws
+    repeats its popular pairs heavily, so draws are made in rounds and
+    de-duplicated until at least 95 % of `num_edges` distinct interactions
+    exist (the realised count is what the benchmark reports).  The weight of an
+    interaction is lognormal(0, 1) hashed from its (user, item) key.  Users are
+    nodes [0, num_users), items [num_users, num_nodes); both id ranges are
+    relabelled.  The list comes out sorted by (user, item)."""
     nu, ni = wl.num_users, wl.num_items
     pu = _relabel(nu, wl.graph_seed, device)
     pi = _relabel(ni, wl.graph_seed + 1, device)
-    srcs, dsts, ws = [], [], []
-    for first in range(0, wl.num_edges, chunk):
-        cnt = min(chunk, wl.num_edges - first)
-        e = torch.arange(first, first + cnt, dtype=torch.int64, device=device)
-        user = pu[_zipf_rank(hashed_unit(wl.graph_seed, e, 2), nu, 1.1)]
-        item = pi[_zipf_rank(hashed_unit(wl.graph_seed, e, 3), ni, 0.9)] + nu
-        z = torch.sqrt(-2.0 * torch.log(hashed_unit(wl.graph_seed, e, 4))) * \
-            torch.cos(2.0 * math.pi * hashed_unit(wl.graph_seed, e, 5))
-        srcs.append(user.to(torch.int32))
-        dsts.append(item.to(torch.int32))
-        ws.append(torch.exp(z).to(torch.float32))
-    return torch.cat(srcs), torch.cat(dsts), torch.cat(ws)
+    keys = torch.empty(0, dtype=torch.int64, device=device)
+    drawn = 0
+    for _ in range(max_rounds):
+        if keys.numel() >= 0.95 * wl.num_edges:
+            break
+        todo = max(1024, int((wl.num_edges - keys.numel()) * 1.6))
+        parts = [keys]
+        for first in range(drawn, drawn + todo, chunk):
+            cnt = min(chunk, drawn + todo - first)
+            e = torch.arange(first, first + cnt, dtype=torch.int64, device=device)
+            user = pu[_zipf_rank(hashed_unit(wl.graph_seed, e, 2), nu, 1.1)]
+            item = pi[_zipf_rank(hashed_unit(wl.graph_seed, e, 3), ni, 0.9)]
+            parts.append(torch.unique(user * ni + item))
+        drawn += todo
+        keys = torch.unique(torch.cat(parts))
+        del parts
+    user = torch.div(keys, ni, rounding_mode="floor")
+    item = keys - user * ni + nu
+    z = torch.sqrt(-2.0 * torch.log(hashed_unit(wl.graph_seed, keys, 4))) * \
+        torch.cos(2.0 * math.pi * hashed_unit(wl.graph_seed, keys, 5))
+    return user.to(torch.int32), item.to(torch.int32), torch.exp(z).to(torch.float32)
 
 
 def edge_list(wl: Workload, device="cpu"):
@@ -245,18 +260,30 @@ def noise_weights(offsets: torch.Tensor) -> torch.Tensor:
     return torch.from_numpy(w).to(offsets.device)
 
 
-def init_tables(num_nodes: int, dim: int, seed: int, device="cpu", dtype: str = "f32",
-                chunk_rows: int = 1 << 20):
-    """Input table U(-0.5/dim, 0.5/dim) (24-bit uniforms), context table zero."""
-    w_in = torch.empty((num_nodes, dim), dtype=torch.float32, device=device)
-    for r0 in range(0, num_nodes, chunk_rows):
-        r1 = min(num_nodes, r0 + chunk_rows)
-        idx = torch.arange(r0 * dim, r1 * dim, dtype=torch.int64, device=device)
+def _fill_uniform(table: torch.Tensor, seed: int, half_width: float, chunk_rows: int = 1 << 20):
+    """table[r, e] = (u - 0.5) * 2 * half_width, u a 24-bit hashed uniform of (seed, r, e)."""
+    n, dim = table.shape
+    for r0 in range(0, n, chunk_rows):
+        r1 = min(n, r0 + chunk_rows)
+        idx = torch.arange(r0 * dim, r1 * dim, dtype=torch.int64, device=table.device)
         bits = hashed_u32(seed, idx, 9) >> 8
-        w_in[r0:r1] = ((bits.to(torch.float32) * (1.0 / 16777216.0) - 0.5) / dim).view(-1, dim)
-    w_out = torch.zeros((num_nodes, dim), dtype=torch.float32, device=device)
-    if dtype == "bf16":
-        return w_in.to(torch.bfloat16), w_out.to(torch.bfloat16)
+        vals = (bits.to(torch.float32) * (1.0 / 16777216.0) - 0.5) * (2.0 * half_width)
+        table[r0:r1] = vals.view(-1, dim).to(table.dtype)
+
+
+def init_tables(num_nodes: int, dim: int, seed: int, device="cpu", dtype: str = "f32",
+                context_seed: int | None = None):
+    """Input table U(-0.5/dim, 0.5/dim) (24-bit uniforms; exact in fp32 for
+    power-of-two dims), context table zero -- or, with `context_seed`, filled
+    the same way from that seed (a lived-in table for throughput runs)."""
+    tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+    w_in = torch.empty((num_nodes, dim), dtype=tdtype, device=device)
+    _fill_uniform(w_in, seed, 0.5 / dim)
+    if context_seed is None:
+        w_out = torch.zeros((num_nodes, dim), dtype=tdtype, device=device)
+    else:
+        w_out = torch.empty((num_nodes, dim), dtype=tdtype, device=device)
+        _fill_uniform(w_out, context_seed, 0.5 / dim)
     return w_in, w_out
 
 

@@ -425,3 +425,92 @@ def test_sgns_step_bf16_rejects_odd_dims(gs):
     i = torch.zeros(4, dtype=torch.int32, device=DEV)
     with pytest.raises(gs.GsError):
         gs.gs_sgns_step(w, w.clone(), i, i, torch.zeros((4, 2), dtype=torch.int32, device=DEV), 0.1)
+
+
+# ----------------------------------------------------------------------------- workloads 3 and 4, scaled down
+def _pipeline_parity(gs, oracle, wl, num_walks, loss_rtol=LOSS_RTOL):
+    """Whole path on a (scaled) workload: every stage against the oracle."""
+    from paper_2407_15452_amd import inputs
+    src, dst, w = inputs.edge_list(wl, "cpu")
+    flags = oracle.DROP_SELF_LOOPS | oracle.DEDUPE | (0 if wl.directed else oracle.SYMMETRIZE)
+    hw = None if w is None else w.numpy()
+    off, nb, wo = oracle.csr_build(src.numpy(), dst.numpy(), hw, wl.num_nodes, flags, wl.offset_bits)
+    g = gs.gs_csr_build(src.to(DEV), dst.to(DEV), None if w is None else w.to(DEV), wl.num_nodes,
+                        flags, wl.offset_bits)
+    np.testing.assert_array_equal(g.offsets.cpu().numpy(), off)
+    np.testing.assert_array_equal(g.nbrs.cpu().numpy(), nb)
+    table = d_table = None
+    if wl.weighted:
+        np.testing.assert_array_equal(g.weights.cpu().numpy(), wo)
+        table = oracle.alias_build(off, wo)
+        d_table = gs.gs_alias_build(g.offsets, g.weights)
+        np.testing.assert_array_equal(d_table.prob.cpu().numpy(), table[0])
+        np.testing.assert_array_equal(d_table.alias.cpu().numpy(), table[1])
+    starts = inputs.walk_starts(wl.num_nodes, 0, num_walks)
+    if wl.node2vec:
+        walks = oracle.node2vec_walk(off, nb, starts.numpy(), wl.walk_len, wl.p, wl.q, wl.walk_seed,
+                                     alias=table)
+        d_walks = gs.gs_node2vec_walk(g, d_table, starts.to(DEV), wl.walk_len, wl.p, wl.q,
+                                      wl.walk_seed)
+    else:
+        walks = oracle.random_walk(off, nb, starts.numpy(), wl.walk_len, wl.walk_seed, alias=table)
+        d_walks = gs.gs_random_walk(g, d_table, starts.to(DEV), wl.walk_len, wl.walk_seed)
+    np.testing.assert_array_equal(d_walks.cpu().numpy(), walks)
+    oc, oo = oracle.make_pairs(walks, wl.window)
+    dc, do, n_pairs = gs.gs_make_pairs(d_walks, wl.window)
+    np.testing.assert_array_equal(dc.cpu().numpy(), oc)
+    np.testing.assert_array_equal(do.cpu().numpy(), oo)
+    noise_w = inputs.noise_weights(torch.as_tensor(off))
+    seg = np.array([0, wl.num_nodes], dtype=np.int64)
+    noise_t = oracle.alias_build(seg, noise_w.numpy())
+    noise = gs.gs_alias_build(_t(seg), noise_w.to(DEV))
+    b = min(n_pairs, 40_000)
+    oneg = oracle.sample_negatives(noise_t, wl.num_nodes, b, wl.num_neg, wl.neg_seed)
+    dneg = gs.gs_sample_negatives(noise, wl.num_nodes, b, wl.num_neg, wl.neg_seed)
+    np.testing.assert_array_equal(dneg.cpu().numpy(), oneg)
+    f_in, f_out = inputs.random_tables(wl.num_nodes, wl.dim, seed=9, scale=2.0 / wl.dim ** 0.5)
+    if wl.dtype == "bf16":
+        b_in, b_out = f_in.to(torch.bfloat16), f_out.to(torch.bfloat16)
+        h_in, h_out = _bf16_bits(b_in), _bf16_bits(b_out)
+        want = oracle.sgns_step(h_in, h_out, oc[:b], oo[:b], oneg, 0.025, dtype=oracle.BF16)
+        d_in, d_out = b_in.to(DEV), b_out.to(DEV)
+        loss = gs.gs_sgns_step(d_in, d_out, dc[:b], do[:b], dneg, 0.025)
+        assert abs(float(loss.item()) - want) <= loss_rtol * abs(want)
+        for got_t, want_bits in ((d_in, h_in), (d_out, h_out)):
+            got_bits = _bf16_bits(got_t)
+            diff = got_bits != want_bits
+            assert diff.mean() <= 1e-3
+            gv = (got_bits.astype(np.uint32) << 16).view(np.float32)
+            wv = (want_bits.astype(np.uint32) << 16).view(np.float32)
+            near = np.abs(got_bits.astype(np.int32) - want_bits.astype(np.int32)) <= 1
+            assert (near | (np.abs(gv - wv) <= EMB_ATOL))[diff].all()
+    else:
+        _sgns_case(gs, oracle, f_in, f_out, oc[:b], oo[:b], oneg, 0.025)
+    return walks
+
+
+def test_workload3_scaled_weighted_bipartite_bf16(gs, oracle):
+    from paper_2407_15452_amd import inputs
+    wl = inputs.WORKLOADS[3].scaled(1e-3)
+    assert wl.weighted and wl.dtype == "bf16" and wl.num_neg == 10 and wl.dim == 256
+    walks = _pipeline_parity(gs, oracle, wl, 3000)
+    # bipartite: users and items alternate along every walk
+    nu = wl.num_users
+    live = walks[:, 1] >= 0
+    assert live.any()
+    side = walks[live][:, :2] >= nu
+    assert (side[:, 0] != side[:, 1]).all()
+
+
+def test_workload4_scaled_directed_int64_offsets(gs, oracle):
+    from paper_2407_15452_amd import inputs
+    wl = inputs.WORKLOADS[4].scaled(1e-3)
+    assert wl.directed and wl.offset_bits == 64
+    walks = _pipeline_parity(gs, oracle, wl, 20_000)
+    assert (walks == -1).any()                 # directed R-MAT: walks do end at sinks
+
+
+def test_workload2_scaled_node2vec(gs, oracle):
+    from paper_2407_15452_amd import inputs
+    wl = inputs.WORKLOADS[2].scaled(5e-3)
+    _pipeline_parity(gs, oracle, wl, 2_000)
