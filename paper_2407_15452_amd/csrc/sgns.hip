@@ -79,6 +79,7 @@ struct SgnsArgs {
   double* loss_partials;    // [forward blocks]
   int64_t forward_blocks;
   int64_t forward_blocks_per_xcd;
+  int32_t update_lds_bytes; // LDS for the block-level sum of long-row partials (0: not used)
   double* loss_out;
 };
 
@@ -455,13 +456,14 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
   T* w_out = static_cast<T*>(a.w_out);
   const int l16 = threadIdx.x & (kGroupLanes - 1);
   const int64_t group = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
+  const int group_in_block = threadIdx.x / kGroupLanes;
   const int64_t slice_begin = group * kSlice;
-  if (slice_begin >= a.num_terms) return;
+  const bool active = slice_begin < a.num_terms;
   const int64_t slice_end = min(slice_begin + kSlice, a.num_terms);
   const Term* __restrict__ sorted = a.sorted;
 
-  int64_t begin = slice_begin, end = slice_end;
-  {
+  int64_t begin = slice_begin, end = active ? slice_end : slice_begin;
+  if (active) {
     const uint32_t w0 = sorted[slice_begin].where;
     const uint32_t len0 = w0 & 0xffffu, pos0 = w0 >> 16;
     if (len0 <= kLongRow && pos0 > 0) begin = slice_begin - pos0 + len0;   // owned by an earlier group
@@ -531,7 +533,42 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
       }
     }
   }
-  if (cur_row >= 0) flush();
+  // Last pending row of this group.  Groups of a block hold consecutive slices,
+  // so a row with very many terms is pending in many of them at once: their
+  // partial sums are added up in LDS first and leave the block as one update
+  // of the side buffer (16 times fewer atomics on the hottest rows).
+  const bool pending_long = cur_row >= 0 && cur_long;
+  if (cur_row >= 0 && !cur_long) flush();
+  if (a.update_lds_bytes == 0) {          // rows too wide for the LDS stage
+    if (pending_long) flush();
+    return;
+  }
+  extern __shared__ float comb_s[];       // [kGroupsPerBlock][dim] partial sums, then the row ids
+  int32_t* comb_row = reinterpret_cast<int32_t*>(comb_s + kGroupsPerBlock * a.dim);
+  if (l16 == 0) comb_row[group_in_block] = pending_long ? cur_row : -1;
+  if (pending_long) {
+    float4* mine = reinterpret_cast<float4*>(comb_s + group_in_block * a.dim);
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      const int q = natural_q<T>(v, l16);
+      if (q < dim4) mine[q] = acc[v];
+    }
+  }
+  __syncthreads();
+  if (pending_long && (group_in_block == 0 || comb_row[group_in_block - 1] != cur_row)) {
+    for (int g2 = group_in_block + 1; g2 < kGroupsPerBlock && comb_row[g2] == cur_row; ++g2) {
+      const float4* other = reinterpret_cast<const float4*>(comb_s + g2 * a.dim);
+#pragma unroll
+      for (int v = 0; v < VPL; ++v) {
+        const int q = natural_q<T>(v, l16);
+        if (q < dim4) {
+          const float4 o = other[q];
+          acc[v].x += o.x; acc[v].y += o.y; acc[v].z += o.z; acc[v].w += o.w;
+        }
+      }
+    }
+    flush();
+  }
 }
 
 // element-wise row helpers for the small follow-up kernels (natural order)
@@ -691,8 +728,8 @@ static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
   sgns_place_kernel<<<(unsigned)ceil_div(a.num_terms, 256), 256, 0, stream>>>(a);
   GS_LAUNCH_CHECK();
   const int64_t update_groups = ceil_div(a.num_terms, kSlice);
-  sgns_update_kernel<T, VPL, UB><<<(unsigned)ceil_div(update_groups, kGroupsPerBlock), kSgnsThreads, 0,
-                                  stream>>>(a);
+  sgns_update_kernel<T, VPL, UB><<<(unsigned)ceil_div(update_groups, kGroupsPerBlock), kSgnsThreads,
+                                  (size_t)a.update_lds_bytes, stream>>>(a);
   GS_LAUNCH_CHECK();
   sgns_long_rows_kernel<T><<<(unsigned)ceil_div(a.long_slots, kGroupsPerBlock), kSgnsThreads, 0,
                             stream>>>(a);
@@ -771,6 +808,7 @@ extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int3
   a.loss_partials = p.loss_partials;
   a.forward_blocks = forward_blocks_for(num_pairs);
   a.forward_blocks_per_xcd = ceil_div(a.forward_blocks, 8);
+  a.update_lds_bytes = dim <= 512 ? kGroupsPerBlock * dim * (int)sizeof(float) + 64 : 0;
   a.loss_out = loss_sum_out;
   // float4 registers per lane for one row: 16 lanes x 4 floats = 64 elements each
   const int vpl = (dim + 63) / 64;
