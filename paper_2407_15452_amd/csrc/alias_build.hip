@@ -2,7 +2,8 @@
 // first-out construction order stated in gs.h (Walker 1977 / Vose 1991).
 // The order of the fp64 operations is part of the definition of the table, so
 // each segment is built sequentially by one lane; parallelism is across
-// segments (per-row tables of a weighted graph).
+// segments (per-row tables of a weighted graph).  A single long segment (the
+// noise table) is built by one workgroup instead, see alias_build_long_kernel.
 #include "common.h"
 
 namespace gs {
@@ -72,6 +73,169 @@ __global__ __launch_bounds__(64) void alias_build_kernel(const OffT* __restrict_
   }
 }
 
+// ---------------------------------------------------------------------------
+// One long segment (the noise table): the same construction, same order, run by
+// one workgroup of 1024 lanes.
+//
+// The sequential loop pairs the oldest small with the oldest large and appends
+// the large to the back of one of the two lists.  If both lists hold at least m
+// entries, the next m iterations use exactly the first m entries of each list
+// as they stand now (appends go to the back), touch 2m distinct entries, and
+// are independent of each other: they can run side by side, and appending
+// their larges in iteration order (a prefix sum over the "became small" flags)
+// leaves both lists exactly as the sequential loop would.  So the workgroup
+// advances in rounds of m = min(|small|, |large|) iterations; when m is small
+// (a few very heavy entries left) lane 0 runs the plain loop instead.
+// S is still the index-order fp64 sum: lanes stage 1024 weights in LDS, lane 0
+// adds them one by one.
+// ---------------------------------------------------------------------------
+constexpr int kLongThreads = 1024;
+constexpr int64_t kLongSegment = 8192;      // single segments at least this long use the workgroup
+constexpr int kSerialBelow = 64;            // rounds narrower than this are run by lane 0
+
+// loads that must see what other lanes of the workgroup stored earlier (bypass the L1)
+__device__ __forceinline__ int32_t ld_i32(const int32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double ld_f64(const double* p) {
+  return __longlong_as_double((long long)__hip_atomic_load(
+      reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+
+// Ranks of the set flags among the 1024 lanes, in lane order, and their total.
+__device__ __forceinline__ void block_rank(bool flag, uint32_t* wave_tot, int& rank, int& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint64_t votes = __ballot(flag);
+  const int before = __popcll(votes & ((1ull << lane) - 1ull));
+  if (lane == 0) wave_tot[wave] = (uint32_t)__popcll(votes);
+  __syncthreads();
+  int base = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < kLongThreads / 64; ++w) {
+    const int c = (int)wave_tot[w];
+    if (w < wave) base += c;
+    all += c;
+  }
+  __syncthreads();
+  rank = base + before;
+  total = all;
+}
+
+template <typename OffT>
+__global__ __launch_bounds__(kLongThreads) void alias_build_long_kernel(
+    const OffT* __restrict__ seg_offsets, const float* __restrict__ weights,
+    float* __restrict__ prob_out, int32_t* __restrict__ alias_out, double* mass,
+    int32_t* small_q /* n */, int32_t* large_q /* 2n */) {
+#pragma clang fp contract(off)  // every fp64 operation below must round on its own
+  __shared__ double tile_s[kLongThreads];
+  __shared__ uint32_t wave_tot[kLongThreads / 64];
+  __shared__ double S_s;
+  __shared__ int64_t q_s[4];                  // small head/tail, large head/tail after a serial stretch
+  const int tid = threadIdx.x;
+  const int64_t begin = (int64_t)seg_offsets[0];
+  const int64_t n = (int64_t)seg_offsets[1] - begin;
+  if (n <= 0) return;
+  const float* w = weights + begin;
+  float* prob = prob_out + begin;
+  int32_t* alias = alias_out + begin;
+
+  // S: index-order sum
+  double run = 0.0;
+  for (int64_t base = 0; base < n; base += kLongThreads) {
+    tile_s[tid] = (base + tid < n) ? (double)w[base + tid] : 0.0;
+    __syncthreads();
+    if (tid == 0) {
+      const int cnt = (int)min((int64_t)kLongThreads, n - base);
+      for (int k = 0; k < cnt; ++k) run += tile_s[k];
+    }
+    __syncthreads();
+  }
+  if (tid == 0) S_s = run;
+  __syncthreads();
+  const double S = S_s;
+  const double dn = (double)n;
+
+  // initial lists, in index order
+  int64_t sh = 0, st = 0, lh = 0, lt = 0;     // heads and tails, identical in every lane
+  for (int64_t base = 0; base < n; base += kLongThreads) {
+    const int64_t i = base + tid;
+    const bool valid = i < n;
+    double m = 0.0;
+    if (valid) { m = (double)w[i] * dn; mass[i] = m; }
+    const bool is_small = valid && m < S;
+    int rs, ts, rl, tl;
+    block_rank(is_small, wave_tot, rs, ts);
+    block_rank(valid && !is_small, wave_tot, rl, tl);
+    if (is_small) small_q[st + rs] = (int32_t)i;
+    else if (valid) large_q[lt + rl] = (int32_t)i;
+    st += ts;
+    lt += tl;
+  }
+
+  while (true) {
+    __threadfence();
+    __syncthreads();
+    const int64_t m = min(st - sh, lt - lh);
+    if (m <= 0) break;
+    if (m < kSerialBelow) {
+      // few entries on one side: the plain loop, for a bounded stretch
+      if (tid == 0) {
+        int64_t a_sh = sh, a_st = st, a_lh = lh, a_lt = lt;
+        for (int it = 0; it < 4096 && a_sh < a_st && a_lh < a_lt; ++it) {
+          const int32_t a = ld_i32(small_q + a_sh++);
+          const int32_t b = ld_i32(large_q + a_lh++);
+          const double ma = ld_f64(mass + a);
+          prob[a] = (float)(ma / S);
+          alias[a] = b;
+          const double mb = (ld_f64(mass + b) + ma) - S;
+          mass[b] = mb;
+          if (mb < S) small_q[a_st++] = b; else large_q[a_lt++] = b;
+        }
+        q_s[0] = a_sh; q_s[1] = a_st; q_s[2] = a_lh; q_s[3] = a_lt;
+      }
+      __syncthreads();
+      sh = q_s[0]; st = q_s[1]; lh = q_s[2]; lt = q_s[3];
+      continue;
+    }
+    int64_t add_s = 0, add_l = 0;
+    for (int64_t base = 0; base < m; base += kLongThreads) {
+      const int64_t i = base + tid;
+      const bool valid = i < m;
+      int32_t b = 0;
+      bool demoted = false;
+      if (valid) {
+        const int32_t a = ld_i32(small_q + sh + i);
+        b = ld_i32(large_q + lh + i);
+        const double ma = ld_f64(mass + a);
+        prob[a] = (float)(ma / S);
+        alias[a] = b;
+        const double mb = (ld_f64(mass + b) + ma) - S;
+        mass[b] = mb;
+        demoted = mb < S;
+      }
+      int rs, ts, rl, tl;
+      block_rank(valid && demoted, wave_tot, rs, ts);
+      block_rank(valid && !demoted, wave_tot, rl, tl);
+      if (valid) {
+        if (demoted) small_q[st + add_s + rs] = b;
+        else large_q[lt + add_l + rl] = b;
+      }
+      add_s += ts;
+      add_l += tl;
+    }
+    sh += m; lh += m;
+    st += add_s; lt += add_l;
+  }
+  for (int64_t i = sh + tid; i < st; i += kLongThreads) {
+    const int32_t x = ld_i32(small_q + i);
+    prob[x] = 1.0f; alias[x] = x;
+  }
+  for (int64_t i = lh + tid; i < lt; i += kLongThreads) {
+    const int32_t x = ld_i32(large_q + i);
+    prob[x] = 1.0f; alias[x] = x;
+  }
+}
+
 struct AliasPlan {
   double* mass;
   int32_t *small_q, *large_q;
@@ -84,7 +248,7 @@ static AliasPlan plan_alias(void* ws, int64_t total_entries) {
   const size_t t = (size_t)(total_entries > 0 ? total_entries : 1);
   p.mass = cv.take<double>(t);
   p.small_q = cv.take<int32_t>(t);
-  p.large_q = cv.take<int32_t>(t);
+  p.large_q = cv.take<int32_t>(2 * t);   // the workgroup variant appends without wrapping
   p.bytes = cv.used;
   return p;
 }
@@ -110,6 +274,16 @@ extern "C" int32_t gs_alias_build(const void* seg_offsets, int32_t offset_bits, 
   AliasPlan p = plan_alias(ws, total_entries);
   if (ws_bytes < p.bytes) return GS_EWORKSPACE;
   if (num_segments == 0 || total_entries == 0) return GS_OK;
+  if (num_segments == 1 && total_entries >= kLongSegment) {
+    if (offset_bits == 64)
+      alias_build_long_kernel<int64_t><<<1, kLongThreads, 0, stream>>>((const int64_t*)seg_offsets,
+          weights, prob_out, alias_out, p.mass, p.small_q, p.large_q);
+    else
+      alias_build_long_kernel<int32_t><<<1, kLongThreads, 0, stream>>>((const int32_t*)seg_offsets,
+          weights, prob_out, alias_out, p.mass, p.small_q, p.large_q);
+    GS_LAUNCH_CHECK();
+    return GS_OK;
+  }
   const int threads = 64;
   const unsigned blocks = (unsigned)ceil_div(num_segments, threads);
   if (offset_bits == 64)

@@ -514,3 +514,29 @@ def test_workload2_scaled_node2vec(gs, oracle):
     from paper_2407_15452_amd import inputs
     wl = inputs.WORKLOADS[2].scaled(5e-3)
     _pipeline_parity(gs, oracle, wl, 2_000)
+
+
+# ----------------------------------------------------------------------------- alias, long single segment
+@pytest.mark.parametrize("kind", ["one_giant", "equal", "two_level", "lognormal", "mostly_zero"])
+def test_alias_build_long_segment_shapes(gs, oracle, kind):
+    """The workgroup construction of one long segment against the oracle's
+    sequential one, on weight shapes that stress its serial and parallel parts."""
+    rng = np.random.default_rng(42)
+    n = 50_003
+    if kind == "one_giant":                     # one entry absorbs all the others, one at a time
+        w = np.full(n, 1e-3, dtype=np.float32)
+        w[n // 3] = 1e6
+    elif kind == "equal":
+        w = np.full(n, 0.75, dtype=np.float32)
+    elif kind == "two_level":                   # half just below, half just above the mean
+        w = np.where(np.arange(n) % 2 == 0, 0.9, 1.1).astype(np.float32)
+    elif kind == "lognormal":
+        w = rng.lognormal(0, 2.5, n).astype(np.float32)
+    else:
+        w = np.zeros(n, dtype=np.float32)
+        w[rng.choice(n, 300, replace=False)] = rng.random(300).astype(np.float32) + 0.1
+    seg = np.array([0, n], dtype=np.int64)
+    prob, alias = oracle.alias_build(seg, w)
+    a = gs.gs_alias_build(_t(seg), _t(w))
+    np.testing.assert_array_equal(a.alias.cpu().numpy(), alias)
+    np.testing.assert_array_equal(a.prob.cpu().numpy(), prob)
