@@ -27,7 +27,68 @@ struct WalkArgs {
   uint64_t seed;
   int32_t walk_len;
   float inv_p, inv_q, max_bias;
+  float inv_num_nodes;
 };
+
+// Is x in the ascending row nbrs[lo, hi)?  Any correct search gives the same
+// walk; this one is built to touch few cache lines.  Node ids of a row are
+// spread over [0, num_nodes), so x is expected near lo + x * (hi - lo) /
+// num_nodes: two interpolation probes land within a few entries of the place,
+// a doubling search from there brackets it, and a short binary search inside
+// the bracket (usually one cache line) decides.  A plain binary search touches
+// about log2(degree) - 3 lines, which is 8 to 12 for the hubs walks keep
+// returning to.
+__device__ __forceinline__ bool row_has(const int32_t* __restrict__ nbrs, int64_t lo, int64_t hi,
+                                        int32_t x, float inv_num_nodes) {
+  const int64_t n = hi - lo;
+  if (n <= 0) return false;
+  int64_t L = lo, H = hi;               // entries before L are < x, entries from H on are > x
+  if (n > 16) {
+    const float slope = (float)n * inv_num_nodes;          // expected entries per unit of id
+    int64_t p = lo + (int64_t)((float)x * slope);
+    p = min(max(p, lo), hi - 1);
+    int32_t y = nbrs[p];
+    if (y == x) return true;
+    int64_t p2 = p + (int64_t)((float)(x - y) * slope);
+    p2 = min(max(p2, lo), hi - 1);
+    if (p2 != p) {
+      const int32_t y2 = nbrs[p2];
+      if (y2 == x) return true;
+      // keep what both probes say about the bracket
+      if (y < x) L = p + 1; else H = p;
+      if (y2 < x) L = max(L, p2 + 1); else H = min(H, p2);
+      p = p2;
+      y = y2;
+    } else {
+      if (y < x) L = p + 1; else H = p;
+    }
+    // doubling search away from p towards x, inside [L, H)
+    if (y < x) {
+      int64_t step = 1;
+      while (L < H) {
+        const int64_t q = min(L + step - 1, H - 1);
+        const int32_t v = nbrs[q];
+        if (v == x) return true;
+        if (v < x) { L = q + 1; step <<= 1; } else { H = q; break; }
+      }
+    } else {
+      int64_t step = 1;
+      while (L < H) {
+        const int64_t q = max(H - step, L);
+        const int32_t v = nbrs[q];
+        if (v == x) return true;
+        if (v > x) { H = q; step <<= 1; } else { L = q + 1; break; }
+      }
+    }
+  }
+  while (L < H) {
+    const int64_t mid = L + ((H - L) >> 1);
+    const int32_t v = nbrs[mid];
+    if (v == x) return true;
+    if (v < x) L = mid + 1; else H = mid;
+  }
+  return false;
+}
 
 template <typename OffT, bool kWeighted, bool kSecondOrder>
 __global__ __launch_bounds__(kWalkThreads) void walk_kernel(WalkArgs a) {
@@ -79,12 +140,7 @@ __global__ __launch_bounds__(kWalkThreads) void walk_kernel(WalkArgs a) {
             }
             if (s < fminf(1.0f, a.inv_q)) break;
             if (!(s < fmaxf(1.0f, a.inv_q))) continue;
-            int64_t l = prev_lo, h = prev_hi;   // lower bound of x in the row of prev
-            while (l < h) {
-              const int64_t mid = l + ((h - l) >> 1);
-              if (nbrs[mid] < x) l = mid + 1; else h = mid;
-            }
-            const float bias = (l < prev_hi && nbrs[l] == x) ? 1.0f : a.inv_q;
+            const float bias = row_has(nbrs, prev_lo, prev_hi, x, a.inv_num_nodes) ? 1.0f : a.inv_q;
             if (s < bias) break;
           }
         }
@@ -106,12 +162,84 @@ __global__ __launch_bounds__(kWalkThreads) void walk_kernel(WalkArgs a) {
   }
 }
 
+// Second-order walks with one attempt per loop iteration.  In a loop per step a
+// wave would wait, at every step, for the lane that needs the most attempts
+// (about 15 at p=0.5, q=2, against a mean of 3.5); here a lane that has its
+// next node moves on to its next step at once, so the wave runs for the largest
+// total number of attempts of its 64 walks, about a third as many iterations.
+// Each lane stages its own last kWin positions in LDS and writes them out as one
+// 64-byte row segment when the window is full (or the walk is over).
+template <typename OffT, bool kWeighted>
+__global__ __launch_bounds__(kWalkThreads) void node2vec_kernel(WalkArgs a) {
+  __shared__ int32_t tile[kWalkThreads / 64][64][kWinPad];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t i = ((int64_t)blockIdx.x * (kWalkThreads / 64) + wave) * 64 + lane;
+  if (i >= a.num_walks) return;
+  const uint64_t id = a.id_base + (uint64_t)i;
+  const int32_t* __restrict__ nbrs = a.nbrs;
+  const OffT* __restrict__ offsets = static_cast<const OffT*>(a.offsets);
+  int32_t* __restrict__ out = a.walks + i * (int64_t)a.walk_len;
+  int32_t* mine = tile[wave][lane];
+  const int32_t last = a.walk_len - 1;      // index of the last position
+  const float bias_lo = fminf(1.0f, a.inv_q), bias_hi = fmaxf(1.0f, a.inv_q);
+
+  int32_t cur = a.starts[i];
+  if (cur < 0 || (int64_t)cur >= a.num_nodes) cur = -1;
+  int32_t prev = -1;
+  int64_t prev_lo = 0, prev_hi = 0, lo = 0, hi = 0;
+  if (cur >= 0) { lo = (int64_t)offsets[cur]; hi = (int64_t)offsets[(int64_t)cur + 1]; }
+  int32_t t = 0;                            // position of cur
+  uint32_t att = 0;
+  mine[0] = cur;
+  if (last == 0) { out[0] = cur; return; }
+
+  while (true) {
+    bool accept;
+    int32_t next = -1;
+    if (hi > lo) {
+      const Block4 b = philox_at(a.seed, id, (uint32_t)t, att);
+      int64_t j = (int64_t)slot_of(b, (uint64_t)(hi - lo));
+      if (kWeighted) {
+        if (!(unit_float(b.x2) < a.prob[lo + j])) j = (int64_t)a.alias[lo + j];
+      }
+      next = nbrs[lo + j];
+      if (t == 0 || att == kMaxAttempts - 1) {
+        accept = true;                      // first step is unbiased; the last attempt is taken
+      } else {
+        // accept iff s < bias(next).  For next != prev the bias is 1 or 1/q, so the
+        // membership search is only needed when s falls between the two.
+        const float s = unit_float(b.x3) * a.max_bias;
+        if (next == prev) accept = s < a.inv_p;
+        else if (s < bias_lo) accept = true;
+        else if (!(s < bias_hi)) accept = false;
+        else accept = s < (row_has(nbrs, prev_lo, prev_hi, next, a.inv_num_nodes) ? 1.0f : a.inv_q);
+      }
+    } else {
+      accept = true;                        // dead end (or dead walk): -1 from here on
+    }
+    if (!accept) { ++att; continue; }
+    prev = cur; prev_lo = lo; prev_hi = hi;
+    cur = next;
+    ++t;
+    att = 0;
+    const int col = t & (kWin - 1);
+    mine[col] = cur;
+    if (col == kWin - 1 || t == last) {
+      const int32_t first = t - col;
+      for (int c = 0; c <= col; ++c) out[first + c] = mine[c];
+    }
+    if (t == last) break;
+    if (cur >= 0) { lo = (int64_t)offsets[cur]; hi = (int64_t)offsets[(int64_t)cur + 1]; }
+    else { lo = 0; hi = 0; }
+  }
+}
+
 template <typename OffT>
 static void launch_walk(bool weighted, bool second, const WalkArgs& a, hipStream_t stream) {
   const unsigned blocks = (unsigned)ceil_div(a.num_walks, kWalkThreads);
   if (second) {
-    if (weighted) walk_kernel<OffT, true, true><<<blocks, kWalkThreads, 0, stream>>>(a);
-    else walk_kernel<OffT, false, true><<<blocks, kWalkThreads, 0, stream>>>(a);
+    if (weighted) node2vec_kernel<OffT, true><<<blocks, kWalkThreads, 0, stream>>>(a);
+    else node2vec_kernel<OffT, false><<<blocks, kWalkThreads, 0, stream>>>(a);
   } else {
     if (weighted) walk_kernel<OffT, true, false><<<blocks, kWalkThreads, 0, stream>>>(a);
     else walk_kernel<OffT, false, false><<<blocks, kWalkThreads, 0, stream>>>(a);
@@ -146,6 +274,7 @@ static int32_t walk_common(const gs_csr* g, const gs_alias* al, const int32_t* s
   a.inv_p = 1.0f / p;
   a.inv_q = 1.0f / q;
   a.max_bias = fmaxf(a.inv_p, fmaxf(1.0f, a.inv_q));
+  a.inv_num_nodes = g->num_nodes > 0 ? 1.0f / (float)g->num_nodes : 0.0f;
   if (g->offset_bits == 64) launch_walk<int64_t>(weighted, second, a, stream);
   else launch_walk<int32_t>(weighted, second, a, stream);
   GS_LAUNCH_CHECK();
