@@ -66,10 +66,15 @@ typedef struct {
 
 /* Alias table(s).  For walks: one table per CSR row, stored at the row's
  * offsets, alias[] = position inside the row.  For negatives: one table of
- * num_nodes entries.  prob == NULL means "uniform". */
+ * num_nodes entries.  prob == NULL means "uniform".  `packed` is optional
+ * (NULL: not provided): the same table with entry i stored as one 8-byte word,
+ * prob bits in the low half and alias in the high half, as written by
+ * gs_alias_pack; the samplers read it instead of the two arrays when present
+ * (one random cache line per draw instead of two). */
 typedef struct {
   const float* prob;
   const int32_t* alias;
+  const uint64_t* packed;
 } gs_alias;
 
 /* HIP error code of the last GS_EHIP on this thread (0 if none). */
@@ -114,6 +119,11 @@ size_t gs_alias_build_workspace_bytes(int64_t num_segments, int64_t total_entrie
 int32_t gs_alias_build(const void* seg_offsets, int32_t offset_bits, int64_t num_segments,
                        int64_t total_entries, const float* weights, float* prob_out,
                        int32_t* alias_out, void* ws, size_t ws_bytes, void* stream);
+
+/* gs_alias_pack -- interleaves a finished table for the samplers:
+ *   packed_out[i] = (uint64)alias[i] << 32 | bits(prob[i]),  i in [0, total_entries). */
+int32_t gs_alias_pack(const float* prob, const int32_t* alias, int64_t total_entries,
+                      uint64_t* packed_out, void* stream);
 
 /* --------------------------------------------------------------------------
  * gs_random_walk -- first-order walks (Sec. 2.2, DeepWalk; Sec. 3.2 counts

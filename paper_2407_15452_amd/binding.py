@@ -22,7 +22,7 @@ GS_F32, GS_BF16 = 0, 1
 EXPORTS = (
     "gs_last_hip_error",
     "gs_csr_build_workspace_bytes", "gs_csr_build",
-    "gs_alias_build_workspace_bytes", "gs_alias_build",
+    "gs_alias_build_workspace_bytes", "gs_alias_build", "gs_alias_pack",
     "gs_random_walk", "gs_node2vec_walk",
     "gs_make_pairs_workspace_bytes", "gs_make_pairs",
     "gs_sample_negatives",
@@ -47,7 +47,7 @@ class CsrStruct(C.Structure):
 
 
 class AliasStruct(C.Structure):
-    _fields_ = [("prob", C.c_void_p), ("alias", C.c_void_p)]
+    _fields_ = [("prob", C.c_void_p), ("alias", C.c_void_p), ("packed", C.c_void_p)]
 
 
 _lib = None
@@ -109,11 +109,13 @@ class Csr:
 
 
 class Alias:
-    def __init__(self, prob: torch.Tensor, alias: torch.Tensor):
+    def __init__(self, prob: torch.Tensor, alias: torch.Tensor, packed=None):
         _dev(prob, torch.float32, "prob")
         _dev(alias, torch.int32, "alias")
-        self.prob, self.alias = prob, alias
-        self.struct = AliasStruct(prob.data_ptr(), alias.data_ptr())
+        _dev(packed, torch.int64, "packed")
+        self.prob, self.alias, self.packed = prob, alias, packed
+        self.struct = AliasStruct(prob.data_ptr(), alias.data_ptr(),
+                                  None if packed is None else packed.data_ptr())
 
 
 def gs_csr_build(src, dst, w, num_nodes: int, flags: int, offset_bits: int = 32, ws=None) -> Csr:
@@ -138,7 +140,17 @@ def gs_csr_build(src, dst, w, num_nodes: int, flags: int, offset_bits: int = 32,
     return Csr(offsets, nbrs[:n], None if w_out is None else w_out[:n], n)
 
 
-def gs_alias_build(seg_offsets, weights, ws=None) -> Alias:
+def gs_alias_pack(prob, alias) -> torch.Tensor:
+    """The table as one 8-byte word per entry (see gs.h)."""
+    total = int(prob.numel())
+    packed = torch.empty(max(1, total), dtype=torch.int64, device=prob.device)
+    rc = lib().gs_alias_pack(_dev(prob, torch.float32, "prob"), _dev(alias, torch.int32, "alias"),
+                             C.c_int64(total), _dev(packed), _stream())
+    _check(rc, "gs_alias_pack")
+    return packed[:total]
+
+
+def gs_alias_build(seg_offsets, weights, ws=None, pack: bool = True) -> Alias:
     l = lib()
     dev = weights.device
     total = int(weights.numel())
@@ -153,7 +165,8 @@ def gs_alias_build(seg_offsets, weights, ws=None) -> Alias:
                           C.c_int64(total), _dev(weights, torch.float32, "weights"), _dev(prob),
                           _dev(alias), _dev(ws), C.c_size_t(ws.numel()), _stream())
     _check(rc, "gs_alias_build")
-    return Alias(prob[:total], alias[:total])
+    prob, alias = prob[:total], alias[:total]
+    return Alias(prob, alias, gs_alias_pack(prob, alias) if pack and total > 0 else None)
 
 
 def _alias_ref(a):

@@ -236,6 +236,12 @@ __global__ __launch_bounds__(kLongThreads) void alias_build_long_kernel(
   }
 }
 
+__global__ void alias_pack_kernel(const float* __restrict__ prob, const int32_t* __restrict__ alias,
+                                  int64_t n, uint64_t* __restrict__ packed) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) packed[i] = ((uint64_t)(uint32_t)alias[i] << 32) | (uint64_t)__float_as_uint(prob[i]);
+}
+
 struct AliasPlan {
   double* mass;
   int32_t *small_q, *large_q;
@@ -292,6 +298,17 @@ extern "C" int32_t gs_alias_build(const void* seg_offsets, int32_t offset_bits, 
   else
     alias_build_kernel<int32_t><<<blocks, threads, 0, stream>>>((const int32_t*)seg_offsets,
         num_segments, weights, prob_out, alias_out, p.mass, p.small_q, p.large_q);
+  GS_LAUNCH_CHECK();
+  return GS_OK;
+}
+
+extern "C" int32_t gs_alias_pack(const float* prob, const int32_t* alias, int64_t total_entries,
+                                 uint64_t* packed_out, void* stream_) {
+  if (total_entries < 0) return GS_EINVAL;
+  if (total_entries == 0) return GS_OK;
+  if (!prob || !alias || !packed_out || !aligned(packed_out, 8)) return GS_EINVAL;
+  alias_pack_kernel<<<(unsigned)ceil_div(total_entries, 256), 256, 0, (hipStream_t)stream_>>>(
+      prob, alias, total_entries, packed_out);
   GS_LAUNCH_CHECK();
   return GS_OK;
 }

@@ -81,6 +81,7 @@ __global__ __launch_bounds__(kEmitThreads) void pairs_emit_kernel(
 }
 
 __global__ void negatives_kernel(const float* __restrict__ prob, const int32_t* __restrict__ alias,
+                                 const uint2* __restrict__ packed,
                                  uint64_t num_nodes, int64_t total, uint64_t pair_base, int32_t k,
                                  uint64_t seed, int32_t* __restrict__ negs) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -89,7 +90,10 @@ __global__ void negatives_kernel(const float* __restrict__ prob, const int32_t* 
   const uint32_t j = (uint32_t)(e - (int64_t)i * k);
   const Block4 b = philox_at(seed, pair_base + i, j, 0x80000000u);
   int64_t s = (int64_t)slot_of(b, num_nodes);
-  if (prob != nullptr) {
+  if (packed != nullptr) {
+    const uint2 e2 = packed[s];                     // (prob bits, alias) in one 8-byte load
+    if (!(unit_float(b.x2) < __uint_as_float(e2.x))) s = (int64_t)(int32_t)e2.y;
+  } else if (prob != nullptr) {
     if (!(unit_float(b.x2) < prob[s])) s = (int64_t)alias[s];
   }
   negs[e] = (int32_t)s;
@@ -160,7 +164,8 @@ extern "C" int32_t gs_sample_negatives(const gs_alias* noise, int64_t num_nodes,
   if (total == 0) return GS_OK;
   if (ceil_div(total, 256) > (int64_t)INT32_MAX) return GS_EOVERFLOW;
   negatives_kernel<<<(unsigned)ceil_div(total, 256), 256, 0, stream>>>(
-      weighted ? noise->prob : nullptr, weighted ? noise->alias : nullptr, (uint64_t)num_nodes, total,
+      weighted ? noise->prob : nullptr, weighted ? noise->alias : nullptr,
+      weighted ? reinterpret_cast<const uint2*>(noise->packed) : nullptr, (uint64_t)num_nodes, total,
       pair_index_base, k, seed, negs_out);
   GS_LAUNCH_CHECK();
   return GS_OK;

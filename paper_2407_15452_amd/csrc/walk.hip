@@ -2,9 +2,11 @@
 // from every node and node2vec's biased second-order walk).
 //
 // One lane per walk.  Every transition is a chain of dependent random reads
-// (row bounds -> neighbour), so throughput comes from many walks in flight.
-// Output rows are staged in LDS in windows of kWin positions and written out
-// as 64-byte row segments instead of one scattered 4-byte store per lane.
+// (row bounds -> neighbour -> for node2vec, the previous node's row), each of
+// which costs a whole cache line from HBM, so throughput comes from many walks
+// in flight and from touching few lines per step.  Output rows are staged in LDS
+// in windows of kWin positions and written out as 64-byte row segments instead
+// of one scattered 4-byte store per position.
 #include "common.h"
 
 namespace gs {
@@ -19,6 +21,7 @@ struct WalkArgs {
   const int32_t* nbrs;
   const float* prob;
   const int32_t* alias;
+  const uint2* packed;      // optional interleaved (prob bits, alias)
   const int32_t* starts;
   int32_t* walks;
   int64_t num_nodes;
@@ -29,6 +32,15 @@ struct WalkArgs {
   float inv_p, inv_q, max_bias;
   float inv_num_nodes;
 };
+
+// Alias step of a weighted draw: keep slot j, or move to the slot's alias.
+__device__ __forceinline__ int64_t alias_pick(const WalkArgs& a, int64_t at, int64_t j, uint32_t word) {
+  if (a.packed != nullptr) {
+    const uint2 e = a.packed[at];
+    return (unit_float(word) < __uint_as_float(e.x)) ? j : (int64_t)(int32_t)e.y;
+  }
+  return (unit_float(word) < a.prob[at]) ? j : (int64_t)a.alias[at];
+}
 
 // Is x in the ascending row nbrs[lo, hi)?  Any correct search gives the same
 // walk; this one is built to touch few cache lines.  Node ids of a row are
@@ -90,7 +102,11 @@ __device__ __forceinline__ bool row_has(const int32_t* __restrict__ nbrs, int64_
   return false;
 }
 
-template <typename OffT, bool kWeighted, bool kSecondOrder>
+// First-order walks: one lane per walk, one dependent pair of random reads per
+// step (row bounds, then the neighbour).  The 64 walks of a wave advance in
+// lock step, so their positions are staged in LDS in windows of kWin and the
+// wave writes them out together, 64 bytes per row segment.
+template <typename OffT, bool kWeighted>
 __global__ __launch_bounds__(kWalkThreads) void walk_kernel(WalkArgs a) {
   __shared__ int32_t tile[kWalkThreads / 64][64][kWinPad];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -106,8 +122,6 @@ __global__ __launch_bounds__(kWalkThreads) void walk_kernel(WalkArgs a) {
     cur = a.starts[i];
     if (cur < 0 || (int64_t)cur >= a.num_nodes) cur = -1;
   }
-  int32_t prev = -1;
-  int64_t prev_lo = 0, prev_hi = 0;   // row of prev (second order only)
 
   for (int32_t t0 = 0; t0 < a.walk_len; t0 += kWin) {
     const int cols = min(kWin, a.walk_len - t0);
@@ -116,36 +130,18 @@ __global__ __launch_bounds__(kWalkThreads) void walk_kernel(WalkArgs a) {
       tile[wave][lane][tt] = cur;
       if (t + 1 >= a.walk_len) break;
       int32_t next = -1;
-      int64_t lo = 0, hi = 0;
       if (cur >= 0) {
-        lo = (int64_t)offsets[cur];
-        hi = (int64_t)offsets[(int64_t)cur + 1];
-        const uint64_t deg = (uint64_t)(hi - lo);
-        if (deg > 0) {
-          for (uint32_t att = 0; att < kMaxAttempts; ++att) {
-            const Block4 b = philox_at(a.seed, id, (uint32_t)t, att);
-            int64_t j = (int64_t)slot_of(b, deg);
-            if (kWeighted) {
-              if (!(unit_float(b.x2) < a.prob[lo + j])) j = (int64_t)a.alias[lo + j];
-            }
-            const int32_t x = nbrs[lo + j];
-            next = x;
-            if (!kSecondOrder || t == 0) break;
-            // accept iff s < bias(x).  For x != prev the bias is 1 or 1/q, so the
-            // membership search is only needed when s falls between the two.
-            const float s = unit_float(b.x3) * a.max_bias;
-            if (x == prev) {
-              if (s < a.inv_p) break;
-              continue;
-            }
-            if (s < fminf(1.0f, a.inv_q)) break;
-            if (!(s < fmaxf(1.0f, a.inv_q))) continue;
-            const float bias = row_has(nbrs, prev_lo, prev_hi, x, a.inv_num_nodes) ? 1.0f : a.inv_q;
-            if (s < bias) break;
+        const int64_t lo = (int64_t)offsets[cur];
+        const int64_t hi = (int64_t)offsets[(int64_t)cur + 1];
+        if (hi > lo) {
+          const Block4 b = philox_at(a.seed, id, (uint32_t)t, 0u);
+          int64_t j = (int64_t)slot_of(b, (uint64_t)(hi - lo));
+          if (kWeighted) {
+            j = alias_pick(a, lo + j, j, b.x2);
           }
+          next = nbrs[lo + j];
         }
       }
-      if (kSecondOrder) { prev = cur; prev_lo = lo; prev_hi = hi; }
       cur = next;
     }
     __syncthreads();
@@ -200,7 +196,7 @@ __global__ __launch_bounds__(kWalkThreads) void node2vec_kernel(WalkArgs a) {
       const Block4 b = philox_at(a.seed, id, (uint32_t)t, att);
       int64_t j = (int64_t)slot_of(b, (uint64_t)(hi - lo));
       if (kWeighted) {
-        if (!(unit_float(b.x2) < a.prob[lo + j])) j = (int64_t)a.alias[lo + j];
+        j = alias_pick(a, lo + j, j, b.x2);
       }
       next = nbrs[lo + j];
       if (t == 0 || att == kMaxAttempts - 1) {
@@ -241,8 +237,8 @@ static void launch_walk(bool weighted, bool second, const WalkArgs& a, hipStream
     if (weighted) node2vec_kernel<OffT, true><<<blocks, kWalkThreads, 0, stream>>>(a);
     else node2vec_kernel<OffT, false><<<blocks, kWalkThreads, 0, stream>>>(a);
   } else {
-    if (weighted) walk_kernel<OffT, true, false><<<blocks, kWalkThreads, 0, stream>>>(a);
-    else walk_kernel<OffT, false, false><<<blocks, kWalkThreads, 0, stream>>>(a);
+    if (weighted) walk_kernel<OffT, true><<<blocks, kWalkThreads, 0, stream>>>(a);
+    else walk_kernel<OffT, false><<<blocks, kWalkThreads, 0, stream>>>(a);
   }
 }
 
@@ -264,6 +260,7 @@ static int32_t walk_common(const gs_csr* g, const gs_alias* al, const int32_t* s
   a.nbrs = g->nbrs;
   a.prob = weighted ? al->prob : nullptr;
   a.alias = weighted ? al->alias : nullptr;
+  a.packed = weighted ? reinterpret_cast<const uint2*>(al->packed) : nullptr;
   a.starts = starts;
   a.walks = walks_out;
   a.num_nodes = g->num_nodes;

@@ -540,3 +540,31 @@ def test_alias_build_long_segment_shapes(gs, oracle, kind):
     a = gs.gs_alias_build(_t(seg), _t(w))
     np.testing.assert_array_equal(a.alias.cpu().numpy(), alias)
     np.testing.assert_array_equal(a.prob.cpu().numpy(), prob)
+
+
+def test_packed_alias_layout_changes_nothing(gs, oracle, cfg0):
+    """Samplers read the interleaved table when it is given; results are the same."""
+    wl, (off, nb), g = cfg0
+    rng = np.random.default_rng(3)
+    w = rng.lognormal(0, 1, nb.size).astype(np.float32)
+    plain = gs.gs_alias_build(g.offsets, _t(w), pack=False)
+    packed = gs.gs_alias_build(g.offsets, _t(w), pack=True)
+    assert plain.packed is None and packed.packed is not None
+    bits = packed.packed.cpu().numpy().view(np.uint64)
+    np.testing.assert_array_equal((bits & 0xFFFFFFFF).astype(np.uint32),
+                                  packed.prob.cpu().numpy().view(np.uint32))
+    np.testing.assert_array_equal((bits >> 32).astype(np.int32), packed.alias.cpu().numpy())
+    starts = _walk_inputs(wl, 5000).to(DEV)
+    a = gs.gs_random_walk(g, plain, starts, 20, 7)
+    b = gs.gs_random_walk(g, packed, starts, 20, 7)
+    assert torch.equal(a, b)
+    a = gs.gs_node2vec_walk(g, plain, starts, 20, 0.5, 2.0, 7)
+    b = gs.gs_node2vec_walk(g, packed, starts, 20, 0.5, 2.0, 7)
+    assert torch.equal(a, b)
+    nw = _t(np.arange(1, wl.num_nodes + 1, dtype=np.float32))
+    seg = _t(np.array([0, wl.num_nodes], dtype=np.int64))
+    n_plain = gs.gs_alias_build(seg, nw, pack=False)
+    n_packed = gs.gs_alias_build(seg, nw, pack=True)
+    a = gs.gs_sample_negatives(n_plain, wl.num_nodes, 20_000, 5, 11)
+    b = gs.gs_sample_negatives(n_packed, wl.num_nodes, 20_000, 5, 11)
+    assert torch.equal(a, b)
