@@ -42,66 +42,6 @@ __device__ __forceinline__ int64_t alias_pick(const WalkArgs& a, int64_t at, int
   return (unit_float(word) < a.prob[at]) ? j : (int64_t)a.alias[at];
 }
 
-// Is x in the ascending row nbrs[lo, hi)?  Any correct search gives the same
-// walk; this one is built to touch few cache lines.  Node ids of a row are
-// spread over [0, num_nodes), so x is expected near lo + x * (hi - lo) /
-// num_nodes: two interpolation probes land within a few entries of the place,
-// a doubling search from there brackets it, and a short binary search inside
-// the bracket (usually one cache line) decides.  A plain binary search touches
-// about log2(degree) - 3 lines, which is 8 to 12 for the hubs walks keep
-// returning to.
-__device__ __forceinline__ bool row_has(const int32_t* __restrict__ nbrs, int64_t lo, int64_t hi,
-                                        int32_t x, float inv_num_nodes) {
-  const int64_t n = hi - lo;
-  if (n <= 0) return false;
-  int64_t L = lo, H = hi;               // entries before L are < x, entries from H on are > x
-  if (n > 16) {
-    const float slope = (float)n * inv_num_nodes;          // expected entries per unit of id
-    int64_t p = lo + (int64_t)((float)x * slope);
-    p = min(max(p, lo), hi - 1);
-    int32_t y = nbrs[p];
-    if (y == x) return true;
-    int64_t p2 = p + (int64_t)((float)(x - y) * slope);
-    p2 = min(max(p2, lo), hi - 1);
-    if (p2 != p) {
-      const int32_t y2 = nbrs[p2];
-      if (y2 == x) return true;
-      // keep what both probes say about the bracket
-      if (y < x) L = p + 1; else H = p;
-      if (y2 < x) L = max(L, p2 + 1); else H = min(H, p2);
-      p = p2;
-      y = y2;
-    } else {
-      if (y < x) L = p + 1; else H = p;
-    }
-    // doubling search away from p towards x, inside [L, H)
-    if (y < x) {
-      int64_t step = 1;
-      while (L < H) {
-        const int64_t q = min(L + step - 1, H - 1);
-        const int32_t v = nbrs[q];
-        if (v == x) return true;
-        if (v < x) { L = q + 1; step <<= 1; } else { H = q; break; }
-      }
-    } else {
-      int64_t step = 1;
-      while (L < H) {
-        const int64_t q = max(H - step, L);
-        const int32_t v = nbrs[q];
-        if (v == x) return true;
-        if (v > x) { H = q; step <<= 1; } else { L = q + 1; break; }
-      }
-    }
-  }
-  while (L < H) {
-    const int64_t mid = L + ((H - L) >> 1);
-    const int32_t v = nbrs[mid];
-    if (v == x) return true;
-    if (v < x) L = mid + 1; else H = mid;
-  }
-  return false;
-}
-
 // First-order walks: one lane per walk, one dependent pair of random reads per
 // step (row bounds, then the neighbour).  The 64 walks of a wave advance in
 // lock step, so their positions are staged in LDS in windows of kWin and the
@@ -158,11 +98,15 @@ __global__ __launch_bounds__(kWalkThreads) void walk_kernel(WalkArgs a) {
   }
 }
 
-// Second-order walks with one attempt per loop iteration.  In a loop per step a
-// wave would wait, at every step, for the lane that needs the most attempts
-// (about 15 at p=0.5, q=2, against a mean of 3.5); here a lane that has its
-// next node moves on to its next step at once, so the wave runs for the largest
-// total number of attempts of its 64 walks, about a third as many iterations.
+// Second-order walks as a per-lane state machine with ONE memory access per
+// loop iteration.  A step of a walk is a chain of dependent random reads of
+// very different length (row bounds; one candidate per attempt, 3.5 attempts on
+// average at p=0.5, q=2; for a quarter of the attempts a search in the previous
+// node's row).  Written as nested loops, a wave waits in every inner loop for
+// its slowest lane and keeps about a third of its lanes busy.  Here every lane
+// carries its own state (which read it needs next), each iteration issues that
+// one read for all 64 lanes together, and the lane then moves to its next state;
+// lanes never wait for each other except at the one load per iteration.
 // Each lane stages its own last kWin positions in LDS and writes them out as one
 // 64-byte row segment when the window is full (or the walk is over).
 template <typename OffT, bool kWeighted>
@@ -179,41 +123,29 @@ __global__ __launch_bounds__(kWalkThreads) void node2vec_kernel(WalkArgs a) {
   const int32_t last = a.walk_len - 1;      // index of the last position
   const float bias_lo = fminf(1.0f, a.inv_q), bias_hi = fmaxf(1.0f, a.inv_q);
 
+  enum : int { kRow, kNewDraw, kAlias, kDraw, kProbe1, kProbe2, kGallop, kBinary, kDone };
   int32_t cur = a.starts[i];
   if (cur < 0 || (int64_t)cur >= a.num_nodes) cur = -1;
   int32_t prev = -1;
   int64_t prev_lo = 0, prev_hi = 0, lo = 0, hi = 0;
-  if (cur >= 0) { lo = (int64_t)offsets[cur]; hi = (int64_t)offsets[(int64_t)cur + 1]; }
   int32_t t = 0;                            // position of cur
   uint32_t att = 0;
+  int state = kRow;
   mine[0] = cur;
   if (last == 0) { out[0] = cur; return; }
 
-  while (true) {
-    bool accept;
-    int32_t next = -1;
-    if (hi > lo) {
-      const Block4 b = philox_at(a.seed, id, (uint32_t)t, att);
-      int64_t j = (int64_t)slot_of(b, (uint64_t)(hi - lo));
-      if (kWeighted) {
-        j = alias_pick(a, lo + j, j, b.x2);
-      }
-      next = nbrs[lo + j];
-      if (t == 0 || att == kMaxAttempts - 1) {
-        accept = true;                      // first step is unbiased; the last attempt is taken
-      } else {
-        // accept iff s < bias(next).  For next != prev the bias is 1 or 1/q, so the
-        // membership search is only needed when s falls between the two.
-        const float s = unit_float(b.x3) * a.max_bias;
-        if (next == prev) accept = s < a.inv_p;
-        else if (s < bias_lo) accept = true;
-        else if (!(s < bias_hi)) accept = false;
-        else accept = s < (row_has(nbrs, prev_lo, prev_hi, next, a.inv_num_nodes) ? 1.0f : a.inv_q);
-      }
-    } else {
-      accept = true;                        // dead end (or dead walk): -1 from here on
-    }
-    if (!accept) { ++att; continue; }
+  // the attempt in flight
+  int64_t j = 0;                            // slot in the row of cur
+  uint32_t word2 = 0;                       // alias uniform (weighted)
+  float s = 0.f;                            // acceptance uniform * max_bias
+  int32_t x = 0;                            // candidate
+  // the membership search in flight: entries before L are < x, entries from H on are > x
+  int64_t L = 0, H = 0, p = 0, step = 1;
+  float slope = 0.f;
+  bool right = false;
+  int64_t pos = 0;                          // what this iteration reads: nbrs[pos] (or the alias entry at pos)
+
+  auto commit = [&](int32_t next) {         // the step is decided: move to position t + 1
     prev = cur; prev_lo = lo; prev_hi = hi;
     cur = next;
     ++t;
@@ -224,9 +156,121 @@ __global__ __launch_bounds__(kWalkThreads) void node2vec_kernel(WalkArgs a) {
       const int32_t first = t - col;
       for (int c = 0; c <= col; ++c) out[first + c] = mine[c];
     }
-    if (t == last) break;
-    if (cur >= 0) { lo = (int64_t)offsets[cur]; hi = (int64_t)offsets[(int64_t)cur + 1]; }
-    else { lo = 0; hi = 0; }
+    state = (t == last) ? kDone : kRow;
+  };
+  auto reject = [&]() { ++att; state = kNewDraw; };
+  auto resolve = [&](bool member) {         // membership of x in the row of prev is known
+    if (s < (member ? 1.0f : a.inv_q)) commit(x); else reject();
+  };
+
+  while (state != kDone) {
+    // ---- bring the lane to a state that needs a read (arithmetic only) -------------------
+    bool ready = false;
+    while (!ready) {
+      switch (state) {
+        case kRow:
+          if (cur < 0) { while (state != kDone) commit(-1); }   // dead walk: -1 to the end
+          ready = true;
+          break;
+        case kNewDraw: {
+          const Block4 b = philox_at(a.seed, id, (uint32_t)t, att);
+          j = (int64_t)slot_of(b, (uint64_t)(hi - lo));
+          word2 = b.x2;
+          s = unit_float(b.x3) * a.max_bias;
+          pos = lo + j;
+          state = (kWeighted ? kAlias : kDraw);
+          ready = true;
+          break;
+        }
+        case kGallop:
+          if (L >= H) { resolve(false); break; }
+          pos = right ? min(L + step - 1, H - 1) : max(H - step, L);
+          ready = true;
+          break;
+        case kBinary:
+          if (L >= H) { resolve(false); break; }
+          pos = L + ((H - L) >> 1);
+          ready = true;
+          break;
+        default:                            // kAlias, kDraw, kProbe1, kProbe2, kDone: pos is set
+          ready = true;
+          break;
+      }
+    }
+    if (state == kDone) break;
+
+    // ---- the one read of this iteration ---------------------------------------------------
+    int64_t r0 = 0, r1 = 0;
+    int32_t v = 0;
+    uint32_t e_prob = 0, e_alias = 0;
+    if (state == kRow) {
+      r0 = (int64_t)offsets[cur];
+      r1 = (int64_t)offsets[(int64_t)cur + 1];
+    } else if (kWeighted && state == kAlias) {
+      if (a.packed != nullptr) { const uint2 e = a.packed[pos]; e_prob = e.x; e_alias = e.y; }
+      else { e_prob = __float_as_uint(a.prob[pos]); e_alias = (uint32_t)a.alias[pos]; }
+    } else {
+      v = nbrs[pos];
+    }
+
+    // ---- consume it --------------------------------------------------------------------------
+    switch (state) {
+      case kRow:
+        lo = r0; hi = r1;
+        if (hi > lo) state = kNewDraw; else commit(-1);           // dead end
+        break;
+      case kAlias:
+        if (!(unit_float(word2) < __uint_as_float(e_prob))) j = (int64_t)(int32_t)e_alias;
+        pos = lo + j;
+        state = kDraw;
+        break;
+      case kDraw:
+        x = v;
+        if (t == 0 || att == kMaxAttempts - 1) { commit(x); break; }   // unbiased first step; last attempt is taken
+        // accept iff s < bias(x).  For x != prev the bias is 1 or 1/q, so the
+        // membership search is only needed when s falls between the two.
+        if (x == prev) { if (s < a.inv_p) commit(x); else reject(); break; }
+        if (s < bias_lo) { commit(x); break; }
+        if (!(s < bias_hi)) { reject(); break; }
+        L = prev_lo; H = prev_hi;
+        if (H - L > 16) {
+          // ids of a row are spread over [0, num_nodes): x is expected near L + x * n / num_nodes
+          slope = (float)(H - L) * a.inv_num_nodes;
+          p = min(max(L + (int64_t)((float)x * slope), L), H - 1);
+          pos = p;
+          state = kProbe1;
+        } else {
+          state = kBinary;
+        }
+        break;
+      case kProbe1: {
+        if (v == x) { resolve(true); break; }
+        if (v < x) L = p + 1; else H = p;
+        const int64_t p2 = min(max(p + (int64_t)((float)(x - v) * slope), prev_lo), prev_hi - 1);
+        right = v < x;
+        step = 1;
+        if (p2 != p) { p = p2; pos = p2; state = kProbe2; } else state = kGallop;
+        break;
+      }
+      case kProbe2:
+        if (v == x) { resolve(true); break; }
+        if (v < x) L = max(L, p + 1); else H = min(H, p);
+        right = v < x;
+        step = 1;
+        state = kGallop;
+        break;
+      case kGallop:                         // doubling search away from the last probe towards x
+        if (v == x) { resolve(true); break; }
+        if (right) { if (v < x) { L = pos + 1; step <<= 1; } else { H = pos; state = kBinary; } }
+        else       { if (v > x) { H = pos; step <<= 1; } else { L = pos + 1; state = kBinary; } }
+        break;
+      case kBinary:
+        if (v == x) { resolve(true); break; }
+        if (v < x) L = pos + 1; else H = pos;
+        break;
+      default:
+        break;
+    }
   }
 }
 
