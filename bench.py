@@ -231,6 +231,28 @@ def main():
     walk_steps_per_s = valid_steps / (walk_big_ms * 1e-3)
     del big
 
+    # ------------------------------------------------------------------ momentum variant (extra)
+    # the paper's optimizer (dense mult / sparse put / dense mult_add); timed on the last batch
+    momentum_ms = None
+    if 2 * wl.num_nodes * wl.dim * elem_bytes <= 32e9:
+        m_in, m_out = torch.zeros_like(w_in), torch.zeros_like(w_out)
+        lo = (K - 1) * B
+        for _ in range(2):
+            gs.gs_sgns_momentum_step(w_in, w_out, m_in, m_out, centers[lo:lo + B],
+                                     contexts[lo:lo + B], negs, lr, 0.9, loss_out=losses[:1],
+                                     ws=sgns_ws)
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(5):
+            gs.gs_sgns_momentum_step(w_in, w_out, m_in, m_out, centers[lo:lo + B],
+                                     contexts[lo:lo + B], negs, lr, 0.9, loss_out=losses[:1],
+                                     ws=sgns_ws)
+        e1.record()
+        torch.cuda.synchronize()
+        momentum_ms = e0.elapsed_time(e1) / 5
+        del m_in, m_out
+
     walk_kind = ("node2vec p=%g q=%g" % (wl.p, wl.q)) if wl.node2vec else "first-order"
     walk_kind += ", alias-weighted" if wl.weighted else ", uniform"
     result = {
@@ -250,6 +272,7 @@ def main():
         "stages_ms": {"walk_chunk": walk_ms, "pairs_chunk": pairs_ms, "sgns_step_mean": sgns_ms,
                       "chunk_walks": int(starts_timed.numel())},
         "mean_loss_per_pair": mean_loss,
+        "momentum_step_ms": momentum_ms,
         "roofline": {"bound": "hbm", "kernel": "gs_sgns_step (all kernels of one call)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "bytes_per_pair": bpp,

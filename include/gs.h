@@ -208,6 +208,27 @@ int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int32_t dim, in
                      int64_t num_pairs, int32_t k, float lr, double* loss_sum_out,
                      void* ws, size_t ws_bytes, void* stream);
 
+/* --------------------------------------------------------------------------
+ * gs_sgns_momentum_step -- the same iteration with the optimizer the paper
+ * runs: SGD with momentum written as the three storage operations of Sec. 3.2
+ * (model update for SGD with momentum), applied to both tables:
+ *     mult      momentum <- mu * momentum                 every row
+ *     put       momentum[r] <- momentum[r] + gradient[r]  rows the batch names
+ *     mult_add  model <- model - lr * momentum            every row
+ *   gradient = gradient of the batch's summed loss at the pre-iteration model
+ *   (the same terms gs_sgns_step applies).  m_in, m_out: momentum tables, same
+ *   shape and dtype as w_in, w_out, distinct from them, updated in place.
+ *   Unlike gs_sgns_step this streams over all four tables once or twice per
+ *   call (two dense passes), as the paper's formulation does.
+ *   Workspace: gs_sgns_step_workspace_bytes().  Other arguments and errors as
+ *   for gs_sgns_step.
+ * ------------------------------------------------------------------------ */
+int32_t gs_sgns_momentum_step(void* w_in, void* w_out, void* m_in, void* m_out, int64_t num_nodes,
+                              int32_t dim, int32_t dtype, const int32_t* centers,
+                              const int32_t* contexts, const int32_t* negs, int64_t num_pairs,
+                              int32_t k, float lr, float mu, double* loss_sum_out, void* ws,
+                              size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

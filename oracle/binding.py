@@ -47,7 +47,7 @@ def _load():
         _lib = C.CDLL(build())
         for name in ("oracle_csr_build", "oracle_alias_build", "oracle_random_walk",
                      "oracle_node2vec_walk", "oracle_make_pairs", "oracle_sample_negatives",
-                     "oracle_sgns_step"):
+                     "oracle_sgns_step", "oracle_sgns_momentum_step"):
             getattr(_lib, name).restype = C.c_int32
         _lib.oracle_philox4x32_10.restype = None
     return _lib
@@ -199,4 +199,22 @@ def sgns_step(w_in, w_out, centers, contexts, negs, lr, dtype=F32):
                                   _ptr(contexts), _ptr(negs), C.c_int64(num_pairs), C.c_int32(k),
                                   C.c_float(lr), C.byref(loss))
     _check(rc, "oracle_sgns_step")
+    return loss.value
+
+
+def sgns_momentum_step(w_in, w_out, m_in, m_out, centers, contexts, negs, lr, mu, dtype=F32):
+    """SGD-with-momentum iteration; updates the four tables in place, returns the summed loss."""
+    want = np.float32 if dtype == F32 else np.uint16
+    for t in (w_in, w_out, m_in, m_out):
+        assert t.dtype == want and t.flags.c_contiguous and t.shape == w_in.shape
+    centers, contexts = _i32(centers), _i32(contexts)
+    negs = _i32(negs)
+    num_pairs = int(centers.shape[0])
+    k = int(negs.shape[1]) if negs.ndim == 2 else 0
+    loss = C.c_double(0.0)
+    rc = _load().oracle_sgns_momentum_step(
+        _ptr(w_in), _ptr(w_out), _ptr(m_in), _ptr(m_out), C.c_int64(w_in.shape[0]),
+        C.c_int32(w_in.shape[1]), C.c_int32(dtype), _ptr(centers), _ptr(contexts), _ptr(negs),
+        C.c_int64(num_pairs), C.c_int32(k), C.c_float(lr), C.c_float(mu), C.byref(loss))
+    _check(rc, "oracle_sgns_momentum_step")
     return loss.value

@@ -147,6 +147,58 @@ double sigmoid(double z) {
   return e / (1.0 + e);
 }
 
+double read_elem(const void* table, int32_t dtype, int32_t dim, int64_t row, int32_t e) {
+  if (dtype == ORACLE_F32) return (double)((const float*)table)[row * dim + e];
+  return (double)bf16_to_float(((const uint16_t*)table)[row * dim + e]);
+}
+
+void write_elem(void* table, int32_t dtype, int32_t dim, int64_t row, int32_t e, double value) {
+  if (dtype == ORACLE_F32) ((float*)table)[row * dim + e] = (float)value;
+  else ((uint16_t*)table)[row * dim + e] = float_to_bf16((float)value);
+}
+
+typedef std::unordered_map<int32_t, std::vector<double>> RowSums;
+
+// Gradient of the batch's summed SGNS loss with respect to the rows it names,
+// at the given tables, in fp64: d_in[c] = sum_j g_j v_j, d_out[row_j] = g_j u.
+int32_t sgns_gradients(const void* w_in, const void* w_out, int64_t num_nodes, int32_t dim,
+                       int32_t dtype, const int32_t* centers, const int32_t* contexts,
+                       const int32_t* negs, int64_t num_pairs, int32_t k, RowSums& d_in,
+                       RowSums& d_out, double* loss_sum_out) {
+  auto slot = [&](RowSums& m, int32_t row) -> std::vector<double>& {
+    auto it = m.find(row);
+    if (it == m.end()) it = m.emplace(row, std::vector<double>((size_t)dim, 0.0)).first;
+    return it->second;
+  };
+  double loss = 0.0;
+  std::vector<double> u((size_t)dim), v((size_t)dim);
+  for (int64_t i = 0; i < num_pairs; ++i) {
+    int32_t c = centers[i];
+    if (c < 0 || c >= num_nodes) return ORACLE_EINVAL;
+    for (int32_t e = 0; e < dim; ++e) u[(size_t)e] = read_elem(w_in, dtype, dim, c, e);
+    std::vector<double>& du = slot(d_in, c);
+    for (int32_t j = 0; j <= k; ++j) {
+      int32_t row = (j == 0) ? contexts[i] : negs[i * (int64_t)k + (j - 1)];
+      if (row < 0 || row >= num_nodes) return ORACLE_EINVAL;
+      double x = 0.0;
+      for (int32_t e = 0; e < dim; ++e) {
+        v[(size_t)e] = read_elem(w_out, dtype, dim, row, e);
+        x += u[(size_t)e] * v[(size_t)e];
+      }
+      double gj;
+      if (j == 0) { loss += softplus(-x); gj = sigmoid(x) - 1.0; }
+      else        { loss += softplus(x);  gj = sigmoid(x); }
+      std::vector<double>& dv = slot(d_out, row);
+      for (int32_t e = 0; e < dim; ++e) {
+        du[(size_t)e] += gj * v[(size_t)e];
+        dv[(size_t)e] += gj * u[(size_t)e];
+      }
+    }
+  }
+  *loss_sum_out = loss;
+  return ORACLE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -436,57 +488,62 @@ int32_t oracle_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int32_t dim
   if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_EINVAL;
   if (num_pairs > 0 && (!centers || !contexts || (k > 0 && !negs))) return ORACLE_EINVAL;
   if (!loss_sum_out) return ORACLE_EINVAL;
-
-  auto read = [&](const void* table, int64_t row, int32_t e) -> double {
-    if (dtype == ORACLE_F32) return (double)((const float*)table)[row * dim + e];
-    return (double)bf16_to_float(((const uint16_t*)table)[row * dim + e]);
-  };
-  auto write = [&](void* table, int64_t row, int32_t e, double value) {
-    if (dtype == ORACLE_F32) ((float*)table)[row * dim + e] = (float)value;
-    else ((uint16_t*)table)[row * dim + e] = float_to_bf16((float)value);
-  };
-
-  std::unordered_map<int32_t, std::vector<double>> d_in, d_out;
-  auto slot = [&](std::unordered_map<int32_t, std::vector<double>>& m, int32_t row)
-      -> std::vector<double>& {
-    auto it = m.find(row);
-    if (it == m.end()) it = m.emplace(row, std::vector<double>((size_t)dim, 0.0)).first;
-    return it->second;
-  };
-
-  double loss = 0.0;
-  std::vector<double> u((size_t)dim), v((size_t)dim);
-  for (int64_t i = 0; i < num_pairs; ++i) {
-    int32_t c = centers[i];
-    if (c < 0 || c >= num_nodes) return ORACLE_EINVAL;
-    for (int32_t e = 0; e < dim; ++e) u[(size_t)e] = read(w_in, c, e);
-    std::vector<double>& du = slot(d_in, c);
-    for (int32_t j = 0; j <= k; ++j) {
-      int32_t row = (j == 0) ? contexts[i] : negs[i * (int64_t)k + (j - 1)];
-      if (row < 0 || row >= num_nodes) return ORACLE_EINVAL;
-      double x = 0.0;
-      for (int32_t e = 0; e < dim; ++e) {
-        v[(size_t)e] = read(w_out, row, e);
-        x += u[(size_t)e] * v[(size_t)e];
-      }
-      double gj;
-      if (j == 0) { loss += softplus(-x); gj = sigmoid(x) - 1.0; }
-      else        { loss += softplus(x);  gj = sigmoid(x); }
-      std::vector<double>& dv = slot(d_out, row);
-      for (int32_t e = 0; e < dim; ++e) {
-        du[(size_t)e] += gj * v[(size_t)e];
-        dv[(size_t)e] += gj * u[(size_t)e];
-      }
-    }
-  }
+  RowSums d_in, d_out;
+  int32_t rc = sgns_gradients(w_in, w_out, num_nodes, dim, dtype, centers, contexts, negs, num_pairs,
+                              k, d_in, d_out, loss_sum_out);
+  if (rc != ORACLE_OK) return rc;
   const double step = (double)lr;
   for (auto& kv : d_in)
     for (int32_t e = 0; e < dim; ++e)
-      write(w_in, kv.first, e, read(w_in, kv.first, e) - step * kv.second[(size_t)e]);
+      write_elem(w_in, dtype, dim, kv.first, e,
+                 read_elem(w_in, dtype, dim, kv.first, e) - step * kv.second[(size_t)e]);
   for (auto& kv : d_out)
     for (int32_t e = 0; e < dim; ++e)
-      write(w_out, kv.first, e, read(w_out, kv.first, e) - step * kv.second[(size_t)e]);
-  *loss_sum_out = loss;
+      write_elem(w_out, dtype, dim, kv.first, e,
+                 read_elem(w_out, dtype, dim, kv.first, e) - step * kv.second[(size_t)e]);
+  return ORACLE_OK;
+}
+
+// ---------------------------------------------------------------------------
+// The same iteration with the optimizer the paper runs (§3.2, model update for
+// SGD with momentum as three storage operations), for both tables:
+//   mult      momentum <- mu * momentum                 (every row)
+//   put       momentum[r] <- momentum[r] + gradient[r]  (rows of the batch)
+//   mult_add  model <- model - lr * momentum            (every row)
+// The gradient is that of the batch's summed SGNS loss at the pre-iteration
+// model.  Each operation reads stored values and rounds once on writing.
+// ---------------------------------------------------------------------------
+int32_t oracle_sgns_momentum_step(void* w_in, void* w_out, void* m_in, void* m_out,
+                                  int64_t num_nodes, int32_t dim, int32_t dtype,
+                                  const int32_t* centers, const int32_t* contexts,
+                                  const int32_t* negs, int64_t num_pairs, int32_t k, float lr,
+                                  float mu, double* loss_sum_out) {
+  if (!w_in || !w_out || !m_in || !m_out || num_nodes < 1 || dim < 1 || num_pairs < 0 || k < 0)
+    return ORACLE_EINVAL;
+  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_EINVAL;
+  if (num_pairs > 0 && (!centers || !contexts || (k > 0 && !negs))) return ORACLE_EINVAL;
+  if (!loss_sum_out) return ORACLE_EINVAL;
+  RowSums d_in, d_out;
+  int32_t rc = sgns_gradients(w_in, w_out, num_nodes, dim, dtype, centers, contexts, negs, num_pairs,
+                              k, d_in, d_out, loss_sum_out);
+  if (rc != ORACLE_OK) return rc;
+  void* model[2] = {w_in, w_out};
+  void* moment[2] = {m_in, m_out};
+  RowSums* grad[2] = {&d_in, &d_out};
+  for (int tb = 0; tb < 2; ++tb) {
+    for (int64_t r = 0; r < num_nodes; ++r)
+      for (int32_t e = 0; e < dim; ++e)
+        write_elem(moment[tb], dtype, dim, r, e, (double)mu * read_elem(moment[tb], dtype, dim, r, e));
+    for (auto& kv : *grad[tb])
+      for (int32_t e = 0; e < dim; ++e)
+        write_elem(moment[tb], dtype, dim, kv.first, e,
+                   read_elem(moment[tb], dtype, dim, kv.first, e) + kv.second[(size_t)e]);
+    for (int64_t r = 0; r < num_nodes; ++r)
+      for (int32_t e = 0; e < dim; ++e)
+        write_elem(model[tb], dtype, dim, r, e,
+                   read_elem(model[tb], dtype, dim, r, e) -
+                       (double)lr * read_elem(moment[tb], dtype, dim, r, e));
+  }
   return ORACLE_OK;
 }
 

@@ -26,7 +26,7 @@ EXPORTS = (
     "gs_random_walk", "gs_node2vec_walk",
     "gs_make_pairs_workspace_bytes", "gs_make_pairs",
     "gs_sample_negatives",
-    "gs_sgns_step_workspace_bytes", "gs_sgns_step",
+    "gs_sgns_step_workspace_bytes", "gs_sgns_step", "gs_sgns_momentum_step",
 )
 
 
@@ -270,4 +270,27 @@ def gs_sgns_step(w_in, w_out, centers, contexts, negs, lr: float, loss_out=None,
                             _dev(loss_out, torch.float64, "loss_sum_out"), _dev(ws),
                             C.c_size_t(ws.numel()), _stream())
     _check(rc, "gs_sgns_step")
+    return loss_out
+
+
+def gs_sgns_momentum_step(w_in, w_out, m_in, m_out, centers, contexts, negs, lr: float, mu: float,
+                          loss_out=None, ws=None):
+    """SGD-with-momentum iteration (see gs.h); the four tables are updated in place."""
+    dtype = GS_BF16 if w_in.dtype == torch.bfloat16 else GS_F32
+    num_nodes, dim = int(w_in.shape[0]), int(w_in.shape[1])
+    num_pairs = int(centers.numel())
+    k = int(negs.shape[1]) if negs.dim() == 2 else 0
+    dev = w_in.device
+    if loss_out is None:
+        loss_out = torch.zeros(1, dtype=torch.float64, device=dev)
+    if ws is None:
+        ws = _workspace(gs_sgns_step_workspace_bytes(num_pairs, num_nodes, k, dim, dtype), dev)
+    rc = lib().gs_sgns_momentum_step(
+        _dev(w_in, None, "w_in"), _dev(w_out, w_in.dtype, "w_out"), _dev(m_in, w_in.dtype, "m_in"),
+        _dev(m_out, w_in.dtype, "m_out"), C.c_int64(num_nodes), C.c_int32(dim), C.c_int32(dtype),
+        _dev(centers, torch.int32, "centers"), _dev(contexts, torch.int32, "contexts"),
+        _dev(negs, torch.int32, "negs") if negs.numel() else None, C.c_int64(num_pairs),
+        C.c_int32(k), C.c_float(lr), C.c_float(mu), _dev(loss_out, torch.float64, "loss_sum_out"),
+        _dev(ws), C.c_size_t(ws.numel()), _stream())
+    _check(rc, "gs_sgns_momentum_step")
     return loss_out

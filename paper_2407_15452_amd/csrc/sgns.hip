@@ -56,8 +56,10 @@ struct Term {      // one (pair, j) contribution to a context-table row
 };
 
 struct SgnsArgs {
-  void* w_in;
+  void* w_in;               // tables the logits are computed from
   void* w_out;
+  void* dst_in;             // tables that receive round(old + delta): the same two for plain
+  void* dst_out;            // SGD, the momentum tables for the momentum step
   const int32_t* centers;
   const int32_t* contexts;
   const int32_t* negs;
@@ -453,7 +455,7 @@ __global__ __launch_bounds__(256) void sgns_place_kernel(SgnsArgs a) {
 template <typename T, int VPL, int UB>
 __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
   const T* __restrict__ w_in = static_cast<const T*>(a.w_in);
-  T* w_out = static_cast<T*>(a.w_out);
+  T* w_out = static_cast<T*>(a.dst_out);   // destination rows (old value and result)
   const int l16 = threadIdx.x & (kGroupLanes - 1);
   const int64_t group = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
   const int group_in_block = threadIdx.x / kGroupLanes;
@@ -585,7 +587,7 @@ __device__ __forceinline__ void elem_store(bf16_t* row, int e, float v) { row[e]
 // position of the window.
 template <typename T>
 __global__ __launch_bounds__(kSgnsThreads) void sgns_long_rows_kernel(SgnsArgs a) {
-  T* w_out = static_cast<T*>(a.w_out);
+  T* w_out = static_cast<T*>(a.dst_out);
   const int l16 = threadIdx.x & (kGroupLanes - 1);
   const int64_t s = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
   const int64_t last_pos = ((s + 1) << kLongShift) - 1;
@@ -634,7 +636,7 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_merge_kernel(SgnsArgs a) {
 
 template <typename T>
 __global__ __launch_bounds__(kSgnsThreads) void sgns_apply_kernel(SgnsArgs a) {
-  T* w_in = static_cast<T*>(a.w_in);
+  T* w_in = static_cast<T*>(a.dst_in);
   const int l16 = threadIdx.x & (kGroupLanes - 1);
   const int64_t group = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
   const int64_t s_mine = group * kGroupLanes + l16;
@@ -752,22 +754,58 @@ static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
 
 __global__ void zero_double_kernel(double* p) { *p = 0.0; }
 
-}  // namespace gs
-
-using namespace gs;
-
-extern "C" size_t gs_sgns_step_workspace_bytes(int64_t num_pairs, int64_t num_nodes, int32_t k,
-                                               int32_t dim, int32_t dtype) {
-  (void)dtype;
-  if (num_pairs < 0 || num_nodes < 0 || k < 0 || dim < 1) return 0;
-  return plan_sgns(nullptr, num_pairs, num_nodes, k, dim).bytes;
+// ---- dense passes of the momentum step (16 bytes per lane, grid-stride) ----------------
+// momentum <- mu * momentum over a whole table ("mult" of GraphScale Sec. 3.2)
+__global__ __launch_bounds__(256) void table_scale_kernel(float4* __restrict__ m, int64_t n4, float mu) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    float4 x = m[i];
+    x.x *= mu; x.y *= mu; x.z *= mu; x.w *= mu;
+    m[i] = x;
+  }
+}
+__global__ __launch_bounds__(256) void table_scale_kernel(uint4* __restrict__ m, int64_t n8, float mu) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    uint4 x = m[i];
+    x.x = pack_bf16(bf16_lo(x.x) * mu, bf16_hi(x.x) * mu);
+    x.y = pack_bf16(bf16_lo(x.y) * mu, bf16_hi(x.y) * mu);
+    x.z = pack_bf16(bf16_lo(x.z) * mu, bf16_hi(x.z) * mu);
+    x.w = pack_bf16(bf16_lo(x.w) * mu, bf16_hi(x.w) * mu);
+    m[i] = x;
+  }
+}
+// model <- model - lr * momentum over a whole table ("mult_add")
+__global__ __launch_bounds__(256) void table_axpy_kernel(float4* __restrict__ w,
+                                                         const float4* __restrict__ m, int64_t n4,
+                                                         float lr) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    float4 x = w[i];
+    const float4 y = m[i];
+    x.x -= lr * y.x; x.y -= lr * y.y; x.z -= lr * y.z; x.w -= lr * y.w;
+    w[i] = x;
+  }
+}
+__global__ __launch_bounds__(256) void table_axpy_kernel(uint4* __restrict__ w,
+                                                         const uint4* __restrict__ m, int64_t n8,
+                                                         float lr) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    uint4 x = w[i];
+    const uint4 y = m[i];
+    x.x = pack_bf16(bf16_lo(x.x) - lr * bf16_lo(y.x), bf16_hi(x.x) - lr * bf16_hi(y.x));
+    x.y = pack_bf16(bf16_lo(x.y) - lr * bf16_lo(y.y), bf16_hi(x.y) - lr * bf16_hi(y.y));
+    x.z = pack_bf16(bf16_lo(x.z) - lr * bf16_lo(y.z), bf16_hi(x.z) - lr * bf16_hi(y.z));
+    x.w = pack_bf16(bf16_lo(x.w) - lr * bf16_lo(y.w), bf16_hi(x.w) - lr * bf16_hi(y.w));
+    w[i] = x;
+  }
 }
 
-extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int32_t dim,
-                                int32_t dtype, const int32_t* centers, const int32_t* contexts,
-                                const int32_t* negs, int64_t num_pairs, int32_t k, float lr,
-                                double* loss_sum_out, void* ws, size_t ws_bytes, void* stream_) {
-  hipStream_t stream = (hipStream_t)stream_;
+static int32_t check_sgns_args(const void* w_in, const void* w_out, int64_t num_nodes, int32_t dim,
+                               int32_t dtype, const int32_t* centers, const int32_t* contexts,
+                               const int32_t* negs, int64_t num_pairs, int32_t k,
+                               const double* loss_sum_out, const void* ws) {
   if (!w_in || !w_out || num_nodes < 1 || num_nodes > (int64_t)INT32_MAX) return GS_EINVAL;
   if (dtype != GS_F32 && dtype != GS_BF16) return GS_EINVAL;
   const int granule = (dtype == GS_BF16) ? 8 : 4;   // elements per 16-byte piece
@@ -777,16 +815,20 @@ extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int3
   if (num_pairs * (int64_t)(k + 1) > (int64_t)0x7fffffff) return GS_EOVERFLOW;
   if (!aligned(w_in, 16) || !aligned(w_out, 16)) return GS_EINVAL;
   if (!ws || !aligned(ws, 256)) return GS_EINVAL;
-  SgnsPlan p = plan_sgns(ws, num_pairs, num_nodes, k, dim);
-  if (ws_bytes < p.bytes) return GS_EWORKSPACE;
-  if (num_pairs == 0) {
-    zero_double_kernel<<<1, 1, 0, stream>>>(loss_sum_out);
-    GS_LAUNCH_CHECK();
-    return GS_OK;
-  }
+  return GS_OK;
+}
+
+// Logits from (w_in, w_out); every touched row r of the destination tables becomes
+// round(dst[r] - lr * gradient_r).  Plain SGD: destination = the tables themselves.
+static int32_t run_sgns(void* w_in, void* w_out, void* dst_in, void* dst_out, int64_t num_nodes,
+                        int32_t dim, int32_t dtype, const int32_t* centers, const int32_t* contexts,
+                        const int32_t* negs, int64_t num_pairs, int32_t k, float lr,
+                        double* loss_sum_out, const SgnsPlan& p, hipStream_t stream) {
   SgnsArgs a;
   a.w_in = w_in;
   a.w_out = w_out;
+  a.dst_in = dst_in;
+  a.dst_out = dst_out;
   a.centers = centers;
   a.contexts = contexts;
   a.negs = negs;
@@ -824,4 +866,82 @@ extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int3
   if (vpl <= 4) return launch_sgns<bf16_t, 4, 3, 4>(a, stream);
   if (vpl <= 8) return launch_sgns<bf16_t, 8, 2, 2>(a, stream);
   return launch_sgns<bf16_t, 16, 1, 1>(a, stream);
+}
+
+}  // namespace gs
+
+using namespace gs;
+
+extern "C" size_t gs_sgns_step_workspace_bytes(int64_t num_pairs, int64_t num_nodes, int32_t k,
+                                               int32_t dim, int32_t dtype) {
+  (void)dtype;
+  if (num_pairs < 0 || num_nodes < 0 || k < 0 || dim < 1) return 0;
+  return plan_sgns(nullptr, num_pairs, num_nodes, k, dim).bytes;
+}
+
+extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int32_t dim,
+                                int32_t dtype, const int32_t* centers, const int32_t* contexts,
+                                const int32_t* negs, int64_t num_pairs, int32_t k, float lr,
+                                double* loss_sum_out, void* ws, size_t ws_bytes, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  const int32_t bad = check_sgns_args(w_in, w_out, num_nodes, dim, dtype, centers, contexts, negs,
+                                      num_pairs, k, loss_sum_out, ws);
+  if (bad != GS_OK) return bad;
+  SgnsPlan p = plan_sgns(ws, num_pairs, num_nodes, k, dim);
+  if (ws_bytes < p.bytes) return GS_EWORKSPACE;
+  if (num_pairs == 0) {
+    zero_double_kernel<<<1, 1, 0, stream>>>(loss_sum_out);
+    GS_LAUNCH_CHECK();
+    return GS_OK;
+  }
+  return run_sgns(w_in, w_out, w_in, w_out, num_nodes, dim, dtype, centers, contexts, negs, num_pairs,
+                  k, lr, loss_sum_out, p, stream);
+}
+
+extern "C" int32_t gs_sgns_momentum_step(void* w_in, void* w_out, void* m_in, void* m_out,
+                                         int64_t num_nodes, int32_t dim, int32_t dtype,
+                                         const int32_t* centers, const int32_t* contexts,
+                                         const int32_t* negs, int64_t num_pairs, int32_t k, float lr,
+                                         float mu, double* loss_sum_out, void* ws, size_t ws_bytes,
+                                         void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  const int32_t bad = check_sgns_args(w_in, w_out, num_nodes, dim, dtype, centers, contexts, negs,
+                                      num_pairs, k, loss_sum_out, ws);
+  if (bad != GS_OK) return bad;
+  if (!m_in || !m_out || !aligned(m_in, 16) || !aligned(m_out, 16)) return GS_EINVAL;
+  if (m_in == w_in || m_in == w_out || m_out == w_in || m_out == w_out || m_in == m_out)
+    return GS_EINVAL;
+  SgnsPlan p = plan_sgns(ws, num_pairs, num_nodes, k, dim);
+  if (ws_bytes < p.bytes) return GS_EWORKSPACE;
+  const int per16 = (dtype == GS_BF16) ? 8 : 4;
+  const int64_t pieces = num_nodes * (int64_t)dim / per16;
+  const unsigned blocks = (unsigned)min((int64_t)(256 * 64), ceil_div(pieces, 256));
+  // mult: momentum <- mu * momentum, every row
+  if (dtype == GS_F32) {
+    table_scale_kernel<<<blocks, 256, 0, stream>>>((float4*)m_in, pieces, mu);
+    table_scale_kernel<<<blocks, 256, 0, stream>>>((float4*)m_out, pieces, mu);
+  } else {
+    table_scale_kernel<<<blocks, 256, 0, stream>>>((uint4*)m_in, pieces, mu);
+    table_scale_kernel<<<blocks, 256, 0, stream>>>((uint4*)m_out, pieces, mu);
+  }
+  GS_LAUNCH_CHECK();
+  // put: momentum[rows of the batch] += gradient (the update machinery with step -1)
+  if (num_pairs == 0) {
+    zero_double_kernel<<<1, 1, 0, stream>>>(loss_sum_out);
+    GS_LAUNCH_CHECK();
+  } else {
+    const int32_t rc = run_sgns(w_in, w_out, m_in, m_out, num_nodes, dim, dtype, centers, contexts,
+                                negs, num_pairs, k, -1.0f, loss_sum_out, p, stream);
+    if (rc != GS_OK) return rc;
+  }
+  // mult_add: model <- model - lr * momentum, every row
+  if (dtype == GS_F32) {
+    table_axpy_kernel<<<blocks, 256, 0, stream>>>((float4*)w_in, (const float4*)m_in, pieces, lr);
+    table_axpy_kernel<<<blocks, 256, 0, stream>>>((float4*)w_out, (const float4*)m_out, pieces, lr);
+  } else {
+    table_axpy_kernel<<<blocks, 256, 0, stream>>>((uint4*)w_in, (const uint4*)m_in, pieces, lr);
+    table_axpy_kernel<<<blocks, 256, 0, stream>>>((uint4*)w_out, (const uint4*)m_out, pieces, lr);
+  }
+  GS_LAUNCH_CHECK();
+  return GS_OK;
 }

@@ -568,3 +568,69 @@ def test_packed_alias_layout_changes_nothing(gs, oracle, cfg0):
     a = gs.gs_sample_negatives(n_plain, wl.num_nodes, 20_000, 5, 11)
     b = gs.gs_sample_negatives(n_packed, wl.num_nodes, 20_000, 5, 11)
     assert torch.equal(a, b)
+
+
+# ----------------------------------------------------------------------------- SGD with momentum
+@pytest.mark.parametrize("dim,k,b,dtype", [(128, 5, 50_001, "f32"), (64, 3, 7_777, "f32"),
+                                           (256, 10, 9_999, "bf16")])
+def test_sgns_momentum_step(gs, oracle, dim, k, b, dtype):
+    """Three consecutive mult / put / mult_add iterations against the oracle."""
+    from paper_2407_15452_amd import inputs
+    n = 5000
+    f_in, f_out = inputs.random_tables(n, dim, seed=dim + k, scale=2.0 / dim ** 0.5)
+    m_a, m_b = inputs.random_tables(n, dim, seed=dim + k + 1, scale=0.01)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    tabs = [t.to(tdt) for t in (f_in, f_out, m_a, m_b)]
+    host = [_bf16_bits(t) if dtype == "bf16" else t.numpy().copy() for t in tabs]
+    dev = [t.to(DEV) for t in tabs]
+    odt = oracle.BF16 if dtype == "bf16" else oracle.F32
+    rng = np.random.default_rng(b)
+    lr, mu = 0.025, 0.9
+    for it in range(3):
+        c = np.repeat(rng.integers(0, n, b // 8 + 1), 8)[:b].astype(np.int32)
+        o = rng.integers(0, n, b).astype(np.int32)
+        neg = (n * rng.random((b, k)) ** 3).astype(np.int32)
+        old_model = [h.copy() for h in host[:2]]
+        want = oracle.sgns_momentum_step(*host, c, o, neg, lr, mu, dtype=odt)
+        loss = gs.gs_sgns_momentum_step(*dev, _t(c), _t(o), _t(neg), lr, mu)
+        torch.cuda.synchronize()
+        assert abs(float(loss.item()) - want) <= LOSS_RTOL * abs(want)
+        f32 = lambda bits: (bits.astype(np.uint32) << 16).view(np.float32)  # noqa: E731
+        for which, (d_t, h_t) in enumerate(zip(dev, host)):
+            if dtype == "bf16" and which >= 2:
+                # momentum tables: one rounding after the fp32 / fp64 gradient sum
+                got = _bf16_bits(d_t)
+                near = np.abs(got.astype(np.int32) - h_t.astype(np.int32)) <= 1
+                assert (near | (np.abs(f32(got) - f32(h_t)) <= EMB_ATOL)).all()
+                assert (got != h_t).mean() <= 2e-3
+            elif dtype == "bf16":
+                # model tables: a momentum entry that rounded the other way moves the model by
+                # lr times a whole bf16 step of the momentum, so the mult_add is checked against
+                # the momentum the GPU itself holds: w' = bf16(w - lr * m')
+                got = _bf16_bits(d_t)
+                m_new = f32(_bf16_bits(dev[which + 2]))
+                w_old = f32(old_model[which])
+                expect = w_old - np.float32(lr) * m_new
+                # within one bf16 step of the exact value (2^-7 relative to the larger operand)
+                scale = np.maximum(np.abs(w_old), np.abs(np.float32(lr) * m_new))
+                ratio = np.abs(f32(got) - expect) / (scale + 1e-30)
+                assert ratio.max() <= 2.0 ** -7, float(ratio.max())
+            else:
+                # momentum entries are unscaled gradient sums; in the hub rows of this batch
+                # they reach magnitudes of 50, where one fp32 step is already 3.8e-6: the
+                # absolute bound is widened by a few fp32 steps of the value itself
+                got = d_t.cpu().numpy()
+                assert (np.abs(got - h_t) <= EMB_ATOL + 1e-6 * np.abs(h_t)).all()
+        if dtype == "bf16":                                 # next iteration from a common state
+            for d_t, h_t in zip(dev, host):
+                d_t.copy_(torch.from_numpy(h_t.view(np.int16)).view(torch.bfloat16))
+
+
+def test_sgns_momentum_step_argument_errors(gs):
+    w = [torch.zeros((10, 8), dtype=torch.float32, device=DEV) for _ in range(4)]
+    i = torch.zeros(4, dtype=torch.int32, device=DEV)
+    n = torch.zeros((4, 2), dtype=torch.int32, device=DEV)
+    with pytest.raises(gs.GsError):            # momentum table aliasing a model table
+        gs.gs_sgns_momentum_step(w[0], w[1], w[0], w[3], i, i, n, 0.1, 0.9)
+    loss = gs.gs_sgns_momentum_step(*w, i, i, n, 0.1, 0.9)
+    assert float(loss.item()) == pytest.approx(4 * 3 * np.log(2.0))

@@ -181,3 +181,60 @@ def test_bf16_tables_round_to_nearest_even_once(oracle):
     got_in = torch.from_numpy(bits_in.view(np.int16)).view(torch.bfloat16)
     got_out = torch.from_numpy(bits_out.view(np.int16)).view(torch.bfloat16)
     assert torch.equal(got_in, want_in) and torch.equal(got_out, want_out)
+
+
+# ----------------------------------------------------------------------------- SGD with momentum
+def test_momentum_step_matches_torch_sgd(oracle):
+    """mult / put / mult_add (GraphScale §3.2) is torch.optim.SGD(momentum=mu) on the dense
+    tables: buf = mu * buf + grad, p -= lr * buf.  Three iterations on different batches."""
+    rng = np.random.default_rng(7)
+    n, d, b, k, lr, mu = 30, 8, 40, 3, 0.05, 0.9
+    w_in = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    w_out = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    m_in = np.zeros((n, d), dtype=np.float32)
+    m_out = np.zeros((n, d), dtype=np.float32)
+    ti = torch.tensor(w_in, dtype=torch.float64, requires_grad=True)
+    to = torch.tensor(w_out, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([ti, to], lr=float(np.float32(lr)), momentum=float(np.float32(mu)))
+    for it in range(3):
+        c, o, neg = _batch(rng, 20, b, k)                # rows 20..29 are never named
+        opt.zero_grad()
+        dense = _dense_loss(ti, to, c, o, neg)
+        dense.backward()
+        opt.step()
+        loss = oracle.sgns_momentum_step(w_in, w_out, m_in, m_out, c, o, neg, lr, mu)
+        assert loss == pytest.approx(dense.item(), rel=1e-6)
+        np.testing.assert_allclose(w_in, ti.detach().numpy(), atol=2e-6)
+        np.testing.assert_allclose(w_out, to.detach().numpy(), atol=2e-6)
+        np.testing.assert_allclose(m_in, opt.state[ti]["momentum_buffer"].numpy(), atol=2e-6)
+        np.testing.assert_allclose(m_out, opt.state[to]["momentum_buffer"].numpy(), atol=2e-6)
+    assert (m_in[20:] == 0).all() and np.abs(m_in[:20]).max() > 0
+
+
+def test_momentum_step_without_momentum_is_plain_sgd(oracle):
+    rng = np.random.default_rng(8)
+    n, d, b, k, lr = 25, 4, 60, 2, 0.1
+    w_in = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    w_out = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    c, o, neg = _batch(rng, n, b, k)
+    a_in, a_out = w_in.copy(), w_out.copy()
+    la = oracle.sgns_step(a_in, a_out, c, o, neg, lr)
+    m_in = rng.normal(0, 1, (n, d)).astype(np.float32)   # wiped by mu = 0
+    m_out = rng.normal(0, 1, (n, d)).astype(np.float32)
+    lb = oracle.sgns_momentum_step(w_in, w_out, m_in, m_out, c, o, neg, lr, 0.0)
+    assert la == lb
+    # w - lr * round32(G) against round32(w - lr * G): one extra fp32 rounding of the gradient
+    np.testing.assert_allclose(w_in, a_in, atol=1e-6)
+    np.testing.assert_allclose(w_out, a_out, atol=1e-6)
+
+
+def test_momentum_step_moves_every_row_with_momentum(oracle):
+    # a row the batch does not name still moves by -lr * mu * momentum (the dense mult_add)
+    w_in = np.ones((4, 2), dtype=np.float32)
+    w_out = np.ones((4, 2), dtype=np.float32)
+    m_in = np.full((4, 2), 0.5, dtype=np.float32)
+    m_out = np.full((4, 2), -0.25, dtype=np.float32)
+    oracle.sgns_momentum_step(w_in, w_out, m_in, m_out, [0], [1], np.array([[1]], dtype=np.int32),
+                              0.5, 0.5)
+    assert m_in[3, 0] == 0.25 and m_out[3, 0] == -0.125
+    assert w_in[3, 0] == 1.0 - 0.5 * 0.25 and w_out[3, 0] == 1.0 + 0.5 * 0.125
