@@ -75,7 +75,7 @@ def log(*a):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+        print("bench.py: the library runs on one GPU only (no sharding, no collectives); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
     if not torch.cuda.is_available():

@@ -44,6 +44,9 @@ constexpr int kScanThreads = 256;
 constexpr int kScanPerThread = 16;
 constexpr int kScanTile = kScanThreads * kScanPerThread;
 constexpr uint32_t kNoOwner = 0xffffffffu;
+constexpr int kHotBits = 8;                      // block-local rank counters in forward
+constexpr int kHotSlots = 1 << kHotBits;
+constexpr uint32_t kRankPending = 0x80000000u;   // rank still relative to the block (ranks < 2^31)
 
 typedef uint16_t bf16_t;           // bfloat16 storage
 
@@ -261,6 +264,14 @@ template <typename T, int VPL, int RB>
 __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) {
   extern __shared__ int32_t idx_s[];              // per group: centres[16], rows[16][K+1]
   __shared__ float loss_s[kGroupsPerBlock];
+  // Rank counters of rows that many terms hit at once are same-address atomics in
+  // memory, which serialise.  Each block therefore counts up to kHotSlots rows
+  // locally first (whichever rows reach a slot of this small LDS table first):
+  // a term of such a row takes a block-local rank, the block adds its total to
+  // the row's global counter once, and the ranks are completed afterwards.
+  __shared__ int32_t hot_key[kHotSlots];
+  __shared__ uint32_t hot_cnt[kHotSlots];
+  __shared__ uint32_t hot_base[kHotSlots];
   const T* __restrict__ w_in = static_cast<const T*>(a.w_in);
   const T* __restrict__ w_out = static_cast<const T*>(a.w_out);
   const int l16 = threadIdx.x & (kGroupLanes - 1);
@@ -275,6 +286,7 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
 
   int32_t* cen_s = idx_s + group_in_block * (kChunkPairs * (K1 + 1));
   int32_t* rows_s = cen_s + kChunkPairs;
+  for (int h = threadIdx.x; h < kHotSlots; h += kSgnsThreads) { hot_key[h] = -1; hot_cnt[h] = 0u; }
   if (l16 < count) cen_s[l16] = a.centers[first + l16];
   for (int t = l16; t < count * K1; t += kGroupLanes) {
     const int p = t / K1, j = t - p * K1;
@@ -304,7 +316,13 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
       const int my_j = j0 + l16;
       const bool mine = l16 < RB && my_j <= K;
       uint32_t rk = 0;
-      if (mine) rk = atomicAdd(a.cnt + prow[my_j], 1u);
+      if (mine) {
+        const int32_t row = prow[my_j];
+        const uint32_t h = ((uint32_t)row * 2654435761u) >> (32 - kHotBits);
+        const int32_t seen = atomicCAS(&hot_key[h], -1, row);
+        if (seen == -1 || seen == row) rk = kRankPending | (atomicAdd(&hot_cnt[h], 1u) << kHotBits) | h;
+        else rk = atomicAdd(a.cnt + row, 1u);
+      }
       float4 vv[RB][VPL];
 #pragma unroll
       for (int b = 0; b < RB; ++b)
@@ -332,6 +350,17 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
   loss = row_sum16(loss);
   if (l16 == 0) loss_s[group_in_block] = loss;
   __syncthreads();
+  // one global update per locally counted row, then complete the pending ranks
+  for (int h = threadIdx.x; h < kHotSlots; h += kSgnsThreads)
+    if (hot_key[h] >= 0) hot_base[h] = atomicAdd(a.cnt + hot_key[h], hot_cnt[h]);
+  __syncthreads();
+  for (int t = l16; t < count * K1; t += kGroupLanes) {
+    const int64_t e = first * (int64_t)K1 + t;
+    // written above by another lane of this group: read it back past the L1
+    const uint32_t rk = __hip_atomic_load(a.rank + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (rk & kRankPending)
+      a.rank[e] = hot_base[rk & (kHotSlots - 1)] + ((rk & ~kRankPending) >> kHotBits);
+  }
   if (threadIdx.x == 0 && block_live) {
     double s = 0.0;
 #pragma unroll
