@@ -212,6 +212,80 @@ __device__ __forceinline__ void axpy(float4 (&acc)[VPL], float c, const float4 (
   }
 }
 
+// A row as it was loaded, kept in as few registers as its storage type needs:
+// fp32 rows VPL float4, bf16 rows VPL/2 uint4 (widened element by element where
+// they are used).  Rows that wait in registers for their turn are held this way,
+// so a bf16 group keeps twice as many of them in flight.
+template <typename T, int VPL>
+struct RawRow;
+template <int VPL>
+struct RawRow<float, VPL> { float4 r[VPL]; };
+template <int VPL>
+struct RawRow<bf16_t, VPL> { uint4 r[VPL / 2]; };
+
+template <int VPL>
+__device__ __forceinline__ void load_raw(const float* __restrict__ table, int64_t row, int dim, int l16,
+                                         RawRow<float, VPL>& x) {
+  load_row<VPL>(table, row, dim, l16, x.r);
+}
+template <int VPL>
+__device__ __forceinline__ void load_raw(const bf16_t* __restrict__ table, int64_t row, int dim, int l16,
+                                         RawRow<bf16_t, VPL>& x) {
+  static_assert(VPL % 2 == 0, "bf16 rows are held as pairs of float4");
+  const uint4* p = reinterpret_cast<const uint4*>(table + row * (int64_t)dim);
+  const int chunks = dim >> 3;
+#pragma unroll
+  for (int w = 0; w < VPL / 2; ++w) {
+    const int c = w * kGroupLanes + l16;
+    x.r[w] = (c < chunks) ? p[c] : make_uint4(0u, 0u, 0u, 0u);
+  }
+}
+
+// Between two uses of a raw bf16 row: makes the compiler widen it again at the
+// second use instead of keeping the widened copy (twice the registers) alive.
+template <int VPL>
+__device__ __forceinline__ void rewiden_later(RawRow<float, VPL>&) {}
+template <int VPL>
+__device__ __forceinline__ void rewiden_later(RawRow<bf16_t, VPL>& x) {
+#pragma unroll
+  for (int w = 0; w < VPL / 2; ++w)
+    asm volatile("" : "+v"(x.r[w].x), "+v"(x.r[w].y), "+v"(x.r[w].z), "+v"(x.r[w].w));
+}
+
+template <int VPL>
+__device__ __forceinline__ float dot_partial(const float4 (&a)[VPL], const RawRow<float, VPL>& b) {
+  return dot_partial<VPL>(a, b.r);
+}
+template <int VPL>
+__device__ __forceinline__ float dot_partial(const float4 (&a)[VPL], const RawRow<bf16_t, VPL>& b) {
+  float s = 0.f;
+#pragma unroll
+  for (int w = 0; w < VPL / 2; ++w) {
+    const uint4 x = b.r[w];
+    s += a[2 * w].x * bf16_lo(x.x) + a[2 * w].y * bf16_hi(x.x) + a[2 * w].z * bf16_lo(x.y) +
+         a[2 * w].w * bf16_hi(x.y);
+    s += a[2 * w + 1].x * bf16_lo(x.z) + a[2 * w + 1].y * bf16_hi(x.z) + a[2 * w + 1].z * bf16_lo(x.w) +
+         a[2 * w + 1].w * bf16_hi(x.w);
+  }
+  return s;
+}
+
+template <int VPL>
+__device__ __forceinline__ void axpy(float4 (&acc)[VPL], float c, const RawRow<float, VPL>& x) {
+  axpy<VPL>(acc, c, x.r);
+}
+template <int VPL>
+__device__ __forceinline__ void axpy(float4 (&acc)[VPL], float c, const RawRow<bf16_t, VPL>& b) {
+#pragma unroll
+  for (int w = 0; w < VPL / 2; ++w) {
+    const uint4 x = b.r[w];
+    acc[2 * w].x += c * bf16_lo(x.x); acc[2 * w].y += c * bf16_hi(x.x);
+    acc[2 * w].z += c * bf16_lo(x.y); acc[2 * w].w += c * bf16_hi(x.y);
+    acc[2 * w + 1].x += c * bf16_lo(x.z); acc[2 * w + 1].y += c * bf16_hi(x.z);
+    acc[2 * w + 1].z += c * bf16_lo(x.w); acc[2 * w + 1].w += c * bf16_hi(x.w);
+  }
+}
+
 // loss and dLoss/dx of one term from its logit: one expf, one log1pf, one divide
 __device__ __forceinline__ void term_grad(float x, bool positive, float& g, float& loss) {
   const float e = expf(-fabsf(x));
@@ -323,10 +397,10 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
         if (seen == -1 || seen == row) rk = kRankPending | (atomicAdd(&hot_cnt[h], 1u) << kHotBits) | h;
         else rk = atomicAdd(a.cnt + row, 1u);
       }
-      float4 vv[RB][VPL];
+      RawRow<T, VPL> vv[RB];
 #pragma unroll
       for (int b = 0; b < RB; ++b)
-        if (j0 + b <= K) load_row<VPL>(w_out, prow[j0 + b], a.dim, l16, vv[b]);
+        if (j0 + b <= K) load_raw<VPL>(w_out, prow[j0 + b], a.dim, l16, vv[b]);
       float x_mine = 0.f;
 #pragma unroll
       for (int b = 0; b < RB; ++b) {
@@ -335,6 +409,8 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
           if (l16 == b) x_mine = x;
         }
       }
+#pragma unroll
+      for (int b = 0; b < RB; ++b) rewiden_later<VPL>(vv[b]);
       float g_mine = 0.f, l_mine = 0.f;
       if (mine) term_grad(x_mine, my_j == 0, g_mine, l_mine);
       loss += l_mine;
@@ -433,11 +509,20 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(uint32_t* __re
   const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanPerThread;
   uint32_t v[kScanPerThread];
   uint32_t local = 0;
+  const bool whole = base + kScanPerThread <= n;   // 64 aligned bytes: four 16-byte accesses
+  if (whole) {
+    const uint4* p4 = reinterpret_cast<const uint4*>(data + base);
 #pragma unroll
-  for (int k = 0; k < kScanPerThread; ++k) {
-    v[k] = (base + k < n) ? data[base + k] : 0u;
-    local += v[k];
+    for (int k4 = 0; k4 < kScanPerThread / 4; ++k4) {
+      const uint4 x = p4[k4];
+      v[4 * k4] = x.x; v[4 * k4 + 1] = x.y; v[4 * k4 + 2] = x.z; v[4 * k4 + 3] = x.w;
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < kScanPerThread; ++k) v[k] = (base + k < n) ? data[base + k] : 0u;
   }
+#pragma unroll
+  for (int k = 0; k < kScanPerThread; ++k) local += v[k];
   uint32_t incl = local;
 #pragma unroll
   for (int d = 1; d < 64; d <<= 1) {
@@ -450,10 +535,23 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(uint32_t* __re
 #pragma unroll
   for (int w = 0; w < kScanThreads / 64; ++w)
     if (w < wave) run += wave_tot[w];
+  if (whole) {
+    uint4* p4 = reinterpret_cast<uint4*>(data + base);
 #pragma unroll
-  for (int k = 0; k < kScanPerThread; ++k) {
-    if (base + k < n) data[base + k] = run;
-    run += v[k];
+    for (int k4 = 0; k4 < kScanPerThread / 4; ++k4) {
+      uint4 x;
+      x.x = run; run += v[4 * k4];
+      x.y = run; run += v[4 * k4 + 1];
+      x.z = run; run += v[4 * k4 + 2];
+      x.w = run; run += v[4 * k4 + 3];
+      p4[k4] = x;
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < kScanPerThread; ++k) {
+      if (base + k < n) data[base + k] = run;
+      run += v[k];
+    }
   }
 }
 
@@ -536,7 +634,7 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
 #pragma unroll
     for (int b0 = 0; b0 < kGroupLanes; b0 += UB) {
       if (b0 < n) {
-        float4 u[UB][VPL];
+        RawRow<T, VPL> u[UB];
         int32_t rows[UB];
         float coefs[UB];
         uint32_t lens[UB];
@@ -546,7 +644,7 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
           coefs[b] = __shfl(t.coef, b0 + b, kGroupLanes);
           lens[b] = __shfl(t.where, b0 + b, kGroupLanes) & 0xffffu;
           const int32_t center = __shfl(t.center, b0 + b, kGroupLanes);
-          if (b0 + b < n) load_row<VPL>(w_in, center, a.dim, l16, u[b]);
+          if (b0 + b < n) load_raw<VPL>(w_in, center, a.dim, l16, u[b]);
         }
 #pragma unroll
         for (int b = 0; b < UB; ++b) {
@@ -891,10 +989,10 @@ static int32_t run_sgns(void* w_in, void* w_out, void* dst_in, void* dst_out, in
     return launch_sgns<float, 16, 1, 1>(a, stream);
   }
   // bf16: a 16-byte piece is 8 elements = two float4, so the register count is even
-  if (vpl <= 2) return launch_sgns<bf16_t, 2, 6, 8>(a, stream);
-  if (vpl <= 4) return launch_sgns<bf16_t, 4, 3, 4>(a, stream);
-  if (vpl <= 8) return launch_sgns<bf16_t, 8, 2, 2>(a, stream);
-  return launch_sgns<bf16_t, 16, 1, 1>(a, stream);
+  if (vpl <= 2) return launch_sgns<bf16_t, 2, 6, 16>(a, stream);
+  if (vpl <= 4) return launch_sgns<bf16_t, 4, 6, 8>(a, stream);
+  if (vpl <= 8) return launch_sgns<bf16_t, 8, 4, 4>(a, stream);
+  return launch_sgns<bf16_t, 16, 2, 2>(a, stream);
 }
 
 }  // namespace gs
