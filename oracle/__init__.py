@@ -7,5 +7,5 @@ imports the product package.  See ``gs_oracle.cpp`` for what is computed.
 from .binding import (  # noqa: F401
     F32, BF16, SYMMETRIZE, DROP_SELF_LOOPS, DEDUPE,
     build, philox4x32_10, csr_build, alias_build, random_walk, node2vec_walk,
-    make_pairs, sample_negatives, sgns_step, sgns_momentum_step,
+    make_pairs, sample_negatives, sample_edges, sgns_step, sgns_momentum_step,
 )

@@ -47,7 +47,7 @@ def _load():
         _lib = C.CDLL(build())
         for name in ("oracle_csr_build", "oracle_alias_build", "oracle_random_walk",
                      "oracle_node2vec_walk", "oracle_make_pairs", "oracle_sample_negatives",
-                     "oracle_sgns_step", "oracle_sgns_momentum_step"):
+                     "oracle_sgns_step", "oracle_sgns_momentum_step", "oracle_sample_edges"):
             getattr(_lib, name).restype = C.c_int32
         _lib.oracle_philox4x32_10.restype = None
     return _lib
@@ -179,6 +179,20 @@ def sample_negatives(noise_alias, num_nodes, num_pairs, k, seed, pair_index_base
     _check(rc, "oracle_sample_negatives")
     del keep
     return out
+
+
+def sample_edges(offsets, nbrs, num_samples, seed, edge_alias=None, sample_index_base=0):
+    """LINE edge sampling: returns (centers, contexts), one CSR entry per sample."""
+    g, keep = _csr_struct(offsets, nbrs)
+    a, keep2 = _alias_struct(edge_alias)
+    centers = np.zeros(max(1, num_samples), dtype=np.int32)
+    contexts = np.zeros(max(1, num_samples), dtype=np.int32)
+    rc = _load().oracle_sample_edges(C.byref(g), None if a is None else C.byref(a),
+                                     C.c_int64(num_samples), C.c_uint64(sample_index_base),
+                                     C.c_uint64(seed), _ptr(centers), _ptr(contexts))
+    _check(rc, "oracle_sample_edges")
+    del keep, keep2
+    return centers[:num_samples], contexts[:num_samples]
 
 
 def sgns_step(w_in, w_out, centers, contexts, negs, lr, dtype=F32):

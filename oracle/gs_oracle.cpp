@@ -469,6 +469,36 @@ int32_t oracle_sample_negatives(const oracle_alias* noise, int64_t num_nodes, in
 }
 
 // ---------------------------------------------------------------------------
+// Edge sampling for LINE (§3.2: a LINE batch is B source nodes, one positive
+// and num_neg negative nodes each; §4 trains LINE next to DeepWalk).  Sample i
+// draws one CSR entry e with probability proportional to its weight (through an
+// alias table over all entries, treated as one segment) or uniformly when no
+// table is given, and returns (row that holds e, nbrs[e]).  In a symmetrised
+// graph every undirected edge is present in both directions, so either endpoint
+// can be the source.  Counter (sample index low, high, 0, 0x40000000).
+// Rows without entries are never a source: the source of entry e is the one
+// row r with offsets[r] <= e < offsets[r+1].
+// ---------------------------------------------------------------------------
+int32_t oracle_sample_edges(const oracle_csr* g, const oracle_alias* edge_alias, int64_t num_samples,
+                            uint64_t sample_index_base, uint64_t seed, int32_t* centers_out,
+                            int32_t* contexts_out) {
+  if (!g || g->num_nodes < 1 || g->num_entries < 1 || num_samples < 0) return ORACLE_EINVAL;
+  if (num_samples > 0 && (!centers_out || !contexts_out)) return ORACLE_EINVAL;
+  std::vector<int32_t> source((size_t)g->num_entries);   // the row that holds each entry
+  for (int64_t r = 0; r < g->num_nodes; ++r)
+    for (int64_t e = offset_at(g->offsets, g->offset_bits, r);
+         e < offset_at(g->offsets, g->offset_bits, r + 1); ++e)
+      source[(size_t)e] = (int32_t)r;
+  for (int64_t i = 0; i < num_samples; ++i) {
+    Block4 b = philox_keyed(seed, sample_index_base + (uint64_t)i, 0u, 0x40000000u);
+    const int64_t e = draw_in_row(edge_alias, 0, g->num_entries, b);
+    centers_out[i] = source[(size_t)e];
+    contexts_out[i] = g->nbrs[e];
+  }
+  return ORACLE_OK;
+}
+
+// ---------------------------------------------------------------------------
 // One SGNS iteration (§3.2: loss on the batch's rows, gradient only for those
 // rows, rows written back, barrier).  For pair i with u = W_in[c_i],
 // v_0 = W_out[o_i], v_k = W_out[neg_{i,k}] (k = 1..K), x_j = <u, v_j>:
