@@ -182,6 +182,27 @@ int32_t gs_sample_negatives(const gs_alias* noise, int64_t num_nodes, int64_t nu
                             int32_t* negs_out, void* stream);
 
 /* --------------------------------------------------------------------------
+ * gs_sample_edges -- the positive pairs of a LINE batch (Sec. 3.2: a LINE batch
+ * of B source nodes holds B * (2 + num_neg) nodes; Sec. 4 trains LINE with 5
+ * negatives per source node).  Sample i draws one CSR entry e, uniformly when
+ * edge_alias is NULL or has prob == NULL, otherwise as an alias draw from one
+ * table over all g->num_entries entries (gs_alias_build with the single
+ * segment {0, num_entries} over the entry weights; alias[] = entry index),
+ * with counter (idx low, idx high, 0, 0x40000000), idx = sample_index_base +
+ * i, and returns centers_out[i] = the row that holds e, contexts_out[i] =
+ * nbrs[e].  In a symmetrised graph both directions of an edge are entries.
+ * The batch is then an ordinary gs_sgns_step batch (second-order proximity:
+ * source rows in w_in, context rows in w_out) with negatives from
+ * gs_sample_negatives.
+ *   centers_out, contexts_out  int32[num_samples] on the device.
+ *   Errors: GS_EINVAL for an empty graph (num_entries < 1), offset_bits other
+ *   than 32 / 64, or a prob without alias.
+ * ------------------------------------------------------------------------ */
+int32_t gs_sample_edges(const gs_csr* g, const gs_alias* edge_alias, int64_t num_samples,
+                        uint64_t sample_index_base, uint64_t seed, int32_t* centers_out,
+                        int32_t* contexts_out, void* stream);
+
+/* --------------------------------------------------------------------------
  * gs_sgns_step -- one training iteration of Sec. 3.2: fetch the batch's rows,
  * loss and sparse gradient on them, write those rows back; reads see the
  * tables as they were before the call (the barrier of "Synchronization").

@@ -25,7 +25,7 @@ EXPORTS = (
     "gs_alias_build_workspace_bytes", "gs_alias_build", "gs_alias_pack",
     "gs_random_walk", "gs_node2vec_walk",
     "gs_make_pairs_workspace_bytes", "gs_make_pairs",
-    "gs_sample_negatives",
+    "gs_sample_negatives", "gs_sample_edges",
     "gs_sgns_step_workspace_bytes", "gs_sgns_step", "gs_sgns_momentum_step",
 )
 
@@ -242,6 +242,22 @@ def gs_sample_negatives(noise, num_nodes: int, num_pairs: int, k: int, seed: int
                                    _dev(out, torch.int32, "negs_out"), _stream())
     _check(rc, "gs_sample_negatives")
     return out
+
+
+def gs_sample_edges(g: Csr, edge_alias, num_samples: int, seed: int, sample_index_base: int = 0,
+                    centers_out=None, contexts_out=None):
+    """LINE positive pairs: returns (centers, contexts), one CSR entry per sample."""
+    dev = g.nbrs.device
+    if centers_out is None:
+        centers_out = torch.empty(max(num_samples, 0), dtype=torch.int32, device=dev)
+    if contexts_out is None:
+        contexts_out = torch.empty(max(num_samples, 0), dtype=torch.int32, device=dev)
+    rc = lib().gs_sample_edges(C.byref(g.struct), _alias_ref(edge_alias), C.c_int64(num_samples),
+                               C.c_uint64(sample_index_base), C.c_uint64(seed),
+                               _dev(centers_out, torch.int32, "centers_out"),
+                               _dev(contexts_out, torch.int32, "contexts_out"), _stream())
+    _check(rc, "gs_sample_edges")
+    return centers_out, contexts_out
 
 
 def gs_sgns_step_workspace_bytes(num_pairs: int, num_nodes: int, k: int, dim: int,

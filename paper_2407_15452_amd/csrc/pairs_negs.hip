@@ -99,6 +99,37 @@ __global__ void negatives_kernel(const float* __restrict__ prob, const int32_t* 
   negs[e] = (int32_t)s;
 }
 
+// One lane per LINE sample: draw an entry, then find the row that holds it
+// (the last row whose offset is <= e; empty rows share their offset with the
+// next row and are skipped by taking the last one).
+template <typename OffT>
+__global__ void edges_kernel(const OffT* __restrict__ offsets, int64_t num_nodes,
+                             const int32_t* __restrict__ nbrs, uint64_t num_entries,
+                             const float* __restrict__ prob, const int32_t* __restrict__ alias,
+                             const uint2* __restrict__ packed, int64_t num_samples,
+                             uint64_t sample_base, uint64_t seed, int32_t* __restrict__ centers,
+                             int32_t* __restrict__ contexts) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= num_samples) return;
+  const Block4 b = philox_at(seed, sample_base + (uint64_t)i, 0u, 0x40000000u);
+  int64_t e = (int64_t)slot_of(b, num_entries);
+  if (packed != nullptr) {
+    const uint2 e2 = packed[e];
+    if (!(unit_float(b.x2) < __uint_as_float(e2.x))) e = (int64_t)(int32_t)e2.y;
+  } else if (prob != nullptr) {
+    if (!(unit_float(b.x2) < prob[e])) e = (int64_t)alias[e];
+  }
+  const int32_t dst = nbrs[e];
+  // first t in [1, num_nodes] with offsets[t] > e; offsets[num_nodes] = num_entries > e
+  int64_t lo = 1, hi = num_nodes;
+  while (lo < hi) {
+    const int64_t mid = (lo + hi) >> 1;
+    if ((int64_t)offsets[mid] > e) hi = mid; else lo = mid + 1;
+  }
+  centers[i] = (int32_t)(lo - 1);
+  contexts[i] = dst;
+}
+
 struct PairsPlan {
   int64_t *bases, *scan_scratch;
   size_t bytes;
@@ -167,6 +198,35 @@ extern "C" int32_t gs_sample_negatives(const gs_alias* noise, int64_t num_nodes,
       weighted ? noise->prob : nullptr, weighted ? noise->alias : nullptr,
       weighted ? reinterpret_cast<const uint2*>(noise->packed) : nullptr, (uint64_t)num_nodes, total,
       pair_index_base, k, seed, negs_out);
+  GS_LAUNCH_CHECK();
+  return GS_OK;
+}
+
+extern "C" int32_t gs_sample_edges(const gs_csr* g, const gs_alias* edge_alias, int64_t num_samples,
+                                   uint64_t sample_index_base, uint64_t seed, int32_t* centers_out,
+                                   int32_t* contexts_out, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  if (!g || g->num_nodes < 1 || g->num_nodes > (int64_t)INT32_MAX || g->num_entries < 1 ||
+      !g->offsets || !g->nbrs || num_samples < 0)
+    return GS_EINVAL;
+  if (g->offset_bits != 32 && g->offset_bits != 64) return GS_EINVAL;
+  if (num_samples > 0 && (!centers_out || !contexts_out)) return GS_EINVAL;
+  const bool weighted = edge_alias != nullptr && edge_alias->prob != nullptr;
+  if (weighted && !edge_alias->alias) return GS_EINVAL;
+  if (num_samples == 0) return GS_OK;
+  if (ceil_div(num_samples, 256) > (int64_t)INT32_MAX) return GS_EOVERFLOW;
+  const float* prob = weighted ? edge_alias->prob : nullptr;
+  const int32_t* alias = weighted ? edge_alias->alias : nullptr;
+  const uint2* packed = weighted ? reinterpret_cast<const uint2*>(edge_alias->packed) : nullptr;
+  const unsigned blocks = (unsigned)ceil_div(num_samples, 256);
+  if (g->offset_bits == 32)
+    edges_kernel<int32_t><<<blocks, 256, 0, stream>>>(
+        static_cast<const int32_t*>(g->offsets), g->num_nodes, g->nbrs, (uint64_t)g->num_entries, prob,
+        alias, packed, num_samples, sample_index_base, seed, centers_out, contexts_out);
+  else
+    edges_kernel<int64_t><<<blocks, 256, 0, stream>>>(
+        static_cast<const int64_t*>(g->offsets), g->num_nodes, g->nbrs, (uint64_t)g->num_entries, prob,
+        alias, packed, num_samples, sample_index_base, seed, centers_out, contexts_out);
   GS_LAUNCH_CHECK();
   return GS_OK;
 }
