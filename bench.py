@@ -253,6 +253,34 @@ def main():
         momentum_ms = e0.elapsed_time(e1) / 5
         del m_in, m_out
 
+    # ------------------------------------------------------------------ LINE batches (extra)
+    # B sampled edges (uniform over the CSR entries) + negatives + the same step
+    line = None
+    if True:
+        lc = torch.empty(B, dtype=torch.int32, device=dev)
+        lo_ = torch.empty(B, dtype=torch.int32, device=dev)
+
+        def line_batch(it):
+            gs.gs_sample_edges(g, None, B, wl.walk_seed ^ 0x4c494e45, sample_index_base=it * B,
+                               centers_out=lc, contexts_out=lo_)
+            gs.gs_sample_negatives(noise, wl.num_nodes, B, k, wl.neg_seed ^ 0x4c494e45,
+                                   pair_index_base=it * B, out=negs)
+            gs.gs_sgns_step(w_in, w_out, lc, lo_, negs, lr, loss_out=losses[:1], ws=sgns_ws)
+
+        for it in range(2):
+            line_batch(it)
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for it in range(2, 7):
+            line_batch(it)
+        e1.record()
+        torch.cuda.synchronize()
+        line_ms = e0.elapsed_time(e1) / 5
+        line = {"ms_per_batch": line_ms, "edges_per_s": B / (line_ms * 1e-3),
+                "what": "gs_sample_edges + gs_sample_negatives + gs_sgns_step per batch of B edges"}
+        del lc, lo_
+
     walk_kind = ("node2vec p=%g q=%g" % (wl.p, wl.q)) if wl.node2vec else "first-order"
     walk_kind += ", alias-weighted" if wl.weighted else ", uniform"
     result = {
@@ -273,6 +301,7 @@ def main():
                       "chunk_walks": int(starts_timed.numel())},
         "mean_loss_per_pair": mean_loss,
         "momentum_step_ms": momentum_ms,
+        "line": line,
         "roofline": {"bound": "hbm", "kernel": "gs_sgns_step (all kernels of one call)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "bytes_per_pair": bpp,
