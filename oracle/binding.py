@@ -47,7 +47,8 @@ def _load():
         _lib = C.CDLL(build())
         for name in ("oracle_csr_build", "oracle_alias_build", "oracle_random_walk",
                      "oracle_node2vec_walk", "oracle_make_pairs", "oracle_sample_negatives",
-                     "oracle_sgns_step", "oracle_sgns_momentum_step", "oracle_sample_edges"):
+                     "oracle_sgns_step", "oracle_sgns_momentum_step", "oracle_sample_edges", "oracle_unique_ids", "oracle_get_rows",
+                     "oracle_put_rows"):
             getattr(_lib, name).restype = C.c_int32
         _lib.oracle_philox4x32_10.restype = None
     return _lib
@@ -232,3 +233,43 @@ def sgns_momentum_step(w_in, w_out, m_in, m_out, centers, contexts, negs, lr, mu
         C.c_int64(num_pairs), C.c_int32(k), C.c_float(lr), C.c_float(mu), C.byref(loss))
     _check(rc, "oracle_sgns_momentum_step")
     return loss.value
+
+
+def unique_ids(ids, num_nodes):
+    """Returns (unique ascending, inverse): ids outside [0, num_nodes) are left out, inverse -1."""
+    ids = _i32(ids)
+    n = int(ids.shape[0])
+    uniq = np.zeros(max(1, n), dtype=np.int32)
+    inverse = np.zeros(max(1, n), dtype=np.int32)
+    count = C.c_int64(0)
+    rc = _load().oracle_unique_ids(_ptr(ids), C.c_int64(n), C.c_int64(num_nodes), _ptr(uniq),
+                                   C.byref(count), _ptr(inverse))
+    _check(rc, "oracle_unique_ids")
+    return uniq[:count.value].copy(), inverse[:n].copy()
+
+
+def get_rows(table, ids, dtype=F32):
+    """table[ids] as float32 [n, dim] (zero rows for ids out of range)."""
+    want = np.float32 if dtype == F32 else np.uint16
+    assert table.dtype == want and table.flags.c_contiguous
+    ids = _i32(ids)
+    n = int(ids.shape[0])
+    out = np.zeros((max(1, n), table.shape[1]), dtype=np.float32)
+    rc = _load().oracle_get_rows(_ptr(table), C.c_int64(table.shape[0]), C.c_int32(table.shape[1]),
+                                 C.c_int32(dtype), _ptr(ids), C.c_int64(n), _ptr(out))
+    _check(rc, "oracle_get_rows")
+    return out[:n]
+
+
+def put_rows(table, ids, rows, scale, dtype=F32):
+    """table[ids[i]] += scale * rows[i] in place (distinct ids)."""
+    want = np.float32 if dtype == F32 else np.uint16
+    assert table.dtype == want and table.flags.c_contiguous
+    ids = _i32(ids)
+    rows = np.ascontiguousarray(rows, dtype=np.float32)
+    n = int(ids.shape[0])
+    assert rows.shape == (n, table.shape[1])
+    rc = _load().oracle_put_rows(_ptr(table), C.c_int64(table.shape[0]), C.c_int32(table.shape[1]),
+                                 C.c_int32(dtype), _ptr(ids), C.c_int64(n), _ptr(rows),
+                                 C.c_float(scale))
+    _check(rc, "oracle_put_rows")

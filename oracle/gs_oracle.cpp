@@ -577,4 +577,67 @@ int32_t oracle_sgns_momentum_step(void* w_in, void* w_out, void* m_in, void* m_o
   return ORACLE_OK;
 }
 
+
+// ---------------------------------------------------------------------------
+// The storage operations of §3.1 / §3.2 on a batch of vertex ids: a trainer
+// merges equal ids of its batch into one request, fetches one n x d block of
+// rows (get), and sends back one block of gradient rows that the storage adds
+// to its rows (put).
+//
+// unique: the distinct ids of the batch in ascending order, and for every
+// batch entry the position of its id in that list.  Ids outside [0, num_nodes)
+// belong to no row: they are left out and their position is -1.
+// ---------------------------------------------------------------------------
+int32_t oracle_unique_ids(const int32_t* ids, int64_t n, int64_t num_nodes, int32_t* unique_out,
+                          int64_t* num_unique_out, int32_t* inverse_out) {
+  if (n < 0 || num_nodes < 1 || !num_unique_out || (n > 0 && (!ids || !unique_out)))
+    return ORACLE_EINVAL;
+  std::vector<int32_t> sorted;
+  for (int64_t i = 0; i < n; ++i)
+    if (ids[i] >= 0 && (int64_t)ids[i] < num_nodes) sorted.push_back(ids[i]);
+  std::sort(sorted.begin(), sorted.end());
+  sorted.erase(std::unique(sorted.begin(), sorted.end()), sorted.end());
+  for (size_t j = 0; j < sorted.size(); ++j) unique_out[j] = sorted[j];
+  *num_unique_out = (int64_t)sorted.size();
+  if (inverse_out)
+    for (int64_t i = 0; i < n; ++i) {
+      auto it = std::lower_bound(sorted.begin(), sorted.end(), ids[i]);
+      inverse_out[i] = (it != sorted.end() && *it == ids[i]) ? (int32_t)(it - sorted.begin()) : -1;
+    }
+  return ORACLE_OK;
+}
+
+// get: out[i] = table[ids[i]] as fp32 (bf16 widened exactly); a zero row for an
+// id outside [0, num_nodes).
+int32_t oracle_get_rows(const void* table, int64_t num_nodes, int32_t dim, int32_t dtype,
+                        const int32_t* ids, int64_t n, float* out) {
+  if (!table || num_nodes < 1 || dim < 1 || n < 0 || (n > 0 && (!ids || !out))) return ORACLE_EINVAL;
+  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_EINVAL;
+  for (int64_t i = 0; i < n; ++i)
+    for (int32_t e = 0; e < dim; ++e) {
+      const bool ok = ids[i] >= 0 && (int64_t)ids[i] < num_nodes;
+      out[i * (int64_t)dim + e] = ok ? (float)read_elem(table, dtype, dim, ids[i], e) : 0.0f;
+    }
+  return ORACLE_OK;
+}
+
+// put: table[ids[i]] <- round(table[ids[i]] + scale * rows[i]), ids distinct
+// (an id outside [0, num_nodes) is skipped).  One rounding per element.
+int32_t oracle_put_rows(void* table, int64_t num_nodes, int32_t dim, int32_t dtype, const int32_t* ids,
+                        int64_t n, const float* rows, float scale) {
+  if (!table || num_nodes < 1 || dim < 1 || n < 0 || (n > 0 && (!ids || !rows))) return ORACLE_EINVAL;
+  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_EINVAL;
+  std::vector<int32_t> seen(ids, ids + n);
+  std::sort(seen.begin(), seen.end());
+  for (size_t j = 1; j < seen.size(); ++j)
+    if (seen[j] == seen[j - 1] && seen[j] >= 0 && (int64_t)seen[j] < num_nodes) return ORACLE_EINVAL;
+  for (int64_t i = 0; i < n; ++i) {
+    if (ids[i] < 0 || (int64_t)ids[i] >= num_nodes) continue;
+    for (int32_t e = 0; e < dim; ++e)
+      write_elem(table, dtype, dim, ids[i], e,
+                 read_elem(table, dtype, dim, ids[i], e) + (double)scale * (double)rows[i * (int64_t)dim + e]);
+  }
+  return ORACLE_OK;
+}
+
 }  // extern "C"

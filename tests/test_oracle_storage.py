@@ -1,0 +1,108 @@
+"""Pins for the oracle's storage operations on a batch of ids (unique / get / put).
+
+They reduce to library routines: numpy.unique with its inverse, fancy indexing,
+numpy.add.at; bf16 through torch's conversions.  Together they give the sparse
+update the paper describes: a put of summed gradient rows onto the distinct ids
+of a batch equals the dense update with a gradient that is zero elsewhere.
+"""
+import numpy as np
+import pytest
+import torch
+
+
+def _bf16_bits(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def _bf16_vals(bits):
+    return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float32).numpy()
+
+
+def test_unique_matches_numpy(oracle):
+    rng = np.random.default_rng(0)
+    ids = rng.integers(0, 50, 400).astype(np.int32)
+    u, inv = oracle.unique_ids(ids, 50)
+    wu, winv = np.unique(ids, return_inverse=True)
+    np.testing.assert_array_equal(u, wu)
+    np.testing.assert_array_equal(inv, winv)
+    np.testing.assert_array_equal(u[inv], ids)
+
+
+def test_unique_edge_cases(oracle):
+    u, inv = oracle.unique_ids(np.zeros(0, dtype=np.int32), 5)
+    assert u.size == 0 and inv.size == 0
+    u, inv = oracle.unique_ids([4, 4, 4], 5)
+    np.testing.assert_array_equal(u, [4]); np.testing.assert_array_equal(inv, [0, 0, 0])
+    u, inv = oracle.unique_ids([7, -3, 2, 5, 2, 9], 6)          # 7, -3, 9 are not rows
+    np.testing.assert_array_equal(u, [2, 5]); np.testing.assert_array_equal(inv, [-1, -1, 0, 1, 0, -1])
+
+
+def test_get_is_fancy_indexing(oracle):
+    rng = np.random.default_rng(1)
+    t = rng.normal(size=(30, 6)).astype(np.float32)
+    ids = np.array([3, 29, 3, 0, 30, -1], dtype=np.int32)
+    got = oracle.get_rows(t, ids)
+    np.testing.assert_array_equal(got[:4], t[ids[:4]])
+    assert (got[4:] == 0).all()
+    bits = _bf16_bits(t)
+    got = oracle.get_rows(bits, ids, dtype=oracle.BF16)
+    np.testing.assert_array_equal(got[:4], _bf16_vals(bits)[ids[:4]])
+
+
+def test_put_is_add_at(oracle):
+    rng = np.random.default_rng(2)
+    t = rng.normal(size=(40, 5)).astype(np.float32)
+    ids = rng.permutation(40)[:17].astype(np.int32)
+    rows = rng.normal(size=(17, 5)).astype(np.float32)
+    want = t.astype(np.float64)
+    np.add.at(want, ids, -0.25 * rows.astype(np.float64))
+    got = t.copy()
+    oracle.put_rows(got, ids, rows, -0.25)
+    np.testing.assert_array_equal(got, want.astype(np.float32))
+    untouched = np.setdiff1d(np.arange(40), ids)
+    np.testing.assert_array_equal(got[untouched], t[untouched])
+    # ids that are not rows are skipped, duplicates are refused
+    got2 = t.copy()
+    oracle.put_rows(got2, np.array([1, 40, -2], dtype=np.int32), rows[:3], 1.0)
+    np.testing.assert_array_equal(got2[1], (t[1].astype(np.float64) + rows[0]).astype(np.float32))
+    np.testing.assert_array_equal(np.delete(got2, 1, 0), np.delete(t, 1, 0))
+    with pytest.raises(ValueError):
+        oracle.put_rows(t.copy(), np.array([1, 1], dtype=np.int32), rows[:2], 1.0)
+
+
+def test_put_bf16_rounds_once(oracle):
+    rng = np.random.default_rng(3)
+    t = rng.normal(size=(20, 8)).astype(np.float32)
+    bits = _bf16_bits(t)
+    ids = np.array([0, 19, 7], dtype=np.int32)
+    rows = rng.normal(size=(3, 8)).astype(np.float32)
+    want = _bf16_vals(bits).astype(np.float64)
+    want[ids] += 0.5 * rows.astype(np.float64)
+    got = bits.copy()
+    oracle.put_rows(got, ids, rows, 0.5, dtype=oracle.BF16)
+    np.testing.assert_array_equal(got, _bf16_bits(want.astype(np.float32)))
+
+
+def test_unique_get_put_give_the_sparse_sgd_step(oracle):
+    """get the distinct rows, compute on the n x d block, put the summed deltas:
+    the result equals the SGNS step on the full tables (the paper's sparse update)."""
+    rng = np.random.default_rng(4)
+    n, d, B, K = 60, 4, 32, 3
+    w_in = rng.uniform(-0.5, 0.5, (n, d)).astype(np.float32)
+    w_out = rng.uniform(-0.5, 0.5, (n, d)).astype(np.float32)
+    c = rng.integers(0, n, B).astype(np.int32)
+    o = rng.integers(0, n, B).astype(np.int32)
+    neg = rng.integers(0, n, (B, K)).astype(np.int32)
+    full_in, full_out = w_in.copy(), w_out.copy()
+    oracle.sgns_step(full_in, full_out, c, o, neg, 0.1)
+    # the same through the block: ids of the batch, compacted tables, local step, put of the deltas
+    ids = np.concatenate([c, o, neg.ravel()])
+    u, inv = oracle.unique_ids(ids, n)
+    blk_in, blk_out = oracle.get_rows(w_in, u), oracle.get_rows(w_out, u)
+    new_in, new_out = blk_in.copy(), blk_out.copy()
+    oracle.sgns_step(new_in, new_out, inv[:B], inv[B:2 * B], inv[2 * B:].reshape(B, K), 0.1)
+    got_in, got_out = w_in.copy(), w_out.copy()
+    oracle.put_rows(got_in, u, new_in.astype(np.float64) - blk_in, 1.0)
+    oracle.put_rows(got_out, u, new_out.astype(np.float64) - blk_out, 1.0)
+    np.testing.assert_allclose(got_in, full_in, atol=1e-6)
+    np.testing.assert_allclose(got_out, full_out, atol=1e-6)
