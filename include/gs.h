@@ -250,6 +250,44 @@ int32_t gs_sgns_momentum_step(void* w_in, void* w_out, void* m_in, void* m_out, 
                               int32_t k, float lr, float mu, double* loss_sum_out, void* ws,
                               size_t ws_bytes, void* stream);
 
+/* --------------------------------------------------------------------------
+ * Storage operations on a batch of vertex ids (Sec. 3.1: a trainer merges equal
+ * vertex ids before it makes a single request and gets one block of rows back;
+ * Sec. 3.2: only the n << N rows of a mini-batch are fetched, and only an
+ * n x d block of gradient rows is sent back and added to the storage).
+ *
+ * gs_unique_ids -- distinct ids of the batch in ascending order.
+ *   ids int32[n] (n < 2^31).  unique_out int32[n] (the first *num_unique_out
+ *   entries are written), num_unique_out int64[1] on the device, inverse_out
+ *   int32[n] or NULL: position of ids[i] in unique_out.  Ids outside
+ *   [0, num_nodes) are left out of unique_out and get inverse -1.
+ *
+ * gs_get_rows -- out[i] = table[ids[i]] for i < n, as fp32 (bf16 rows widened
+ *   exactly); a zero row for an id outside [0, num_nodes).  out float[n][dim].
+ *
+ * gs_put_rows -- table[ids[i]] = round(table[ids[i]] + scale * rows[i]), one
+ *   rounding per element (fp32 tables: of the exact sum to fp64 then fp32; bf16
+ *   tables: from there to bf16, nearest even).  rows float[n][dim].  The ids
+ *   must be distinct (as gs_unique_ids returns them): rows of equal ids race.
+ *   Ids outside [0, num_nodes) are skipped.
+ *
+ *   count_dev (both calls): NULL, or int64[1] on the device: only the first
+ *   min(n, *count_dev) ids are processed, so that the count written by
+ *   gs_unique_ids can be used without a host round trip.
+ *   table [num_nodes][dim] of dtype GS_F32 | GS_BF16, 16-byte aligned; dim a
+ *   multiple of 4 (fp32) or 8 (bf16).  Errors: GS_EINVAL otherwise.
+ * ------------------------------------------------------------------------ */
+size_t gs_unique_ids_workspace_bytes(int64_t n);
+int32_t gs_unique_ids(const int32_t* ids, int64_t n, int64_t num_nodes, int32_t* unique_out,
+                      int64_t* num_unique_out, int32_t* inverse_out, void* ws, size_t ws_bytes,
+                      void* stream);
+int32_t gs_get_rows(const void* table, int64_t num_nodes, int32_t dim, int32_t dtype,
+                    const int32_t* ids, int64_t n, const int64_t* count_dev, float* out,
+                    void* stream);
+int32_t gs_put_rows(void* table, int64_t num_nodes, int32_t dim, int32_t dtype, const int32_t* ids,
+                    int64_t n, const int64_t* count_dev, const float* rows, float scale,
+                    void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,6 +27,7 @@ EXPORTS = (
     "gs_make_pairs_workspace_bytes", "gs_make_pairs",
     "gs_sample_negatives", "gs_sample_edges",
     "gs_sgns_step_workspace_bytes", "gs_sgns_step", "gs_sgns_momentum_step",
+    "gs_unique_ids_workspace_bytes", "gs_unique_ids", "gs_get_rows", "gs_put_rows",
 )
 
 
@@ -310,3 +311,52 @@ def gs_sgns_momentum_step(w_in, w_out, m_in, m_out, centers, contexts, negs, lr:
         _dev(ws), C.c_size_t(ws.numel()), _stream())
     _check(rc, "gs_sgns_momentum_step")
     return loss_out
+
+
+def gs_unique_ids_workspace_bytes(n: int) -> int:
+    return int(lib().gs_unique_ids_workspace_bytes(C.c_int64(n)))
+
+
+def gs_unique_ids(ids, num_nodes: int, want_inverse: bool = True, ws=None):
+    """Returns (unique_out [n], num_unique device int64[1], inverse [n] or None); only the
+    first num_unique entries of unique_out are meaningful."""
+    n = int(ids.numel())
+    dev = ids.device
+    unique_out = torch.empty(max(n, 1), dtype=torch.int32, device=dev)
+    count = torch.zeros(1, dtype=torch.int64, device=dev)
+    inverse = torch.empty(max(n, 1), dtype=torch.int32, device=dev) if want_inverse else None
+    if ws is None:
+        ws = _workspace(gs_unique_ids_workspace_bytes(n), dev)
+    rc = lib().gs_unique_ids(_dev(ids, torch.int32, "ids"), C.c_int64(n), C.c_int64(num_nodes),
+                             _dev(unique_out, torch.int32), _dev(count, torch.int64),
+                             _dev(inverse, torch.int32) if inverse is not None else None,
+                             _dev(ws), C.c_size_t(ws.numel()), _stream())
+    _check(rc, "gs_unique_ids")
+    return unique_out[:n], count, (inverse[:n] if inverse is not None else None)
+
+
+def _table_dtype(table):
+    return GS_BF16 if table.dtype == torch.bfloat16 else GS_F32
+
+
+def gs_get_rows(table, ids, count=None, out=None):
+    """out[i] = table[ids[i]] as float32; `count` (device int64[1]) limits the rows processed."""
+    n, dim = int(ids.numel()), int(table.shape[1])
+    if out is None:
+        out = torch.empty((n, dim), dtype=torch.float32, device=table.device)
+    rc = lib().gs_get_rows(_dev(table), C.c_int64(table.shape[0]), C.c_int32(dim),
+                           C.c_int32(_table_dtype(table)), _dev(ids, torch.int32, "ids"), C.c_int64(n),
+                           _dev(count, torch.int64) if count is not None else None,
+                           _dev(out, torch.float32, "out"), _stream())
+    _check(rc, "gs_get_rows")
+    return out
+
+
+def gs_put_rows(table, ids, rows, scale: float, count=None):
+    """table[ids[i]] += scale * rows[i] in place; the ids must be distinct."""
+    n, dim = int(ids.numel()), int(table.shape[1])
+    rc = lib().gs_put_rows(_dev(table), C.c_int64(table.shape[0]), C.c_int32(dim),
+                           C.c_int32(_table_dtype(table)), _dev(ids, torch.int32, "ids"), C.c_int64(n),
+                           _dev(count, torch.int64) if count is not None else None,
+                           _dev(rows, torch.float32, "rows"), C.c_float(scale), _stream())
+    _check(rc, "gs_put_rows")

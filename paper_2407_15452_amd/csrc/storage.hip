@@ -1,0 +1,251 @@
+// Storage operations on a batch of vertex ids (GraphScale Sec. 3.1 / 3.2): merge
+// equal ids into one request (gs_unique_ids), fetch one n x d block of rows
+// (gs_get_rows), add one block of gradient rows to the table (gs_put_rows).
+#include "common.h"
+
+namespace gs {
+
+namespace {
+
+constexpr int kRowLanes = 16;                       // lanes per row, 16 bytes each per access
+constexpr int kRowThreads = 256;
+constexpr int kRowsPerBlock = kRowThreads / kRowLanes;
+
+// id -> sort key; ids that are not rows get the key num_nodes and sort last
+__global__ void unique_keys_kernel(const int32_t* __restrict__ ids, int64_t n, int64_t num_nodes,
+                                   uint64_t* __restrict__ keys, uint32_t* __restrict__ index) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int32_t v = ids[i];
+  keys[i] = (v >= 0 && (int64_t)v < num_nodes) ? (uint64_t)v : (uint64_t)num_nodes;
+  index[i] = (uint32_t)i;
+}
+
+// head[j] = 1 where a new valid id starts in the sorted keys
+__global__ void unique_heads_kernel(const uint64_t* __restrict__ keys, int64_t n, int64_t num_nodes,
+                                    int64_t* __restrict__ head) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  const uint64_t k = keys[j];
+  head[j] = (k < (uint64_t)num_nodes && (j == 0 || keys[j - 1] != k)) ? 1 : 0;
+}
+
+// before[j] = number of heads before j (exclusive scan of head)
+__global__ void unique_emit_kernel(const uint64_t* __restrict__ keys, const uint32_t* __restrict__ index,
+                                   const int64_t* __restrict__ before, int64_t n, int64_t num_nodes,
+                                   int32_t* __restrict__ unique_out, int32_t* __restrict__ inverse_out) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  const uint64_t k = keys[j];
+  const bool valid = k < (uint64_t)num_nodes;
+  const bool is_head = valid && (j == 0 || keys[j - 1] != k);
+  const int64_t b = before[j];
+  if (is_head) unique_out[b] = (int32_t)k;
+  if (inverse_out) inverse_out[index[j]] = valid ? (int32_t)(is_head ? b : b - 1) : -1;
+}
+
+__device__ __forceinline__ int64_t live_count(int64_t n, const int64_t* count_dev) {
+  if (count_dev == nullptr) return n;
+  const int64_t c = *count_dev;
+  return c < 0 ? 0 : (c < n ? c : n);
+}
+
+__device__ __forceinline__ float widen_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float widen_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ uint32_t round_bf16(float f) {   // nearest even, finite inputs
+  const uint32_t b = __float_as_uint(f);
+  return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
+}
+// round(old + scale * r): exact product and one rounding of the sum in fp64,
+// then to fp32 (and from there to bf16 for bf16 tables)
+__device__ __forceinline__ float sum_once(float old, float scale, float r) {
+  return (float)((double)old + (double)scale * (double)r);
+}
+
+__global__ __launch_bounds__(kRowThreads) void get_rows_f32_kernel(
+    const float* __restrict__ table, int64_t num_nodes, int32_t dim, const int32_t* __restrict__ ids,
+    int64_t n, const int64_t* __restrict__ count_dev, float* __restrict__ out) {
+  const int l16 = threadIdx.x & (kRowLanes - 1);
+  const int64_t i = (int64_t)blockIdx.x * kRowsPerBlock + threadIdx.x / kRowLanes;
+  if (i >= live_count(n, count_dev)) return;
+  const int32_t id = ids[i];
+  const bool ok = id >= 0 && (int64_t)id < num_nodes;
+  const float4* src = reinterpret_cast<const float4*>(table + (int64_t)(ok ? id : 0) * dim);
+  float4* dst = reinterpret_cast<float4*>(out + i * (int64_t)dim);
+  for (int q = l16; q < (dim >> 2); q += kRowLanes)
+    dst[q] = ok ? src[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+__global__ __launch_bounds__(kRowThreads) void get_rows_bf16_kernel(
+    const uint16_t* __restrict__ table, int64_t num_nodes, int32_t dim, const int32_t* __restrict__ ids,
+    int64_t n, const int64_t* __restrict__ count_dev, float* __restrict__ out) {
+  const int l16 = threadIdx.x & (kRowLanes - 1);
+  const int64_t i = (int64_t)blockIdx.x * kRowsPerBlock + threadIdx.x / kRowLanes;
+  if (i >= live_count(n, count_dev)) return;
+  const int32_t id = ids[i];
+  const bool ok = id >= 0 && (int64_t)id < num_nodes;
+  const uint4* src = reinterpret_cast<const uint4*>(table + (int64_t)(ok ? id : 0) * dim);
+  float4* dst = reinterpret_cast<float4*>(out + i * (int64_t)dim);
+  for (int c = l16; c < (dim >> 3); c += kRowLanes) {
+    const uint4 x = ok ? src[c] : make_uint4(0u, 0u, 0u, 0u);
+    dst[2 * c] = make_float4(widen_lo(x.x), widen_hi(x.x), widen_lo(x.y), widen_hi(x.y));
+    dst[2 * c + 1] = make_float4(widen_lo(x.z), widen_hi(x.z), widen_lo(x.w), widen_hi(x.w));
+  }
+}
+
+__global__ __launch_bounds__(kRowThreads) void put_rows_f32_kernel(
+    float* __restrict__ table, int64_t num_nodes, int32_t dim, const int32_t* __restrict__ ids, int64_t n,
+    const int64_t* __restrict__ count_dev, const float* __restrict__ rows, float scale) {
+  const int l16 = threadIdx.x & (kRowLanes - 1);
+  const int64_t i = (int64_t)blockIdx.x * kRowsPerBlock + threadIdx.x / kRowLanes;
+  if (i >= live_count(n, count_dev)) return;
+  const int32_t id = ids[i];
+  if (id < 0 || (int64_t)id >= num_nodes) return;
+  float4* dst = reinterpret_cast<float4*>(table + (int64_t)id * dim);
+  const float4* src = reinterpret_cast<const float4*>(rows + i * (int64_t)dim);
+  for (int q = l16; q < (dim >> 2); q += kRowLanes) {
+    const float4 o = dst[q], r = src[q];
+    dst[q] = make_float4(sum_once(o.x, scale, r.x), sum_once(o.y, scale, r.y),
+                         sum_once(o.z, scale, r.z), sum_once(o.w, scale, r.w));
+  }
+}
+
+__global__ __launch_bounds__(kRowThreads) void put_rows_bf16_kernel(
+    uint16_t* __restrict__ table, int64_t num_nodes, int32_t dim, const int32_t* __restrict__ ids,
+    int64_t n, const int64_t* __restrict__ count_dev, const float* __restrict__ rows, float scale) {
+  const int l16 = threadIdx.x & (kRowLanes - 1);
+  const int64_t i = (int64_t)blockIdx.x * kRowsPerBlock + threadIdx.x / kRowLanes;
+  if (i >= live_count(n, count_dev)) return;
+  const int32_t id = ids[i];
+  if (id < 0 || (int64_t)id >= num_nodes) return;
+  uint4* dst = reinterpret_cast<uint4*>(table + (int64_t)id * dim);
+  const float4* src = reinterpret_cast<const float4*>(rows + i * (int64_t)dim);
+  for (int c = l16; c < (dim >> 3); c += kRowLanes) {
+    const uint4 o = dst[c];
+    const float4 a = src[2 * c], b = src[2 * c + 1];
+    uint4 x;
+    x.x = round_bf16(sum_once(widen_lo(o.x), scale, a.x)) | (round_bf16(sum_once(widen_hi(o.x), scale, a.y)) << 16);
+    x.y = round_bf16(sum_once(widen_lo(o.y), scale, a.z)) | (round_bf16(sum_once(widen_hi(o.y), scale, a.w)) << 16);
+    x.z = round_bf16(sum_once(widen_lo(o.z), scale, b.x)) | (round_bf16(sum_once(widen_hi(o.z), scale, b.y)) << 16);
+    x.w = round_bf16(sum_once(widen_lo(o.w), scale, b.z)) | (round_bf16(sum_once(widen_hi(o.w), scale, b.w)) << 16);
+    dst[c] = x;
+  }
+}
+
+struct UniquePlan {
+  uint64_t *keys, *keys_alt;
+  uint32_t *index, *index_alt;
+  int64_t *head, *scan_scratch;
+  void* sort_scratch;
+  size_t bytes;
+};
+
+UniquePlan plan_unique(void* ws, int64_t n) {
+  Carver cv(ws);
+  UniquePlan p;
+  const size_t m = (size_t)(n > 0 ? n : 1);
+  p.keys = cv.take<uint64_t>(m);
+  p.keys_alt = cv.take<uint64_t>(m);
+  p.index = cv.take<uint32_t>(m);
+  p.index_alt = cv.take<uint32_t>(m);
+  p.head = cv.take<int64_t>(m);
+  p.scan_scratch = cv.take<int64_t>(scan_scratch_elems((int64_t)m));
+  p.sort_scratch = cv.take<char>(radix_sort_scratch_bytes((int64_t)m));
+  p.bytes = cv.used;
+  return p;
+}
+
+int bits_for(uint64_t max_value) {
+  int b = 1;
+  while (b < 64 && (max_value >> b) != 0) ++b;
+  return b;
+}
+
+int32_t check_rows_args(const void* table, int64_t num_nodes, int32_t dim, int32_t dtype,
+                        const int32_t* ids, int64_t n, const void* block) {
+  if (!table || num_nodes < 1 || num_nodes > (int64_t)INT32_MAX || n < 0) return GS_EINVAL;
+  if (dtype != GS_F32 && dtype != GS_BF16) return GS_EINVAL;
+  if (dim < 1 || dim % (dtype == GS_BF16 ? 8 : 4) != 0) return GS_EINVAL;
+  if (n > 0 && (!ids || !block)) return GS_EINVAL;
+  if (!aligned(table, 16) || (n > 0 && !aligned(block, 16))) return GS_EINVAL;
+  if (ceil_div(n, kRowsPerBlock) > (int64_t)INT32_MAX) return GS_EOVERFLOW;
+  return GS_OK;
+}
+
+}  // namespace
+
+}  // namespace gs
+
+using namespace gs;
+
+extern "C" size_t gs_unique_ids_workspace_bytes(int64_t n) {
+  if (n < 0) return 0;
+  return plan_unique(nullptr, n).bytes;
+}
+
+extern "C" int32_t gs_unique_ids(const int32_t* ids, int64_t n, int64_t num_nodes, int32_t* unique_out,
+                                 int64_t* num_unique_out, int32_t* inverse_out, void* ws,
+                                 size_t ws_bytes, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  if (n < 0 || n >= ((int64_t)1 << 31) || num_nodes < 1 || num_nodes > (int64_t)INT32_MAX ||
+      !num_unique_out)
+    return GS_EINVAL;
+  if (n > 0 && (!ids || !unique_out)) return GS_EINVAL;
+  if (!ws || !aligned(ws, 256)) return GS_EINVAL;
+  UniquePlan p = plan_unique(ws, n);
+  if (ws_bytes < p.bytes) return GS_EWORKSPACE;
+  const unsigned blocks = (unsigned)ceil_div(n, 256);
+  if (n > 0) {
+    unique_keys_kernel<<<blocks, 256, 0, stream>>>(ids, n, num_nodes, p.keys, p.index);
+    GS_LAUNCH_CHECK();
+    int32_t rc = radix_sort_u64_u32(p.keys, p.index, p.keys_alt, p.index_alt, n, 0,
+                                    bits_for((uint64_t)num_nodes), 0, 0, p.sort_scratch, stream);
+    if (rc != GS_OK) return rc;
+    unique_heads_kernel<<<blocks, 256, 0, stream>>>(p.keys, n, num_nodes, p.head);
+    GS_LAUNCH_CHECK();
+  }
+  int32_t rc = exclusive_scan_i64(p.head, n, p.scan_scratch, num_unique_out, stream);
+  if (rc != GS_OK) return rc;
+  if (n > 0) {
+    unique_emit_kernel<<<blocks, 256, 0, stream>>>(p.keys, p.index, p.head, n, num_nodes, unique_out,
+                                                   inverse_out);
+    GS_LAUNCH_CHECK();
+  }
+  return GS_OK;
+}
+
+extern "C" int32_t gs_get_rows(const void* table, int64_t num_nodes, int32_t dim, int32_t dtype,
+                               const int32_t* ids, int64_t n, const int64_t* count_dev, float* out,
+                               void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  const int32_t rc = check_rows_args(table, num_nodes, dim, dtype, ids, n, out);
+  if (rc != GS_OK) return rc;
+  if (n == 0) return GS_OK;
+  const unsigned blocks = (unsigned)ceil_div(n, kRowsPerBlock);
+  if (dtype == GS_F32)
+    get_rows_f32_kernel<<<blocks, kRowThreads, 0, stream>>>(static_cast<const float*>(table), num_nodes,
+                                                            dim, ids, n, count_dev, out);
+  else
+    get_rows_bf16_kernel<<<blocks, kRowThreads, 0, stream>>>(static_cast<const uint16_t*>(table),
+                                                             num_nodes, dim, ids, n, count_dev, out);
+  GS_LAUNCH_CHECK();
+  return GS_OK;
+}
+
+extern "C" int32_t gs_put_rows(void* table, int64_t num_nodes, int32_t dim, int32_t dtype,
+                               const int32_t* ids, int64_t n, const int64_t* count_dev,
+                               const float* rows, float scale, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  const int32_t rc = check_rows_args(table, num_nodes, dim, dtype, ids, n, rows);
+  if (rc != GS_OK) return rc;
+  if (n == 0) return GS_OK;
+  const unsigned blocks = (unsigned)ceil_div(n, kRowsPerBlock);
+  if (dtype == GS_F32)
+    put_rows_f32_kernel<<<blocks, kRowThreads, 0, stream>>>(static_cast<float*>(table), num_nodes, dim,
+                                                            ids, n, count_dev, rows, scale);
+  else
+    put_rows_bf16_kernel<<<blocks, kRowThreads, 0, stream>>>(static_cast<uint16_t*>(table), num_nodes,
+                                                             dim, ids, n, count_dev, rows, scale);
+  GS_LAUNCH_CHECK();
+  return GS_OK;
+}
