@@ -281,6 +281,37 @@ def main():
                 "what": "gs_sample_edges + gs_sample_negatives + gs_sgns_step per batch of B edges"}
         del lc, lo_
 
+    # ------------------------------------------------------------------ get / put of a batch (extra)
+    # the ids of the last batch: merge, fetch the block of distinct rows, add a block back
+    lo = (K - 1) * B
+    batch_ids = torch.cat([centers[lo:lo + B], contexts[lo:lo + B], negs.reshape(-1)])
+    uniq_ws = torch.empty(gs.gs_unique_ids_workspace_bytes(batch_ids.numel()), dtype=torch.uint8,
+                          device=dev)
+    uniq, ucount, _ = gs.gs_unique_ids(batch_ids, wl.num_nodes, ws=uniq_ws)
+    n_uniq = int(ucount.item())
+    block = torch.empty((n_uniq, wl.dim), dtype=torch.float32, device=dev)
+
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    unique_ms = timed(lambda: gs.gs_unique_ids(batch_ids, wl.num_nodes, ws=uniq_ws))
+    get_ms = timed(lambda: gs.gs_get_rows(w_out, uniq[:n_uniq], out=block))
+    put_ms = timed(lambda: gs.gs_put_rows(w_out, uniq[:n_uniq], block, 0.0))
+    rb_blk = wl.dim * 4
+    row_bytes = wl.dim * elem_bytes
+    storage = {"batch_ids": int(batch_ids.numel()), "distinct": n_uniq, "unique_ms": unique_ms,
+               "get_ms": get_ms, "get_GBps": n_uniq * (row_bytes + rb_blk) / get_ms / 1e6,
+               "put_ms": put_ms, "put_GBps": n_uniq * (2 * row_bytes + rb_blk) / put_ms / 1e6}
+    del block, uniq_ws, batch_ids
+
     walk_kind = ("node2vec p=%g q=%g" % (wl.p, wl.q)) if wl.node2vec else "first-order"
     walk_kind += ", alias-weighted" if wl.weighted else ", uniform"
     result = {
@@ -302,6 +333,7 @@ def main():
         "mean_loss_per_pair": mean_loss,
         "momentum_step_ms": momentum_ms,
         "line": line,
+        "storage_ops": storage,
         "roofline": {"bound": "hbm", "kernel": "gs_sgns_step (all kernels of one call)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "bytes_per_pair": bpp,
