@@ -48,7 +48,7 @@ def _load():
         for name in ("oracle_csr_build", "oracle_alias_build", "oracle_random_walk",
                      "oracle_node2vec_walk", "oracle_make_pairs", "oracle_sample_negatives",
                      "oracle_sgns_step", "oracle_sgns_momentum_step", "oracle_sample_edges", "oracle_unique_ids", "oracle_get_rows",
-                     "oracle_put_rows"):
+                     "oracle_put_rows", "oracle_sgns_adam_step"):
             getattr(_lib, name).restype = C.c_int32
         _lib.oracle_philox4x32_10.restype = None
     return _lib
@@ -273,3 +273,22 @@ def put_rows(table, ids, rows, scale, dtype=F32):
                                  C.c_int32(dtype), _ptr(ids), C.c_int64(n), _ptr(rows),
                                  C.c_float(scale))
     _check(rc, "oracle_put_rows")
+
+
+def sgns_adam_step(w_in, w_out, m_in, m_out, v_in, v_out, centers, contexts, negs, lr, beta1, beta2,
+                   eps, t):
+    """Adam iteration number t (>= 1) on float32 tables, in place; returns the summed loss."""
+    for a in (w_in, w_out, m_in, m_out, v_in, v_out):
+        assert a.dtype == np.float32 and a.flags.c_contiguous and a.shape == w_in.shape
+    centers, contexts = _i32(centers), _i32(contexts)
+    negs = _i32(negs)
+    num_pairs = int(centers.shape[0])
+    k = int(negs.shape[1]) if negs.ndim == 2 else 0
+    loss = C.c_double(0.0)
+    rc = _load().oracle_sgns_adam_step(
+        _ptr(w_in), _ptr(w_out), _ptr(m_in), _ptr(m_out), _ptr(v_in), _ptr(v_out),
+        C.c_int64(w_in.shape[0]), C.c_int32(w_in.shape[1]), _ptr(centers), _ptr(contexts), _ptr(negs),
+        C.c_int64(num_pairs), C.c_int32(k), C.c_float(lr), C.c_float(beta1), C.c_float(beta2),
+        C.c_float(eps), C.c_int64(t), C.byref(loss))
+    _check(rc, "oracle_sgns_adam_step")
+    return loss.value

@@ -579,6 +579,57 @@ int32_t oracle_sgns_momentum_step(void* w_in, void* w_out, void* m_in, void* m_o
 
 
 // ---------------------------------------------------------------------------
+// The same iteration with Adam (§3.2 names Adam next to SGD with momentum as an
+// optimizer kept inside the storage; the update rule is Kingma & Ba's), run the
+// same way as the momentum step: dense operations over every row around a sparse
+// put of the batch's gradient rows g (zero for rows outside the batch):
+//   mult   m <- beta1 * m,  v <- beta2 * v                               (every row)
+//   put    m[r] <- m[r] + (1 - beta1) * g[r],  v[r] <- v[r] + (1 - beta2) * g[r]^2
+//   apply  w <- w - (lr / (1 - beta1^t)) * m / (sqrt(v) / sqrt(1 - beta2^t) + eps)
+// t >= 1 is the number of this iteration.  Each operation reads stored values
+// and rounds once on writing.  fp32 tables only.
+// ---------------------------------------------------------------------------
+int32_t oracle_sgns_adam_step(float* w_in, float* w_out, float* m_in, float* m_out, float* v_in,
+                              float* v_out, int64_t num_nodes, int32_t dim, const int32_t* centers,
+                              const int32_t* contexts, const int32_t* negs, int64_t num_pairs,
+                              int32_t k, float lr, float beta1, float beta2, float eps, int64_t t,
+                              double* loss_sum_out) {
+  if (!w_in || !w_out || !m_in || !m_out || !v_in || !v_out || t < 1) return ORACLE_EINVAL;
+  if (num_nodes < 1 || dim < 1 || num_pairs < 0 || k < 0 || !loss_sum_out) return ORACLE_EINVAL;
+  if (num_pairs > 0 && (!centers || !contexts || (k > 0 && !negs))) return ORACLE_EINVAL;
+  RowSums d_in, d_out;
+  int32_t rc = sgns_gradients(w_in, w_out, num_nodes, dim, ORACLE_F32, centers, contexts, negs,
+                              num_pairs, k, d_in, d_out, loss_sum_out);
+  if (rc != ORACLE_OK) return rc;
+  const double b1 = (double)beta1, b2 = (double)beta2;
+  const double step = (double)lr / (1.0 - std::pow(b1, (double)t));
+  const double root_c2 = std::sqrt(1.0 - std::pow(b2, (double)t));
+  float* model[2] = {w_in, w_out};
+  float* first[2] = {m_in, m_out};
+  float* second[2] = {v_in, v_out};
+  RowSums* grad[2] = {&d_in, &d_out};
+  for (int tb = 0; tb < 2; ++tb) {
+    const int64_t total = num_nodes * (int64_t)dim;
+    for (int64_t i = 0; i < total; ++i) {
+      first[tb][i] = (float)(b1 * (double)first[tb][i]);
+      second[tb][i] = (float)(b2 * (double)second[tb][i]);
+    }
+    for (auto& kv : *grad[tb])
+      for (int32_t e = 0; e < dim; ++e) {
+        const int64_t i = kv.first * (int64_t)dim + e;
+        const double g = kv.second[(size_t)e];
+        first[tb][i] = (float)((double)first[tb][i] + (1.0 - b1) * g);
+        second[tb][i] = (float)((double)second[tb][i] + (1.0 - b2) * g * g);
+      }
+    for (int64_t i = 0; i < total; ++i) {
+      const double m = (double)first[tb][i], v = (double)second[tb][i];
+      model[tb][i] = (float)((double)model[tb][i] - step * m / (std::sqrt(v) / root_c2 + (double)eps));
+    }
+  }
+  return ORACLE_OK;
+}
+
+// ---------------------------------------------------------------------------
 // The storage operations of §3.1 / §3.2 on a batch of vertex ids: a trainer
 // merges equal ids of its batch into one request, fetches one n x d block of
 // rows (get), and sends back one block of gradient rows that the storage adds

@@ -238,3 +238,65 @@ def test_momentum_step_moves_every_row_with_momentum(oracle):
                               0.5, 0.5)
     assert m_in[3, 0] == 0.25 and m_out[3, 0] == -0.125
     assert w_in[3, 0] == 1.0 - 0.5 * 0.25 and w_out[3, 0] == 1.0 + 0.5 * 0.125
+
+
+def test_adam_step_matches_torch_adam(oracle):
+    """mult / put / apply over the storage is torch.optim.Adam on the dense tables (gradient
+    zero outside the batch).  Four iterations on different batches, state compared too."""
+    rng = np.random.default_rng(17)
+    n, d, b, k = 30, 8, 40, 3
+    lr, b1, b2, eps = 0.01, 0.9, 0.999, 1e-8
+    w_in = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    w_out = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    m_in, m_out, v_in, v_out = (np.zeros((n, d), dtype=np.float32) for _ in range(4))
+    ti = torch.tensor(w_in, dtype=torch.float64, requires_grad=True)
+    to = torch.tensor(w_out, dtype=torch.float64, requires_grad=True)
+    f = lambda x: float(np.float32(x))
+    opt = torch.optim.Adam([ti, to], lr=f(lr), betas=(f(b1), f(b2)), eps=f(eps))
+    for it in range(1, 5):
+        c, o, neg = _batch(rng, 20, b, k)                # rows 20..29 are never named
+        opt.zero_grad()
+        dense = _dense_loss(ti, to, c, o, neg)
+        dense.backward()
+        opt.step()
+        loss = oracle.sgns_adam_step(w_in, w_out, m_in, m_out, v_in, v_out, c, o, neg, lr, b1, b2,
+                                     eps, it)
+        assert loss == pytest.approx(dense.item(), rel=1e-6)
+        np.testing.assert_allclose(w_in, ti.detach().numpy(), atol=2e-6)
+        np.testing.assert_allclose(w_out, to.detach().numpy(), atol=2e-6)
+        np.testing.assert_allclose(m_in, opt.state[ti]["exp_avg"].numpy(), rtol=1e-5, atol=1e-7)
+        np.testing.assert_allclose(v_out, opt.state[to]["exp_avg_sq"].numpy(), rtol=1e-5, atol=1e-9)
+    assert (m_in[20:] == 0).all() and (v_in[20:] == 0).all() and np.abs(m_in[:20]).max() > 0
+    np.testing.assert_array_equal(w_in[20:], ti.detach().numpy()[20:].astype(np.float32))
+
+
+def test_adam_first_step_has_magnitude_lr(oracle):
+    # t = 1: m / (1 - b1) = g, sqrt(v / (1 - b2)) = |g|, so every touched element moves by lr * sign(g)
+    rng = np.random.default_rng(18)
+    n, d, lr = 12, 4, 0.05
+    w_in = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    w_out = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    c, o, neg = _batch(rng, n, 30, 2)
+    a_in, a_out = w_in.copy(), w_out.copy()
+    oracle.sgns_step(a_in, a_out, c, o, neg, 1.0)        # a - w = -gradient
+    z = [np.zeros((n, d), dtype=np.float32) for _ in range(4)]
+    b_in, b_out = w_in.copy(), w_out.copy()
+    oracle.sgns_adam_step(b_in, b_out, *z, c, o, neg, lr, 0.9, 0.999, 1e-12, 1)
+    for before, sgd, adam in ((w_in, a_in, b_in), (w_out, a_out, b_out)):
+        g = before.astype(np.float64) - sgd
+        big = np.abs(g) > 1e-3
+        np.testing.assert_allclose((adam - before)[big], -lr * np.sign(g[big]), rtol=1e-4)
+        assert ((adam - before)[g == 0] == 0).all()
+
+
+def test_adam_decays_state_of_rows_outside_the_batch(oracle):
+    # the dense passes: an unnamed row keeps moving along its decayed first moment
+    w_in = np.ones((4, 2), dtype=np.float32)
+    w_out = np.ones((4, 2), dtype=np.float32)
+    m_in = np.full((4, 2), 0.5, dtype=np.float32); m_out = m_in.copy()
+    v_in = np.full((4, 2), 0.25, dtype=np.float32); v_out = v_in.copy()
+    oracle.sgns_adam_step(w_in, w_out, m_in, m_out, v_in, v_out, [0], [1],
+                          np.array([[1]], dtype=np.int32), 0.1, 0.5, 0.5, 0.0, 1)
+    assert m_in[3, 0] == 0.25 and v_in[3, 0] == 0.125
+    # step = lr / (1 - 0.5) = 0.2; denominator sqrt(0.125) / sqrt(0.5) = 0.5
+    assert w_in[3, 0] == pytest.approx(1.0 - 0.2 * 0.25 / 0.5, abs=1e-7)
