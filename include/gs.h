@@ -251,6 +251,26 @@ int32_t gs_sgns_momentum_step(void* w_in, void* w_out, void* m_in, void* m_out, 
                               size_t ws_bytes, void* stream);
 
 /* --------------------------------------------------------------------------
+ * gs_sgns_adam_step -- the iteration with Adam kept inside the storage (Sec. 3.2
+ * names Adam next to SGD with momentum; the rule is Kingma & Ba's), run like
+ * the momentum step as dense operations around a sparse put of the batch's
+ * gradient rows g (gradient of the summed loss at the pre-iteration model):
+ *   mult   m <- beta1 * m, v <- beta2 * v                         (every row)
+ *   put    m[r] += (1 - beta1) * g[r], v[r] += (1 - beta2) * g[r]^2  (batch rows)
+ *   apply  w <- w - (lr / (1 - beta1^t)) * m / (sqrt(v) / sqrt(1 - beta2^t) + eps)
+ * for both tables; t >= 1 is the number of this iteration.  Six distinct fp32
+ * tables [num_nodes][dim], 16-byte aligned; other arguments, workspace and
+ * limits as for gs_sgns_step with dtype GS_F32.
+ *   Errors: GS_EINVAL also for t < 1, beta outside [0, 1), eps < 0, or two
+ *   tables at the same address.
+ * ------------------------------------------------------------------------ */
+int32_t gs_sgns_adam_step(float* w_in, float* w_out, float* m_in, float* m_out, float* v_in,
+                          float* v_out, int64_t num_nodes, int32_t dim, const int32_t* centers,
+                          const int32_t* contexts, const int32_t* negs, int64_t num_pairs, int32_t k,
+                          float lr, float beta1, float beta2, float eps, int64_t t,
+                          double* loss_sum_out, void* ws, size_t ws_bytes, void* stream);
+
+/* --------------------------------------------------------------------------
  * Storage operations on a batch of vertex ids (Sec. 3.1: a trainer merges equal
  * vertex ids before it makes a single request and gets one block of rows back;
  * Sec. 3.2: only the n << N rows of a mini-batch are fetched, and only an

@@ -26,7 +26,7 @@ EXPORTS = (
     "gs_random_walk", "gs_node2vec_walk",
     "gs_make_pairs_workspace_bytes", "gs_make_pairs",
     "gs_sample_negatives", "gs_sample_edges",
-    "gs_sgns_step_workspace_bytes", "gs_sgns_step", "gs_sgns_momentum_step",
+    "gs_sgns_step_workspace_bytes", "gs_sgns_step", "gs_sgns_momentum_step", "gs_sgns_adam_step",
     "gs_unique_ids_workspace_bytes", "gs_unique_ids", "gs_get_rows", "gs_put_rows",
 )
 
@@ -360,3 +360,28 @@ def gs_put_rows(table, ids, rows, scale: float, count=None):
                            _dev(count, torch.int64) if count is not None else None,
                            _dev(rows, torch.float32, "rows"), C.c_float(scale), _stream())
     _check(rc, "gs_put_rows")
+
+
+def gs_sgns_adam_step(w_in, w_out, m_in, m_out, v_in, v_out, centers, contexts, negs, lr: float,
+                      beta1: float, beta2: float, eps: float, t: int, loss_out=None, ws=None):
+    """Adam iteration number t on six float32 tables, in place; returns the device loss scalar."""
+    num_nodes, dim = int(w_in.shape[0]), int(w_in.shape[1])
+    num_pairs = int(centers.numel())
+    k = int(negs.shape[1]) if negs.dim() == 2 else 0
+    dev = w_in.device
+    for tb in (w_in, w_out, m_in, m_out, v_in, v_out):
+        if tb.dtype != torch.float32 or tuple(tb.shape) != (num_nodes, dim) or not tb.is_contiguous():
+            raise TypeError("Adam tables must be contiguous float32 [num_nodes, dim]")
+    if loss_out is None:
+        loss_out = torch.zeros(1, dtype=torch.float64, device=dev)
+    if ws is None:
+        ws = _workspace(gs_sgns_step_workspace_bytes(num_pairs, num_nodes, k, dim, GS_F32), dev)
+    rc = lib().gs_sgns_adam_step(
+        _dev(w_in), _dev(w_out), _dev(m_in), _dev(m_out), _dev(v_in), _dev(v_out),
+        C.c_int64(num_nodes), C.c_int32(dim), _dev(centers, torch.int32, "centers"),
+        _dev(contexts, torch.int32, "contexts"), _dev(negs, torch.int32, "negs"),
+        C.c_int64(num_pairs), C.c_int32(k), C.c_float(lr), C.c_float(beta1), C.c_float(beta2),
+        C.c_float(eps), C.c_int64(t), _dev(loss_out, torch.float64), _dev(ws),
+        C.c_size_t(ws.numel()), _stream())
+    _check(rc, "gs_sgns_adam_step")
+    return loss_out

@@ -29,6 +29,9 @@
 // A row is handled by 16 lanes holding 16-byte pieces (256 contiguous bytes per
 // load instruction); a wave works on four rows at once and a dot product is a
 // 16-lane DPP reduction.  No matrix cores: 0.3 flop per byte moved.
+#include <cmath>
+#include <type_traits>
+
 #include "common.h"
 
 namespace gs {
@@ -63,6 +66,9 @@ struct SgnsArgs {
   void* w_out;
   void* dst_in;             // tables that receive round(old + delta): the same two for plain
   void* dst_out;            // SGD, the momentum tables for the momentum step
+  float* sq_in;             // Adam only (else null): with delta D of a row, the destination row
+  float* sq_out;            // gets c1 * D and this second-moment row gets c2 * D * D (fp32 tables)
+  float c1, c2;
   const int32_t* centers;
   const int32_t* contexts;
   const int32_t* negs;
@@ -579,8 +585,9 @@ __global__ __launch_bounds__(256) void sgns_place_kernel(SgnsArgs a) {
 // handled slice by slice; their partial sums meet in the fp32 side buffer at
 // slot (position of the row's first term) >> kLongShift, which no two long rows
 // can share because each of them spans more than 2^kLongShift positions.
-template <typename T, int VPL, int UB>
+template <typename T, int VPL, int UB, bool kSq>
 __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
+  static_assert(!kSq || std::is_same<T, float>::value, "second-moment tables are fp32");
   const T* __restrict__ w_in = static_cast<const T*>(a.w_in);
   T* w_out = static_cast<T*>(a.dst_out);   // destination rows (old value and result)
   const int l16 = threadIdx.x & (kGroupLanes - 1);
@@ -621,6 +628,17 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
           unsafeAtomicAdd(dst + 4 * q + 3, acc[v].w);
         }
       }
+    } else if constexpr (kSq) {
+      float4 old2[VPL], d1[VPL], d2[VPL];
+      load_row<VPL>(a.sq_out, cur_row, a.dim, l16, old2);
+#pragma unroll
+      for (int v = 0; v < VPL; ++v) {
+        const float4 d = acc[v];
+        d1[v] = make_float4(a.c1 * d.x, a.c1 * d.y, a.c1 * d.z, a.c1 * d.w);
+        d2[v] = make_float4(a.c2 * d.x * d.x, a.c2 * d.y * d.y, a.c2 * d.z * d.z, a.c2 * d.w * d.w);
+      }
+      store_row_sum<VPL>(w_out, cur_row, a.dim, l16, old, d1);
+      store_row_sum<VPL>(a.sq_out, cur_row, a.dim, l16, old2, d2);
     } else {
       store_row_sum<VPL>(w_out, cur_row, a.dim, l16, old, acc);
     }
@@ -725,6 +743,15 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_long_rows_kernel(SgnsArgs a
   if ((first_pos >> kLongShift) != s) return;
   const float* src = a.long_acc + s * (int64_t)a.dim;
   T* dst = w_out + t.row * (int64_t)a.dim;
+  if (a.sq_out != nullptr) {
+    float* sq = a.sq_out + t.row * (int64_t)a.dim;
+    for (int e = l16; e < a.dim; e += kGroupLanes) {
+      const float d = src[e];
+      elem_store(dst, e, elem_load(dst, e) + a.c1 * d);
+      sq[e] += a.c2 * d * d;
+    }
+    return;
+  }
   for (int e = l16; e < a.dim; e += kGroupLanes) elem_store(dst, e, elem_load(dst, e) + src[e]);
 }
 
@@ -777,6 +804,15 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_apply_kernel(SgnsArgs a) {
     if (c < 0) continue;
     const float* src = a.stage_delta + (group * kGroupLanes + b) * (int64_t)a.dim;
     T* dst = w_in + c * (int64_t)a.dim;
+    if (a.sq_in != nullptr) {
+      float* sq = a.sq_in + c * (int64_t)a.dim;
+      for (int e = l16; e < a.dim; e += kGroupLanes) {
+        const float d = -a.lr * src[e];
+        elem_store(dst, e, elem_load(dst, e) + a.c1 * d);
+        sq[e] += a.c2 * d * d;
+      }
+      continue;
+    }
     for (int e = l16; e < a.dim; e += kGroupLanes)
       elem_store(dst, e, elem_load(dst, e) - a.lr * src[e]);
   }
@@ -857,8 +893,18 @@ static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
   sgns_place_kernel<<<(unsigned)ceil_div(a.num_terms, 256), 256, 0, stream>>>(a);
   GS_LAUNCH_CHECK();
   const int64_t update_groups = ceil_div(a.num_terms, kSlice);
-  sgns_update_kernel<T, VPL, UB><<<(unsigned)ceil_div(update_groups, kGroupsPerBlock), kSgnsThreads,
-                                  (size_t)a.update_lds_bytes, stream>>>(a);
+  const unsigned update_blocks = (unsigned)ceil_div(update_groups, kGroupsPerBlock);
+  if constexpr (std::is_same<T, float>::value) {
+    if (a.sq_out != nullptr)
+      sgns_update_kernel<T, VPL, UB, true><<<update_blocks, kSgnsThreads, (size_t)a.update_lds_bytes,
+                                            stream>>>(a);
+    else
+      sgns_update_kernel<T, VPL, UB, false><<<update_blocks, kSgnsThreads, (size_t)a.update_lds_bytes,
+                                             stream>>>(a);
+  } else {
+    sgns_update_kernel<T, VPL, UB, false><<<update_blocks, kSgnsThreads, (size_t)a.update_lds_bytes,
+                                           stream>>>(a);
+  }
   GS_LAUNCH_CHECK();
   sgns_long_rows_kernel<T><<<(unsigned)ceil_div(a.long_slots, kGroupsPerBlock), kSgnsThreads, 0,
                             stream>>>(a);
@@ -929,6 +975,37 @@ __global__ __launch_bounds__(256) void table_axpy_kernel(uint4* __restrict__ w,
   }
 }
 
+// Adam's dense passes over a whole fp32 table: decay of both moments, then the model update
+__global__ __launch_bounds__(256) void adam_decay_kernel(float4* __restrict__ m, float4* __restrict__ v,
+                                                         int64_t n4, float beta1, float beta2) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    float4 x = m[i], y = v[i];
+    x.x *= beta1; x.y *= beta1; x.z *= beta1; x.w *= beta1;
+    y.x *= beta2; y.y *= beta2; y.z *= beta2; y.w *= beta2;
+    m[i] = x;
+    v[i] = y;
+  }
+}
+__device__ __forceinline__ float adam_move(float m, float v, float step, float root_c2, float eps) {
+  return step * m / (sqrtf(v) / root_c2 + eps);
+}
+__global__ __launch_bounds__(256) void adam_apply_kernel(float4* __restrict__ w,
+                                                         const float4* __restrict__ m,
+                                                         const float4* __restrict__ v, int64_t n4,
+                                                         float step, float root_c2, float eps) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    float4 x = w[i];
+    const float4 a = m[i], b = v[i];
+    x.x -= adam_move(a.x, b.x, step, root_c2, eps);
+    x.y -= adam_move(a.y, b.y, step, root_c2, eps);
+    x.z -= adam_move(a.z, b.z, step, root_c2, eps);
+    x.w -= adam_move(a.w, b.w, step, root_c2, eps);
+    w[i] = x;
+  }
+}
+
 static int32_t check_sgns_args(const void* w_in, const void* w_out, int64_t num_nodes, int32_t dim,
                                int32_t dtype, const int32_t* centers, const int32_t* contexts,
                                const int32_t* negs, int64_t num_pairs, int32_t k,
@@ -950,8 +1027,14 @@ static int32_t check_sgns_args(const void* w_in, const void* w_out, int64_t num_
 static int32_t run_sgns(void* w_in, void* w_out, void* dst_in, void* dst_out, int64_t num_nodes,
                         int32_t dim, int32_t dtype, const int32_t* centers, const int32_t* contexts,
                         const int32_t* negs, int64_t num_pairs, int32_t k, float lr,
-                        double* loss_sum_out, const SgnsPlan& p, hipStream_t stream) {
+                        double* loss_sum_out, const SgnsPlan& p, hipStream_t stream,
+                        float* sq_in = nullptr, float* sq_out = nullptr, float c1 = 1.f,
+                        float c2 = 0.f) {
   SgnsArgs a;
+  a.sq_in = sq_in;
+  a.sq_out = sq_out;
+  a.c1 = c1;
+  a.c2 = c2;
   a.w_in = w_in;
   a.w_out = w_out;
   a.dst_in = dst_in;
@@ -1069,6 +1152,53 @@ extern "C" int32_t gs_sgns_momentum_step(void* w_in, void* w_out, void* m_in, vo
     table_axpy_kernel<<<blocks, 256, 0, stream>>>((uint4*)w_in, (const uint4*)m_in, pieces, lr);
     table_axpy_kernel<<<blocks, 256, 0, stream>>>((uint4*)w_out, (const uint4*)m_out, pieces, lr);
   }
+  GS_LAUNCH_CHECK();
+  return GS_OK;
+}
+
+extern "C" int32_t gs_sgns_adam_step(float* w_in, float* w_out, float* m_in, float* m_out, float* v_in,
+                                     float* v_out, int64_t num_nodes, int32_t dim,
+                                     const int32_t* centers, const int32_t* contexts,
+                                     const int32_t* negs, int64_t num_pairs, int32_t k, float lr,
+                                     float beta1, float beta2, float eps, int64_t t,
+                                     double* loss_sum_out, void* ws, size_t ws_bytes, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  const int32_t bad = check_sgns_args(w_in, w_out, num_nodes, dim, GS_F32, centers, contexts, negs,
+                                      num_pairs, k, loss_sum_out, ws);
+  if (bad != GS_OK) return bad;
+  float* tables[6] = {w_in, w_out, m_in, m_out, v_in, v_out};
+  for (int i = 0; i < 6; ++i) {
+    if (!tables[i] || !aligned(tables[i], 16)) return GS_EINVAL;
+    for (int j = 0; j < i; ++j)
+      if (tables[i] == tables[j]) return GS_EINVAL;
+  }
+  if (t < 1 || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f))
+    return GS_EINVAL;
+  SgnsPlan p = plan_sgns(ws, num_pairs, num_nodes, k, dim);
+  if (ws_bytes < p.bytes) return GS_EWORKSPACE;
+  const int64_t pieces = num_nodes * (int64_t)dim / 4;
+  const unsigned blocks = (unsigned)min((int64_t)(256 * 64), ceil_div(pieces, 256));
+  // mult: both moments decay, every row
+  adam_decay_kernel<<<blocks, 256, 0, stream>>>((float4*)m_in, (float4*)v_in, pieces, beta1, beta2);
+  adam_decay_kernel<<<blocks, 256, 0, stream>>>((float4*)m_out, (float4*)v_out, pieces, beta1, beta2);
+  GS_LAUNCH_CHECK();
+  // put: m[r] += (1 - beta1) g[r], v[r] += (1 - beta2) g[r]^2 for the rows of the batch
+  if (num_pairs == 0) {
+    zero_double_kernel<<<1, 1, 0, stream>>>(loss_sum_out);
+    GS_LAUNCH_CHECK();
+  } else {
+    const int32_t rc = run_sgns(w_in, w_out, m_in, m_out, num_nodes, dim, GS_F32, centers, contexts,
+                                negs, num_pairs, k, -1.0f, loss_sum_out, p, stream, v_in, v_out,
+                                1.0f - beta1, 1.0f - beta2);
+    if (rc != GS_OK) return rc;
+  }
+  // apply: w -= (lr / (1 - beta1^t)) * m / (sqrt(v) / sqrt(1 - beta2^t) + eps), every row
+  const float step = (float)((double)lr / (1.0 - pow((double)beta1, (double)t)));
+  const float root_c2 = (float)sqrt(1.0 - pow((double)beta2, (double)t));
+  adam_apply_kernel<<<blocks, 256, 0, stream>>>((float4*)w_in, (const float4*)m_in,
+                                                (const float4*)v_in, pieces, step, root_c2, eps);
+  adam_apply_kernel<<<blocks, 256, 0, stream>>>((float4*)w_out, (const float4*)m_out,
+                                                (const float4*)v_out, pieces, step, root_c2, eps);
   GS_LAUNCH_CHECK();
   return GS_OK;
 }

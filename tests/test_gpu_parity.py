@@ -634,3 +634,67 @@ def test_sgns_momentum_step_argument_errors(gs):
         gs.gs_sgns_momentum_step(w[0], w[1], w[0], w[3], i, i, n, 0.1, 0.9)
     loss = gs.gs_sgns_momentum_step(*w, i, i, n, 0.1, 0.9)
     assert float(loss.item()) == pytest.approx(4 * 3 * np.log(2.0))
+
+
+# ----------------------------------------------------------------------------- Adam
+@pytest.mark.parametrize("dim,k,b,eps", [(128, 5, 50_001, 1e-8), (64, 3, 7_777, 1e-8),
+                                         (256, 10, 9_999, 1e-4), (320, 2, 4_096, 1e-8)])
+def test_sgns_adam_step(gs, oracle, dim, k, b, eps):
+    """Three consecutive Adam iterations (dense decay, sparse put, dense apply) against the
+    oracle.  Both moments are compared element by element.  The model is compared (a) with
+    the apply formula evaluated in fp64 from the moments the GPU itself holds, on every
+    element, and (b) with the oracle wherever the denominator sqrt(v)/sqrt(1-beta2^t)+eps is
+    at least 1e-3: below that the update lr*m/denominator magnifies the fp32 summation
+    noise of a gradient that cancels to almost zero (an element whose gradient is 1e-9 on
+    one side and -1e-9 on the other moves by +lr or -lr), which no summation order fixes."""
+    from paper_2407_15452_amd import inputs
+    n = 5000
+    f_in, f_out = inputs.random_tables(n, dim, seed=dim + k, scale=2.0 / dim ** 0.5)
+    zeros = [torch.zeros((n, dim), dtype=torch.float32) for _ in range(4)]
+    host = [t.numpy().copy() for t in (f_in, f_out, *zeros)]
+    dev = [t.to(DEV) for t in (f_in, f_out, *zeros)]
+    rng = np.random.default_rng(b)
+    lr, b1, b2 = 0.01, 0.9, 0.999
+    for it in range(1, 4):
+        c = np.repeat(rng.integers(0, n, b // 8 + 1), 8)[:b].astype(np.int32)
+        o = rng.integers(0, n, b).astype(np.int32)
+        neg = (n * rng.random((b, k)) ** 3).astype(np.int32)
+        old_model = [h.copy() for h in host[:2]]
+        want = oracle.sgns_adam_step(*host, c, o, neg, lr, b1, b2, eps, it)
+        loss = gs.gs_sgns_adam_step(*dev, _t(c), _t(o), _t(neg), lr, b1, b2, eps, it)
+        torch.cuda.synchronize()
+        assert abs(float(loss.item()) - want) <= LOSS_RTOL * abs(want)
+        got = [d.cpu().numpy() for d in dev]
+        for which in (2, 3, 4, 5):                       # m_in, m_out, v_in, v_out
+            assert (np.abs(got[which] - host[which]) <= 1e-6 + 1e-5 * np.abs(host[which])).all()
+        step = np.float64(np.float32(lr)) / (1.0 - np.float64(np.float32(b1)) ** it)
+        root = np.sqrt(1.0 - np.float64(np.float32(b2)) ** it)
+        for which in (0, 1):
+            m, v = got[which + 2].astype(np.float64), got[which + 4].astype(np.float64)
+            denom = np.sqrt(v) / root + np.float64(np.float32(eps))
+            expect = old_model[which].astype(np.float64) - step * m / np.where(denom > 0, denom, 1.0)
+            assert np.abs(got[which] - expect).max() <= 1e-6
+            safe = (np.sqrt(host[which + 4].astype(np.float64)) / root + eps) >= 1e-3
+            assert safe.mean() > 0.5 if which == 1 else True
+            assert np.abs(got[which] - host[which])[safe].max() <= EMB_ATOL
+            assert np.abs(got[which] - host[which]).max() <= 2.0 * step + EMB_ATOL
+            untouched = host[which + 4].max(axis=1) == 0   # rows no batch has named yet
+            np.testing.assert_array_equal(got[which][untouched], old_model[which][untouched])
+        for d_t, h_t in zip(dev, host):                      # next iteration from a common state
+            d_t.copy_(torch.from_numpy(h_t))
+
+
+def test_sgns_adam_step_argument_errors(gs):
+    w = [torch.zeros((10, 8), dtype=torch.float32, device=DEV) for _ in range(6)]
+    i = torch.zeros(4, dtype=torch.int32, device=DEV)
+    n = torch.zeros((4, 2), dtype=torch.int32, device=DEV)
+    with pytest.raises(gs.GsError):            # a moment table aliasing another table
+        gs.gs_sgns_adam_step(w[0], w[1], w[2], w[3], w[2], w[5], i, i, n, 0.1, 0.9, 0.999, 1e-8, 1)
+    with pytest.raises(gs.GsError):            # iteration numbers start at 1
+        gs.gs_sgns_adam_step(*w, i, i, n, 0.1, 0.9, 0.999, 1e-8, 0)
+    with pytest.raises(gs.GsError):
+        gs.gs_sgns_adam_step(*w, i, i, n, 0.1, 1.0, 0.999, 1e-8, 1)
+    with pytest.raises(TypeError):
+        gs.gs_sgns_adam_step(w[0].to(torch.bfloat16), *w[1:], i, i, n, 0.1, 0.9, 0.999, 1e-8, 1)
+    loss = gs.gs_sgns_adam_step(*w, i, i, n, 0.1, 0.9, 0.999, 1e-8, 1)
+    assert float(loss.item()) == pytest.approx(4 * 3 * np.log(2.0))
