@@ -252,6 +252,25 @@ def main():
         torch.cuda.synchronize()
         momentum_ms = e0.elapsed_time(e1) / 5
         del m_in, m_out
+    adam_ms = None
+    if wl.dtype == "f32" and 6 * wl.num_nodes * wl.dim * 4 <= 48e9:
+        # throw-away copies: Adam's unit-sized steps would disturb the tables the later extras read
+        a_tabs = [w_in.clone(), w_out.clone()] + [torch.zeros_like(w_in) for _ in range(4)]
+        lo = (K - 1) * B
+        adam = lambda t: gs.gs_sgns_adam_step(*a_tabs, centers[lo:lo + B], contexts[lo:lo + B], negs,  # noqa: E731
+                                              1e-3, 0.9, 0.999, 1e-8, t, loss_out=losses[:1],
+                                              ws=sgns_ws)
+        for t in (1, 2):
+            adam(t)
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for t in range(3, 8):
+            adam(t)
+        e1.record()
+        torch.cuda.synchronize()
+        adam_ms = e0.elapsed_time(e1) / 5
+        del a_tabs
 
     # ------------------------------------------------------------------ LINE batches (extra)
     # B sampled edges (uniform over the CSR entries) + negatives + the same step
@@ -332,6 +351,7 @@ def main():
                       "chunk_walks": int(starts_timed.numel())},
         "mean_loss_per_pair": mean_loss,
         "momentum_step_ms": momentum_ms,
+        "adam_step_ms": adam_ms,
         "line": line,
         "storage_ops": storage,
         "roofline": {"bound": "hbm", "kernel": "gs_sgns_step (all kernels of one call)",
