@@ -251,6 +251,24 @@ int32_t gs_sgns_momentum_step(void* w_in, void* w_out, void* m_in, void* m_out, 
                               size_t ws_bytes, void* stream);
 
 /* --------------------------------------------------------------------------
+ * gs_sgns_step_fused -- gs_sample_negatives and gs_sgns_step in one call: the
+ * negatives of pair i are drawn inside the step, from the same counters
+ * (pair_index_base + i, j, 0x80000000) and the same table `noise` (NULL or
+ * prob == NULL: uniform over the nodes), so the result is that of the two
+ * calls; the caller provides no negs array (the draws are kept in the
+ * workspace for the later kernels of the step).
+ *   Other arguments, limits and errors as for gs_sgns_step; the workspace is
+ *   gs_sgns_step_fused_workspace_bytes (the step's own plus 4*num_pairs*k).
+ * ------------------------------------------------------------------------ */
+size_t gs_sgns_step_fused_workspace_bytes(int64_t num_pairs, int64_t num_nodes, int32_t k,
+                                          int32_t dim, int32_t dtype);
+int32_t gs_sgns_step_fused(void* w_in, void* w_out, int64_t num_nodes, int32_t dim, int32_t dtype,
+                           const int32_t* centers, const int32_t* contexts, int64_t num_pairs,
+                           const gs_alias* noise, uint64_t pair_index_base, uint64_t neg_seed,
+                           int32_t k, float lr, double* loss_sum_out, void* ws, size_t ws_bytes,
+                           void* stream);
+
+/* --------------------------------------------------------------------------
  * gs_sgns_adam_step -- the iteration with Adam kept inside the storage (Sec. 3.2
  * names Adam next to SGD with momentum; the rule is Kingma & Ba's), run like
  * the momentum step as dense operations around a sparse put of the batch's

@@ -27,6 +27,7 @@ EXPORTS = (
     "gs_make_pairs_workspace_bytes", "gs_make_pairs",
     "gs_sample_negatives", "gs_sample_edges",
     "gs_sgns_step_workspace_bytes", "gs_sgns_step", "gs_sgns_momentum_step", "gs_sgns_adam_step",
+    "gs_sgns_step_fused_workspace_bytes", "gs_sgns_step_fused",
     "gs_unique_ids_workspace_bytes", "gs_unique_ids", "gs_get_rows", "gs_put_rows",
 )
 
@@ -384,4 +385,31 @@ def gs_sgns_adam_step(w_in, w_out, m_in, m_out, v_in, v_out, centers, contexts, 
         C.c_float(eps), C.c_int64(t), _dev(loss_out, torch.float64), _dev(ws),
         C.c_size_t(ws.numel()), _stream())
     _check(rc, "gs_sgns_adam_step")
+    return loss_out
+
+
+def gs_sgns_step_fused_workspace_bytes(num_pairs: int, num_nodes: int, k: int, dim: int,
+                                       dtype: int = GS_F32) -> int:
+    return int(lib().gs_sgns_step_fused_workspace_bytes(C.c_int64(num_pairs), C.c_int64(num_nodes),
+                                                        C.c_int32(k), C.c_int32(dim), C.c_int32(dtype)))
+
+
+def gs_sgns_step_fused(w_in, w_out, centers, contexts, noise, k: int, neg_seed: int, lr: float,
+                       pair_index_base: int = 0, loss_out=None, ws=None):
+    """gs_sample_negatives + gs_sgns_step in one call; returns the device loss scalar."""
+    dtype = GS_BF16 if w_in.dtype == torch.bfloat16 else GS_F32
+    num_nodes, dim = int(w_in.shape[0]), int(w_in.shape[1])
+    num_pairs = int(centers.numel())
+    dev = w_in.device
+    if loss_out is None:
+        loss_out = torch.zeros(1, dtype=torch.float64, device=dev)
+    if ws is None:
+        ws = _workspace(gs_sgns_step_fused_workspace_bytes(num_pairs, num_nodes, k, dim, dtype), dev)
+    rc = lib().gs_sgns_step_fused(
+        _dev(w_in), _dev(w_out), C.c_int64(num_nodes), C.c_int32(dim), C.c_int32(dtype),
+        _dev(centers, torch.int32, "centers"), _dev(contexts, torch.int32, "contexts"),
+        C.c_int64(num_pairs), _alias_ref(noise), C.c_uint64(pair_index_base), C.c_uint64(neg_seed),
+        C.c_int32(k), C.c_float(lr), _dev(loss_out, torch.float64), _dev(ws), C.c_size_t(ws.numel()),
+        _stream())
+    _check(rc, "gs_sgns_step_fused")
     return loss_out

@@ -89,6 +89,23 @@ __device__ __forceinline__ uint64_t slot_of(const Block4& b, uint64_t n) {
 
 __device__ __forceinline__ float unit_float(uint32_t x) { return (float)(x >> 8) * 0x1p-24f; }
 
+// One draw from a single alias table of n entries with random block b: words 0,1
+// choose the slot, word 2 decides between the slot and its alias.  All three
+// table pointers null: uniform.  `packed` (prob bits, alias) is read when present.
+__device__ __forceinline__ int64_t table_draw(const float* __restrict__ prob,
+                                              const int32_t* __restrict__ alias,
+                                              const uint2* __restrict__ packed, uint64_t n,
+                                              const Block4& b) {
+  int64_t s = (int64_t)slot_of(b, n);
+  if (packed != nullptr) {
+    const uint2 e = packed[s];                      // one 8-byte load
+    if (!(unit_float(b.x2) < __uint_as_float(e.x))) s = (int64_t)(int32_t)e.y;
+  } else if (prob != nullptr) {
+    if (!(unit_float(b.x2) < prob[s])) s = (int64_t)alias[s];
+  }
+  return s;
+}
+
 template <typename OffT>
 __device__ __forceinline__ int64_t load_off(const void* offsets, int64_t i) {
   return (int64_t) static_cast<const OffT*>(offsets)[i];

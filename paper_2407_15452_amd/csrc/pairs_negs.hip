@@ -89,14 +89,7 @@ __global__ void negatives_kernel(const float* __restrict__ prob, const int32_t* 
   const uint64_t i = (uint64_t)(e / k);
   const uint32_t j = (uint32_t)(e - (int64_t)i * k);
   const Block4 b = philox_at(seed, pair_base + i, j, 0x80000000u);
-  int64_t s = (int64_t)slot_of(b, num_nodes);
-  if (packed != nullptr) {
-    const uint2 e2 = packed[s];                     // (prob bits, alias) in one 8-byte load
-    if (!(unit_float(b.x2) < __uint_as_float(e2.x))) s = (int64_t)(int32_t)e2.y;
-  } else if (prob != nullptr) {
-    if (!(unit_float(b.x2) < prob[s])) s = (int64_t)alias[s];
-  }
-  negs[e] = (int32_t)s;
+  negs[e] = (int32_t)table_draw(prob, alias, packed, num_nodes, b);
 }
 
 // One lane per LINE sample: draw an entry, then find the row that holds it
@@ -112,13 +105,7 @@ __global__ void edges_kernel(const OffT* __restrict__ offsets, int64_t num_nodes
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= num_samples) return;
   const Block4 b = philox_at(seed, sample_base + (uint64_t)i, 0u, 0x40000000u);
-  int64_t e = (int64_t)slot_of(b, num_entries);
-  if (packed != nullptr) {
-    const uint2 e2 = packed[e];
-    if (!(unit_float(b.x2) < __uint_as_float(e2.x))) e = (int64_t)(int32_t)e2.y;
-  } else if (prob != nullptr) {
-    if (!(unit_float(b.x2) < prob[e])) e = (int64_t)alias[e];
-  }
+  const int64_t e = table_draw(prob, alias, packed, num_entries, b);
   const int32_t dst = nbrs[e];
   // first t in [1, num_nodes] with offsets[t] > e; offsets[num_nodes] = num_entries > e
   int64_t lo = 1, hi = num_nodes;

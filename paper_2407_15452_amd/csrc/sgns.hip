@@ -69,6 +69,16 @@ struct SgnsArgs {
   float* sq_in;             // Adam only (else null): with delta D of a row, the destination row
   float* sq_out;            // gets c1 * D and this second-moment row gets c2 * D * D (fp32 tables)
   float c1, c2;
+  // negatives drawn inside the step (draw_negs != 0): entry (i, j) is the draw of
+  // gs_sample_negatives for pair index neg_pair_base + i, written to negs_draw
+  // (which `negs` then points to) for the later kernels
+  int32_t draw_negs;
+  const float* noise_prob;
+  const int32_t* noise_alias;
+  const uint2* noise_packed;
+  uint64_t neg_seed;
+  uint64_t neg_pair_base;
+  int32_t* negs_draw;
   const int32_t* centers;
   const int32_t* contexts;
   const int32_t* negs;
@@ -370,7 +380,18 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
   if (l16 < count) cen_s[l16] = a.centers[first + l16];
   for (int t = l16; t < count * K1; t += kGroupLanes) {
     const int p = t / K1, j = t - p * K1;
-    rows_s[t] = (j == 0) ? a.contexts[first + p] : a.negs[(first + p) * (int64_t)K + (j - 1)];
+    int32_t row;
+    if (j == 0) {
+      row = a.contexts[first + p];
+    } else if (a.draw_negs) {
+      const Block4 b = philox_at(a.neg_seed, a.neg_pair_base + (uint64_t)(first + p), (uint32_t)(j - 1),
+                                 0x80000000u);
+      row = (int32_t)table_draw(a.noise_prob, a.noise_alias, a.noise_packed, (uint64_t)a.num_nodes, b);
+      a.negs_draw[(first + p) * (int64_t)K + (j - 1)] = row;
+    } else {
+      row = a.negs[(first + p) * (int64_t)K + (j - 1)];
+    }
+    rows_s[t] = row;
   }
   __syncthreads();
 
@@ -1022,19 +1043,37 @@ static int32_t check_sgns_args(const void* w_in, const void* w_out, int64_t num_
   return GS_OK;
 }
 
+// What the variants of the step add to the plain one.
+struct SgnsExtras {
+  float* sq_in = nullptr;          // Adam: second-moment tables and the two put coefficients
+  float* sq_out = nullptr;
+  float c1 = 1.f, c2 = 0.f;
+  const gs_alias* noise = nullptr; // negatives drawn inside the step (negs_draw != null)
+  uint64_t neg_seed = 0, neg_pair_base = 0;
+  int32_t* negs_draw = nullptr;
+};
+
 // Logits from (w_in, w_out); every touched row r of the destination tables becomes
 // round(dst[r] - lr * gradient_r).  Plain SGD: destination = the tables themselves.
 static int32_t run_sgns(void* w_in, void* w_out, void* dst_in, void* dst_out, int64_t num_nodes,
                         int32_t dim, int32_t dtype, const int32_t* centers, const int32_t* contexts,
                         const int32_t* negs, int64_t num_pairs, int32_t k, float lr,
                         double* loss_sum_out, const SgnsPlan& p, hipStream_t stream,
-                        float* sq_in = nullptr, float* sq_out = nullptr, float c1 = 1.f,
-                        float c2 = 0.f) {
+                        const SgnsExtras& x = SgnsExtras()) {
   SgnsArgs a;
-  a.sq_in = sq_in;
-  a.sq_out = sq_out;
-  a.c1 = c1;
-  a.c2 = c2;
+  a.sq_in = x.sq_in;
+  a.sq_out = x.sq_out;
+  a.c1 = x.c1;
+  a.c2 = x.c2;
+  a.draw_negs = x.negs_draw != nullptr ? 1 : 0;
+  const bool weighted = x.noise != nullptr && x.noise->prob != nullptr;
+  a.noise_prob = weighted ? x.noise->prob : nullptr;
+  a.noise_alias = weighted ? x.noise->alias : nullptr;
+  a.noise_packed = weighted ? reinterpret_cast<const uint2*>(x.noise->packed) : nullptr;
+  a.neg_seed = x.neg_seed;
+  a.neg_pair_base = x.neg_pair_base;
+  a.negs_draw = x.negs_draw;
+  if (a.draw_negs) negs = x.negs_draw;
   a.w_in = w_in;
   a.w_out = w_out;
   a.dst_in = dst_in;
@@ -1106,6 +1145,45 @@ extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int3
   }
   return run_sgns(w_in, w_out, w_in, w_out, num_nodes, dim, dtype, centers, contexts, negs, num_pairs,
                   k, lr, loss_sum_out, p, stream);
+}
+
+// workspace of the fused call: the step's own, then the drawn negatives
+static size_t fused_negs_bytes(int64_t num_pairs, int32_t k) {
+  return align_up((size_t)(num_pairs > 0 ? num_pairs : 1) * (size_t)(k > 0 ? k : 1) * sizeof(int32_t));
+}
+
+extern "C" size_t gs_sgns_step_fused_workspace_bytes(int64_t num_pairs, int64_t num_nodes, int32_t k,
+                                                     int32_t dim, int32_t dtype) {
+  (void)dtype;
+  if (num_pairs < 0 || num_nodes < 0 || k < 0 || dim < 1) return 0;
+  return plan_sgns(nullptr, num_pairs, num_nodes, k, dim).bytes + fused_negs_bytes(num_pairs, k);
+}
+
+extern "C" int32_t gs_sgns_step_fused(void* w_in, void* w_out, int64_t num_nodes, int32_t dim,
+                                      int32_t dtype, const int32_t* centers, const int32_t* contexts,
+                                      int64_t num_pairs, const gs_alias* noise,
+                                      uint64_t pair_index_base, uint64_t neg_seed, int32_t k, float lr,
+                                      double* loss_sum_out, void* ws, size_t ws_bytes, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  // the negatives live in the workspace: hand the checker a non-null stand-in
+  const int32_t bad = check_sgns_args(w_in, w_out, num_nodes, dim, dtype, centers, contexts,
+                                      static_cast<const int32_t*>(ws), num_pairs, k, loss_sum_out, ws);
+  if (bad != GS_OK) return bad;
+  if (noise != nullptr && noise->prob != nullptr && !noise->alias) return GS_EINVAL;
+  SgnsPlan p = plan_sgns(ws, num_pairs, num_nodes, k, dim);
+  if (ws_bytes < p.bytes + fused_negs_bytes(num_pairs, k)) return GS_EWORKSPACE;
+  if (num_pairs == 0) {
+    zero_double_kernel<<<1, 1, 0, stream>>>(loss_sum_out);
+    GS_LAUNCH_CHECK();
+    return GS_OK;
+  }
+  SgnsExtras x;
+  x.noise = noise;
+  x.neg_seed = neg_seed;
+  x.neg_pair_base = pair_index_base;
+  x.negs_draw = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + p.bytes);
+  return run_sgns(w_in, w_out, w_in, w_out, num_nodes, dim, dtype, centers, contexts, nullptr,
+                  num_pairs, k, lr, loss_sum_out, p, stream, x);
 }
 
 extern "C" int32_t gs_sgns_momentum_step(void* w_in, void* w_out, void* m_in, void* m_out,
@@ -1187,9 +1265,13 @@ extern "C" int32_t gs_sgns_adam_step(float* w_in, float* w_out, float* m_in, flo
     zero_double_kernel<<<1, 1, 0, stream>>>(loss_sum_out);
     GS_LAUNCH_CHECK();
   } else {
+    SgnsExtras x;
+    x.sq_in = v_in;
+    x.sq_out = v_out;
+    x.c1 = 1.0f - beta1;
+    x.c2 = 1.0f - beta2;
     const int32_t rc = run_sgns(w_in, w_out, m_in, m_out, num_nodes, dim, GS_F32, centers, contexts,
-                                negs, num_pairs, k, -1.0f, loss_sum_out, p, stream, v_in, v_out,
-                                1.0f - beta1, 1.0f - beta2);
+                                negs, num_pairs, k, -1.0f, loss_sum_out, p, stream, x);
     if (rc != GS_OK) return rc;
   }
   // apply: w -= (lr / (1 - beta1^t)) * m / (sqrt(v) / sqrt(1 - beta2^t) + eps), every row

@@ -698,3 +698,68 @@ def test_sgns_adam_step_argument_errors(gs):
         gs.gs_sgns_adam_step(w[0].to(torch.bfloat16), *w[1:], i, i, n, 0.1, 0.9, 0.999, 1e-8, 1)
     loss = gs.gs_sgns_adam_step(*w, i, i, n, 0.1, 0.9, 0.999, 1e-8, 1)
     assert float(loss.item()) == pytest.approx(4 * 3 * np.log(2.0))
+
+
+# ----------------------------------------------------------------------------- fused negatives
+@pytest.mark.parametrize("dim,k,b,dtype,weighted,pack", [(128, 5, 50_001, "f32", True, True),
+                                                         (64, 3, 7_777, "f32", True, False),
+                                                         (64, 5, 65_536, "f32", False, False),
+                                                         (256, 10, 9_999, "bf16", True, True),
+                                                         (128, 0, 1_000, "f32", True, True)])
+def test_sgns_step_fused_draws_the_same_negatives(gs, oracle, cfg0, dim, k, b, dtype, weighted, pack):
+    """The fused call against the oracle's sample_negatives + sgns_step, two consecutive
+    batches with a pair index base beyond 32 bits."""
+    from paper_2407_15452_amd import inputs
+    wl, (off, nb), g = cfg0
+    n = wl.num_nodes
+    noise_h = noise_d = None
+    if weighted:
+        nw = inputs.noise_weights(torch.as_tensor(off)).numpy()
+        seg = np.array([0, n], dtype=np.int32)
+        noise_h = oracle.alias_build(seg, nw)
+        noise_d = gs.gs_alias_build(_t(seg), _t(nw), pack=pack)
+    f_in, f_out = inputs.random_tables(n, dim, seed=dim + k, scale=2.0 / dim ** 0.5)
+    rng = np.random.default_rng(b)
+    if dtype == "bf16":
+        d_in, d_out = f_in.to(torch.bfloat16).to(DEV), f_out.to(torch.bfloat16).to(DEV)
+        h_in, h_out = _bf16_bits(d_in).copy(), _bf16_bits(d_out).copy()
+        code = oracle.BF16
+    else:
+        d_in, d_out = f_in.to(DEV), f_out.to(DEV)
+        h_in, h_out = f_in.numpy().copy(), f_out.numpy().copy()
+        code = oracle.F32
+    base = (1 << 34) + 11
+    for it in range(2):
+        c = np.repeat(rng.integers(0, n, b // 8 + 1), 8)[:b].astype(np.int32)
+        o = rng.integers(0, n, b).astype(np.int32)
+        neg = oracle.sample_negatives(noise_h, n, b, k, seed=99, pair_index_base=base + it * b)
+        if k == 0:
+            neg = np.zeros((b, 0), dtype=np.int32)
+        want = oracle.sgns_step(h_in, h_out, c, o, neg, 0.01, dtype=code)
+        loss = gs.gs_sgns_step_fused(d_in, d_out, _t(c), _t(o), noise_d, k, 99, 0.01,
+                                     pair_index_base=base + it * b)
+        torch.cuda.synchronize()
+        assert abs(float(loss.item()) - want) <= LOSS_RTOL * abs(want)
+        if dtype == "bf16":
+            f32 = lambda bits: (bits.astype(np.uint32) << 16).view(np.float32)  # noqa: E731
+            for d_t, h_t in ((d_in, h_in), (d_out, h_out)):
+                got = _bf16_bits(d_t)
+                near = np.abs(got.astype(np.int32) - h_t.astype(np.int32)) <= 1
+                assert (near | (np.abs(f32(got) - f32(h_t)) <= EMB_ATOL)).all()
+                assert (got != h_t).mean() <= 1e-3
+                d_t.copy_(torch.from_numpy(h_t.view(np.int16)).view(torch.bfloat16))
+        else:
+            assert np.abs(d_in.cpu().numpy() - h_in).max() <= EMB_ATOL
+            assert np.abs(d_out.cpu().numpy() - h_out).max() <= EMB_ATOL
+
+
+def test_sgns_step_fused_argument_errors(gs):
+    w = [torch.zeros((10, 8), dtype=torch.float32, device=DEV) for _ in range(2)]
+    i = torch.zeros(4, dtype=torch.int32, device=DEV)
+    small = torch.empty(256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(gs.GsError):
+        gs.gs_sgns_step_fused(w[0], w[1], i, i, None, 2, 1, 0.1, ws=small)
+    with pytest.raises(gs.GsError):
+        gs.gs_sgns_step_fused(w[0], w[1], i, i, None, 61, 1, 0.1)
+    loss = gs.gs_sgns_step_fused(w[0], w[1], i, i, None, 2, 1, 0.1)
+    assert float(loss.item()) == pytest.approx(4 * 3 * np.log(2.0))
