@@ -272,6 +272,35 @@ def main():
         adam_ms = e0.elapsed_time(e1) / 5
         del a_tabs
 
+    # ------------------------------------------------------------------ fused negatives (extra)
+    # the same batches with the negatives drawn inside the step, against the two separate calls
+    fused_ws = torch.empty(gs.gs_sgns_step_fused_workspace_bytes(B, wl.num_nodes, k, wl.dim, sgns_dtype),
+                           dtype=torch.uint8, device=dev)
+
+    def two_calls(j):
+        gs.gs_sample_negatives(noise, wl.num_nodes, B, k, wl.neg_seed, pair_index_base=j * B, out=negs)
+        gs.gs_sgns_step(w_in, w_out, centers[j * B:(j + 1) * B], contexts[j * B:(j + 1) * B], negs, lr,
+                        loss_out=losses[:1], ws=sgns_ws)
+
+    def one_call(j):
+        gs.gs_sgns_step_fused(w_in, w_out, centers[j * B:(j + 1) * B], contexts[j * B:(j + 1) * B],
+                              noise, k, wl.neg_seed, lr, pair_index_base=j * B, loss_out=losses[:1],
+                              ws=fused_ws)
+
+    fused = {}
+    for name, fn in (("negatives_then_step_ms", two_calls), ("fused_step_ms", one_call)):
+        for j in range(min(2, K)):
+            fn(j)
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for j in range(K):
+            fn(j)
+        e1.record()
+        torch.cuda.synchronize()
+        fused[name] = e0.elapsed_time(e1) / K
+    del fused_ws
+
     # ------------------------------------------------------------------ LINE batches (extra)
     # B sampled edges (uniform over the CSR entries) + negatives + the same step
     line = None
@@ -352,6 +381,7 @@ def main():
         "mean_loss_per_pair": mean_loss,
         "momentum_step_ms": momentum_ms,
         "adam_step_ms": adam_ms,
+        "fused_negatives": fused,
         "line": line,
         "storage_ops": storage,
         "roofline": {"bound": "hbm", "kernel": "gs_sgns_step (all kernels of one call)",
