@@ -139,3 +139,66 @@ def test_pairs_negatives_and_sgns_batch(gs, oracle, big):
     assert abs(got - want) <= 1e-5 * abs(want)
     assert np.abs(w_in.cpu().numpy() - h_in).max() <= 1e-5
     assert np.abs(w_out.cpu().numpy() - h_out).max() <= 1e-5
+
+
+def test_line_edges_full_size(gs, oracle, big):
+    """2,000,000 LINE samples over the 140 M entries, uniform and weighted (alias table over
+    all entries, built by the long-segment kernel), every sample against the oracle."""
+    wl, g, off, nb, _, _ = big
+    B = wl.batch_pairs
+    base = (1 << 36) + 1
+    c, o = gs.gs_sample_edges(g, None, B, seed=wl.walk_seed, sample_index_base=base)
+    want_c, want_o = oracle.sample_edges(off, nb, B, seed=wl.walk_seed, sample_index_base=base)
+    np.testing.assert_array_equal(c.cpu().numpy(), want_c)
+    np.testing.assert_array_equal(o.cpu().numpy(), want_o)
+    from paper_2407_15452_amd import inputs
+    E = nb.size
+    w = (inputs.hashed_u32(7, torch.arange(E, dtype=torch.int64, device=DEV), 3) >> 8).to(torch.float32)
+    w = (w * (1.0 / (1 << 24))) ** 4 + 1e-3                         # skewed positive weights
+    seg = torch.tensor([0, E], dtype=torch.int64, device=DEV)
+    table = gs.gs_alias_build(seg, w, pack=True)
+    c, o = gs.gs_sample_edges(g, table, B, seed=5)
+    host_table = (table.prob.cpu().numpy(), table.alias.cpu().numpy())
+    want_c, want_o = oracle.sample_edges(off, nb, B, seed=5, edge_alias=host_table)
+    np.testing.assert_array_equal(c.cpu().numpy(), want_c)
+    np.testing.assert_array_equal(o.cpu().numpy(), want_o)
+    # the table itself on a property that holds at any size: implied mass of every entry
+    # (own acceptance + what the aliases send to it) equals its weight share
+    prob, alias = host_table
+    mass = prob.astype(np.float64)
+    np.add.at(mass, alias, 1.0 - prob.astype(np.float64))
+    share = w.cpu().numpy().astype(np.float64)
+    share *= E / share.sum()
+    assert np.abs(mass - share).max() <= 1e-4 * max(1.0, share.max())
+
+
+def test_storage_ops_full_size(gs, oracle, big):
+    """The ids of one 2,000,000-pair batch (14 M ids): merged ids against numpy, get and put
+    of the distinct rows against the oracle on a sample of rows."""
+    wl, g, off, nb, _, _ = big
+    from paper_2407_15452_amd import inputs
+    n, d, B, K = wl.num_nodes, wl.dim, wl.batch_pairs, wl.num_neg
+    c, o = gs.gs_sample_edges(g, None, B, seed=3)
+    negs = gs.gs_sample_negatives(None, n, B, K, seed=4, device=DEV)
+    ids = torch.cat([c, o, negs.reshape(-1)])
+    u, count, inv = gs.gs_unique_ids(ids, n)
+    k = int(count.item())
+    want_u, want_inv = np.unique(ids.cpu().numpy(), return_inverse=True)
+    assert k == want_u.size
+    np.testing.assert_array_equal(u[:k].cpu().numpy(), want_u)
+    np.testing.assert_array_equal(inv.cpu().numpy(), want_inv)
+    table = inputs.random_tables(n, d, seed=6, scale=0.2, device=DEV)[0]
+    before = table.clone()
+    block = gs.gs_get_rows(table, u, count=count)
+    assert torch.equal(block[:k], before[u[:k].long()])
+    delta = inputs.random_tables(k, d, seed=8, scale=1.0, device=DEV)[1]
+    gs.gs_put_rows(table, u, delta, -0.125, count=count)
+    rng = np.random.default_rng(0)
+    pick = np.sort(rng.choice(k, 2000, replace=False))
+    rows = want_u[pick]
+    sub = before[torch.as_tensor(rows, device=DEV).long()].cpu().numpy().copy()
+    oracle.put_rows(sub, np.arange(rows.size, dtype=np.int32), delta.cpu().numpy()[pick], -0.125)
+    np.testing.assert_array_equal(table[torch.as_tensor(rows, device=DEV).long()].cpu().numpy(), sub)
+    untouched = torch.ones(n, dtype=torch.bool, device=DEV)
+    untouched[u[:k].long()] = False
+    assert torch.equal(table[untouched], before[untouched])
