@@ -61,6 +61,8 @@ def parse():
     ap.add_argument("--workload", type=int, default=2)
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the momentum / Adam / LINE / fused-negatives / get-put measurements")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for HBM byte counters)")
     ap.add_argument("--walk-sample", type=int, default=4_000_000,
@@ -231,134 +233,136 @@ def main():
     walk_steps_per_s = valid_steps / (walk_big_ms * 1e-3)
     del big
 
-    # ------------------------------------------------------------------ momentum variant (extra)
-    # the paper's optimizer (dense mult / sparse put / dense mult_add); timed on the last batch
-    momentum_ms = None
-    if 2 * wl.num_nodes * wl.dim * elem_bytes <= 32e9:
-        m_in, m_out = torch.zeros_like(w_in), torch.zeros_like(w_out)
+    # ------------------------------------------------------------------ extra measurements
+    # (other entry points on the same tables and batches; --no-extras leaves them out, e.g. for
+    # a kernel profile of the timed path alone)
+    momentum_ms = adam_ms = fused = line = storage = None
+    if not args.no_extras:
+        # ------------------------------------------------------------------ momentum variant (extra)
+        # the paper's optimizer (dense mult / sparse put / dense mult_add); timed on the last batch
+        if 2 * wl.num_nodes * wl.dim * elem_bytes <= 32e9:
+            m_in, m_out = torch.zeros_like(w_in), torch.zeros_like(w_out)
+            lo = (K - 1) * B
+            for _ in range(2):
+                gs.gs_sgns_momentum_step(w_in, w_out, m_in, m_out, centers[lo:lo + B],
+                                         contexts[lo:lo + B], negs, lr, 0.9, loss_out=losses[:1],
+                                         ws=sgns_ws)
+            torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            for _ in range(5):
+                gs.gs_sgns_momentum_step(w_in, w_out, m_in, m_out, centers[lo:lo + B],
+                                         contexts[lo:lo + B], negs, lr, 0.9, loss_out=losses[:1],
+                                         ws=sgns_ws)
+            e1.record()
+            torch.cuda.synchronize()
+            momentum_ms = e0.elapsed_time(e1) / 5
+            del m_in, m_out
+        if wl.dtype == "f32" and 6 * wl.num_nodes * wl.dim * 4 <= 48e9:
+            # throw-away copies: Adam's unit-sized steps would disturb the tables the later extras read
+            a_tabs = [w_in.clone(), w_out.clone()] + [torch.zeros_like(w_in) for _ in range(4)]
+            lo = (K - 1) * B
+            adam = lambda t: gs.gs_sgns_adam_step(*a_tabs, centers[lo:lo + B], contexts[lo:lo + B], negs,  # noqa: E731
+                                                  1e-3, 0.9, 0.999, 1e-8, t, loss_out=losses[:1],
+                                                  ws=sgns_ws)
+            for t in (1, 2):
+                adam(t)
+            torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            for t in range(3, 8):
+                adam(t)
+            e1.record()
+            torch.cuda.synchronize()
+            adam_ms = e0.elapsed_time(e1) / 5
+            del a_tabs
+
+        # ------------------------------------------------------------------ fused negatives (extra)
+        # the same batches with the negatives drawn inside the step, against the two separate calls
+        fused_ws = torch.empty(gs.gs_sgns_step_fused_workspace_bytes(B, wl.num_nodes, k, wl.dim, sgns_dtype),
+                               dtype=torch.uint8, device=dev)
+
+        def two_calls(j):
+            gs.gs_sample_negatives(noise, wl.num_nodes, B, k, wl.neg_seed, pair_index_base=j * B, out=negs)
+            gs.gs_sgns_step(w_in, w_out, centers[j * B:(j + 1) * B], contexts[j * B:(j + 1) * B], negs, lr,
+                            loss_out=losses[:1], ws=sgns_ws)
+
+        def one_call(j):
+            gs.gs_sgns_step_fused(w_in, w_out, centers[j * B:(j + 1) * B], contexts[j * B:(j + 1) * B],
+                                  noise, k, wl.neg_seed, lr, pair_index_base=j * B, loss_out=losses[:1],
+                                  ws=fused_ws)
+
+        fused = {}
+        for name, fn in (("negatives_then_step_ms", two_calls), ("fused_step_ms", one_call)):
+            for j in range(min(2, K)):
+                fn(j)
+            torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            for j in range(K):
+                fn(j)
+            e1.record()
+            torch.cuda.synchronize()
+            fused[name] = e0.elapsed_time(e1) / K
+        del fused_ws
+
+        # ------------------------------------------------------------------ LINE batches (extra)
+        # B sampled edges (uniform over the CSR entries) + negatives + the same step
+        if True:
+            lc = torch.empty(B, dtype=torch.int32, device=dev)
+            lo_ = torch.empty(B, dtype=torch.int32, device=dev)
+
+            def line_batch(it):
+                gs.gs_sample_edges(g, None, B, wl.walk_seed ^ 0x4c494e45, sample_index_base=it * B,
+                                   centers_out=lc, contexts_out=lo_)
+                gs.gs_sample_negatives(noise, wl.num_nodes, B, k, wl.neg_seed ^ 0x4c494e45,
+                                       pair_index_base=it * B, out=negs)
+                gs.gs_sgns_step(w_in, w_out, lc, lo_, negs, lr, loss_out=losses[:1], ws=sgns_ws)
+
+            for it in range(2):
+                line_batch(it)
+            torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            for it in range(2, 7):
+                line_batch(it)
+            e1.record()
+            torch.cuda.synchronize()
+            line_ms = e0.elapsed_time(e1) / 5
+            line = {"ms_per_batch": line_ms, "edges_per_s": B / (line_ms * 1e-3),
+                    "what": "gs_sample_edges + gs_sample_negatives + gs_sgns_step per batch of B edges"}
+            del lc, lo_
+
+        # ------------------------------------------------------------------ get / put of a batch (extra)
+        # the ids of the last batch: merge, fetch the block of distinct rows, add a block back
         lo = (K - 1) * B
-        for _ in range(2):
-            gs.gs_sgns_momentum_step(w_in, w_out, m_in, m_out, centers[lo:lo + B],
-                                     contexts[lo:lo + B], negs, lr, 0.9, loss_out=losses[:1],
-                                     ws=sgns_ws)
-        torch.cuda.synchronize()
-        e0, e1 = ev(), ev()
-        e0.record()
-        for _ in range(5):
-            gs.gs_sgns_momentum_step(w_in, w_out, m_in, m_out, centers[lo:lo + B],
-                                     contexts[lo:lo + B], negs, lr, 0.9, loss_out=losses[:1],
-                                     ws=sgns_ws)
-        e1.record()
-        torch.cuda.synchronize()
-        momentum_ms = e0.elapsed_time(e1) / 5
-        del m_in, m_out
-    adam_ms = None
-    if wl.dtype == "f32" and 6 * wl.num_nodes * wl.dim * 4 <= 48e9:
-        # throw-away copies: Adam's unit-sized steps would disturb the tables the later extras read
-        a_tabs = [w_in.clone(), w_out.clone()] + [torch.zeros_like(w_in) for _ in range(4)]
-        lo = (K - 1) * B
-        adam = lambda t: gs.gs_sgns_adam_step(*a_tabs, centers[lo:lo + B], contexts[lo:lo + B], negs,  # noqa: E731
-                                              1e-3, 0.9, 0.999, 1e-8, t, loss_out=losses[:1],
-                                              ws=sgns_ws)
-        for t in (1, 2):
-            adam(t)
-        torch.cuda.synchronize()
-        e0, e1 = ev(), ev()
-        e0.record()
-        for t in range(3, 8):
-            adam(t)
-        e1.record()
-        torch.cuda.synchronize()
-        adam_ms = e0.elapsed_time(e1) / 5
-        del a_tabs
+        batch_ids = torch.cat([centers[lo:lo + B], contexts[lo:lo + B], negs.reshape(-1)])
+        uniq_ws = torch.empty(gs.gs_unique_ids_workspace_bytes(batch_ids.numel()), dtype=torch.uint8,
+                              device=dev)
+        uniq, ucount, _ = gs.gs_unique_ids(batch_ids, wl.num_nodes, ws=uniq_ws)
+        n_uniq = int(ucount.item())
+        block = torch.empty((n_uniq, wl.dim), dtype=torch.float32, device=dev)
 
-    # ------------------------------------------------------------------ fused negatives (extra)
-    # the same batches with the negatives drawn inside the step, against the two separate calls
-    fused_ws = torch.empty(gs.gs_sgns_step_fused_workspace_bytes(B, wl.num_nodes, k, wl.dim, sgns_dtype),
-                           dtype=torch.uint8, device=dev)
-
-    def two_calls(j):
-        gs.gs_sample_negatives(noise, wl.num_nodes, B, k, wl.neg_seed, pair_index_base=j * B, out=negs)
-        gs.gs_sgns_step(w_in, w_out, centers[j * B:(j + 1) * B], contexts[j * B:(j + 1) * B], negs, lr,
-                        loss_out=losses[:1], ws=sgns_ws)
-
-    def one_call(j):
-        gs.gs_sgns_step_fused(w_in, w_out, centers[j * B:(j + 1) * B], contexts[j * B:(j + 1) * B],
-                              noise, k, wl.neg_seed, lr, pair_index_base=j * B, loss_out=losses[:1],
-                              ws=fused_ws)
-
-    fused = {}
-    for name, fn in (("negatives_then_step_ms", two_calls), ("fused_step_ms", one_call)):
-        for j in range(min(2, K)):
-            fn(j)
-        torch.cuda.synchronize()
-        e0, e1 = ev(), ev()
-        e0.record()
-        for j in range(K):
-            fn(j)
-        e1.record()
-        torch.cuda.synchronize()
-        fused[name] = e0.elapsed_time(e1) / K
-    del fused_ws
-
-    # ------------------------------------------------------------------ LINE batches (extra)
-    # B sampled edges (uniform over the CSR entries) + negatives + the same step
-    line = None
-    if True:
-        lc = torch.empty(B, dtype=torch.int32, device=dev)
-        lo_ = torch.empty(B, dtype=torch.int32, device=dev)
-
-        def line_batch(it):
-            gs.gs_sample_edges(g, None, B, wl.walk_seed ^ 0x4c494e45, sample_index_base=it * B,
-                               centers_out=lc, contexts_out=lo_)
-            gs.gs_sample_negatives(noise, wl.num_nodes, B, k, wl.neg_seed ^ 0x4c494e45,
-                                   pair_index_base=it * B, out=negs)
-            gs.gs_sgns_step(w_in, w_out, lc, lo_, negs, lr, loss_out=losses[:1], ws=sgns_ws)
-
-        for it in range(2):
-            line_batch(it)
-        torch.cuda.synchronize()
-        e0, e1 = ev(), ev()
-        e0.record()
-        for it in range(2, 7):
-            line_batch(it)
-        e1.record()
-        torch.cuda.synchronize()
-        line_ms = e0.elapsed_time(e1) / 5
-        line = {"ms_per_batch": line_ms, "edges_per_s": B / (line_ms * 1e-3),
-                "what": "gs_sample_edges + gs_sample_negatives + gs_sgns_step per batch of B edges"}
-        del lc, lo_
-
-    # ------------------------------------------------------------------ get / put of a batch (extra)
-    # the ids of the last batch: merge, fetch the block of distinct rows, add a block back
-    lo = (K - 1) * B
-    batch_ids = torch.cat([centers[lo:lo + B], contexts[lo:lo + B], negs.reshape(-1)])
-    uniq_ws = torch.empty(gs.gs_unique_ids_workspace_bytes(batch_ids.numel()), dtype=torch.uint8,
-                          device=dev)
-    uniq, ucount, _ = gs.gs_unique_ids(batch_ids, wl.num_nodes, ws=uniq_ws)
-    n_uniq = int(ucount.item())
-    block = torch.empty((n_uniq, wl.dim), dtype=torch.float32, device=dev)
-
-    def timed(fn, reps=5):
-        fn()
-        torch.cuda.synchronize()
-        a, b = ev(), ev()
-        a.record()
-        for _ in range(reps):
+        def timed(fn, reps=5):
             fn()
-        b.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) / reps
+            torch.cuda.synchronize()
+            a, b = ev(), ev()
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
 
-    unique_ms = timed(lambda: gs.gs_unique_ids(batch_ids, wl.num_nodes, ws=uniq_ws))
-    get_ms = timed(lambda: gs.gs_get_rows(w_out, uniq[:n_uniq], out=block))
-    put_ms = timed(lambda: gs.gs_put_rows(w_out, uniq[:n_uniq], block, 0.0))
-    rb_blk = wl.dim * 4
-    row_bytes = wl.dim * elem_bytes
-    storage = {"batch_ids": int(batch_ids.numel()), "distinct": n_uniq, "unique_ms": unique_ms,
-               "get_ms": get_ms, "get_GBps": n_uniq * (row_bytes + rb_blk) / get_ms / 1e6,
-               "put_ms": put_ms, "put_GBps": n_uniq * (2 * row_bytes + rb_blk) / put_ms / 1e6}
-    del block, uniq_ws, batch_ids
+        unique_ms = timed(lambda: gs.gs_unique_ids(batch_ids, wl.num_nodes, ws=uniq_ws))
+        get_ms = timed(lambda: gs.gs_get_rows(w_out, uniq[:n_uniq], out=block))
+        put_ms = timed(lambda: gs.gs_put_rows(w_out, uniq[:n_uniq], block, 0.0))
+        rb_blk = wl.dim * 4
+        row_bytes = wl.dim * elem_bytes
+        storage = {"batch_ids": int(batch_ids.numel()), "distinct": n_uniq, "unique_ms": unique_ms,
+                   "get_ms": get_ms, "get_GBps": n_uniq * (row_bytes + rb_blk) / get_ms / 1e6,
+                   "put_ms": put_ms, "put_GBps": n_uniq * (2 * row_bytes + rb_blk) / put_ms / 1e6}
+        del block, uniq_ws, batch_ids
 
     walk_kind = ("node2vec p=%g q=%g" % (wl.p, wl.q)) if wl.node2vec else "first-order"
     walk_kind += ", alias-weighted" if wl.weighted else ", uniform"
