@@ -1,9 +1,10 @@
 // gs_alias_build: alias tables, one per segment, in the canonical first-in
 // first-out construction order stated in gs.h (Walker 1977 / Vose 1991).
 // The order of the fp64 operations is part of the definition of the table, so
-// each segment is built sequentially by one lane; parallelism is across
-// segments (per-row tables of a weighted graph).  A single long segment (the
-// noise table) is built by one workgroup instead, see alias_build_long_kernel.
+// each short segment is built sequentially by one lane; parallelism is across
+// segments (per-row tables of a weighted graph).  Long segments (the noise
+// table, the rows of hub nodes) are built by one workgroup each, see
+// alias_build_long_kernel.
 #include "common.h"
 
 namespace gs {
@@ -16,13 +17,14 @@ __global__ __launch_bounds__(64) void alias_build_kernel(const OffT* __restrict_
                                                          int32_t* __restrict__ alias_out,
                                                          double* __restrict__ mass_ws,
                                                          int32_t* __restrict__ small_ws,
-                                                         int32_t* __restrict__ large_ws) {
+                                                         int32_t* __restrict__ large_ws,
+                                                         int64_t skip_from) {
 #pragma clang fp contract(off)  // every fp64 operation below must round on its own
   const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (s >= num_segments) return;
   const int64_t begin = (int64_t)seg_offsets[s];
   const int64_t n = (int64_t)seg_offsets[s + 1] - begin;
-  if (n <= 0) return;
+  if (n <= 0 || n >= skip_from) return;        // long segments are left to the workgroup kernel
   const float* w = weights + begin;
   float* prob = prob_out + begin;
   int32_t* alias = alias_out + begin;
@@ -74,8 +76,8 @@ __global__ __launch_bounds__(64) void alias_build_kernel(const OffT* __restrict_
 }
 
 // ---------------------------------------------------------------------------
-// One long segment (the noise table): the same construction, same order, run by
-// one workgroup of 1024 lanes.
+// A long segment (the noise table, a hub row): the same construction, same order,
+// run by one workgroup of 1024 lanes.
 //
 // The sequential loop pairs the oldest small with the oldest large and appends
 // the large to the back of one of the two lists.  If both lists hold at least m
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(64) void alias_build_kernel(const OffT* __restrict_
 // adds them one by one.
 // ---------------------------------------------------------------------------
 constexpr int kLongThreads = 1024;
-constexpr int64_t kLongSegment = 8192;      // single segments at least this long use the workgroup
+constexpr int64_t kLongSegment = 8192;      // segments at least this long use the workgroup
 constexpr int kSerialBelow = 64;            // rounds narrower than this are run by lane 0
 
 // loads that must see what other lanes of the workgroup stored earlier (bypass the L1)
@@ -121,23 +123,49 @@ __device__ __forceinline__ void block_rank(bool flag, uint32_t* wave_tot, int& r
   total = all;
 }
 
+// the segments the workgroup kernel takes, in any order
+template <typename OffT>
+__global__ void alias_find_long_kernel(const OffT* __restrict__ seg_offsets, int64_t num_segments,
+                                       int64_t* __restrict__ long_ids, int64_t capacity,
+                                       unsigned long long* __restrict__ long_count) {
+  const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= num_segments) return;
+  if ((int64_t)seg_offsets[s + 1] - (int64_t)seg_offsets[s] >= kLongSegment) {
+    // capacity = total_entries / kLongSegment bounds the count when the offsets add up to
+    // total_entries; an inconsistent pair of arguments must still not write out of bounds
+    const unsigned long long at = atomicAdd(long_count, 1ull);
+    if (at < (unsigned long long)capacity) long_ids[at] = s;
+  }
+}
+
+__global__ void zero_u64_kernel(unsigned long long* p) { *p = 0ull; }
+
+// One workgroup per long segment.  long_ids == null: the single segment 0.
+// Scratch per entry of the segment, at the segment's own offsets: mass, the
+// small list (n entries), the large list (2n: appended without wrapping).
 template <typename OffT>
 __global__ __launch_bounds__(kLongThreads) void alias_build_long_kernel(
-    const OffT* __restrict__ seg_offsets, const float* __restrict__ weights,
-    float* __restrict__ prob_out, int32_t* __restrict__ alias_out, double* mass,
-    int32_t* small_q /* n */, int32_t* large_q /* 2n */) {
+    const OffT* __restrict__ seg_offsets, const int64_t* __restrict__ long_ids,
+    const unsigned long long* __restrict__ long_count, const float* __restrict__ weights,
+    float* __restrict__ prob_out, int32_t* __restrict__ alias_out, double* mass_ws,
+    int32_t* small_ws, int32_t* large_ws) {
 #pragma clang fp contract(off)  // every fp64 operation below must round on its own
   __shared__ double tile_s[kLongThreads];
   __shared__ uint32_t wave_tot[kLongThreads / 64];
   __shared__ double S_s;
   __shared__ int64_t q_s[4];                  // small head/tail, large head/tail after a serial stretch
   const int tid = threadIdx.x;
-  const int64_t begin = (int64_t)seg_offsets[0];
-  const int64_t n = (int64_t)seg_offsets[1] - begin;
+  if (long_ids != nullptr && (unsigned long long)blockIdx.x >= *long_count) return;
+  const int64_t seg = long_ids != nullptr ? long_ids[blockIdx.x] : 0;
+  const int64_t begin = (int64_t)seg_offsets[seg];
+  const int64_t n = (int64_t)seg_offsets[seg + 1] - begin;
   if (n <= 0) return;
   const float* w = weights + begin;
   float* prob = prob_out + begin;
   int32_t* alias = alias_out + begin;
+  double* mass = mass_ws + begin;
+  int32_t* small_q = small_ws + begin;
+  int32_t* large_q = large_ws + 2 * begin;
 
   // S: index-order sum
   double run = 0.0;
@@ -245,6 +273,9 @@ __global__ void alias_pack_kernel(const float* __restrict__ prob, const int32_t*
 struct AliasPlan {
   double* mass;
   int32_t *small_q, *large_q;
+  int64_t* long_ids;
+  unsigned long long* long_count;
+  int64_t max_long;
   size_t bytes;
 };
 
@@ -255,8 +286,45 @@ static AliasPlan plan_alias(void* ws, int64_t total_entries) {
   p.mass = cv.take<double>(t);
   p.small_q = cv.take<int32_t>(t);
   p.large_q = cv.take<int32_t>(2 * t);   // the workgroup variant appends without wrapping
+  p.max_long = (int64_t)(t / (size_t)kLongSegment) + 1;
+  p.long_ids = cv.take<int64_t>((size_t)p.max_long);
+  p.long_count = cv.take<unsigned long long>(1);
   p.bytes = cv.used;
   return p;
+}
+
+template <typename OffT>
+static int32_t launch_alias_build(const OffT* seg_offsets, int64_t num_segments, int64_t total_entries,
+                                  const float* weights, float* prob_out, int32_t* alias_out,
+                                  const AliasPlan& p, hipStream_t stream) {
+  if (num_segments == 1) {
+    if (total_entries >= kLongSegment) {
+      alias_build_long_kernel<OffT><<<1, kLongThreads, 0, stream>>>(
+          seg_offsets, nullptr, nullptr, weights, prob_out, alias_out, p.mass, p.small_q, p.large_q);
+      GS_LAUNCH_CHECK();
+      return GS_OK;
+    }
+  }
+  const int threads = 64;
+  const unsigned blocks = (unsigned)ceil_div(num_segments, threads);
+  // at most this many segments can be long; none: the lane kernel alone
+  const int64_t max_long = min(num_segments, total_entries / kLongSegment);
+  alias_build_kernel<OffT><<<blocks, threads, 0, stream>>>(
+      seg_offsets, num_segments, weights, prob_out, alias_out, p.mass, p.small_q, p.large_q,
+      max_long > 0 ? kLongSegment : INT64_MAX);
+  GS_LAUNCH_CHECK();
+  if (max_long > 0) {
+    zero_u64_kernel<<<1, 1, 0, stream>>>(p.long_count);
+    GS_LAUNCH_CHECK();
+    alias_find_long_kernel<OffT><<<(unsigned)ceil_div(num_segments, 256), 256, 0, stream>>>(
+        seg_offsets, num_segments, p.long_ids, max_long, p.long_count);
+    GS_LAUNCH_CHECK();
+    alias_build_long_kernel<OffT><<<(unsigned)max_long, kLongThreads, 0, stream>>>(
+        seg_offsets, p.long_ids, p.long_count, weights, prob_out, alias_out, p.mass, p.small_q,
+        p.large_q);
+    GS_LAUNCH_CHECK();
+  }
+  return GS_OK;
 }
 
 }  // namespace gs
@@ -280,26 +348,11 @@ extern "C" int32_t gs_alias_build(const void* seg_offsets, int32_t offset_bits, 
   AliasPlan p = plan_alias(ws, total_entries);
   if (ws_bytes < p.bytes) return GS_EWORKSPACE;
   if (num_segments == 0 || total_entries == 0) return GS_OK;
-  if (num_segments == 1 && total_entries >= kLongSegment) {
-    if (offset_bits == 64)
-      alias_build_long_kernel<int64_t><<<1, kLongThreads, 0, stream>>>((const int64_t*)seg_offsets,
-          weights, prob_out, alias_out, p.mass, p.small_q, p.large_q);
-    else
-      alias_build_long_kernel<int32_t><<<1, kLongThreads, 0, stream>>>((const int32_t*)seg_offsets,
-          weights, prob_out, alias_out, p.mass, p.small_q, p.large_q);
-    GS_LAUNCH_CHECK();
-    return GS_OK;
-  }
-  const int threads = 64;
-  const unsigned blocks = (unsigned)ceil_div(num_segments, threads);
   if (offset_bits == 64)
-    alias_build_kernel<int64_t><<<blocks, threads, 0, stream>>>((const int64_t*)seg_offsets,
-        num_segments, weights, prob_out, alias_out, p.mass, p.small_q, p.large_q);
-  else
-    alias_build_kernel<int32_t><<<blocks, threads, 0, stream>>>((const int32_t*)seg_offsets,
-        num_segments, weights, prob_out, alias_out, p.mass, p.small_q, p.large_q);
-  GS_LAUNCH_CHECK();
-  return GS_OK;
+    return launch_alias_build((const int64_t*)seg_offsets, num_segments, total_entries, weights,
+                              prob_out, alias_out, p, stream);
+  return launch_alias_build((const int32_t*)seg_offsets, num_segments, total_entries, weights, prob_out,
+                            alias_out, p, stream);
 }
 
 extern "C" int32_t gs_alias_pack(const float* prob, const int32_t* alias, int64_t total_entries,

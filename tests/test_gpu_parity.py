@@ -817,3 +817,22 @@ def test_step_replays_from_a_captured_graph(gs, oracle, cfg0):
         assert np.abs(d_out.cpu().numpy() - h_out).max() <= EMB_ATOL * (it + 1)
         # eager work of the program's own between the replays
         _ = (d_in * 2).sum().item()
+
+
+@pytest.mark.parametrize("bits", [32, 64])
+def test_alias_build_rows_of_hub_nodes(gs, oracle, bits):
+    """Per-row tables of a graph whose hub rows are long enough for the workgroup kernel
+    (>= 8192 entries), next to rows just below the threshold, short rows and empty rows."""
+    rng = np.random.default_rng(bits)
+    lens = np.concatenate([[20_000, 0, 8_192, 8_191, 1, 0, 50_000, 9_000],
+                           rng.integers(0, 40, 3_000), [12_345]]).astype(np.int64)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    total = int(off[-1])
+    w = rng.lognormal(0, 2.0, total).astype(np.float32)
+    w[rng.random(total) < 0.05] = 0
+    w[off[6]:off[6] + 10] = 1e6                              # a few very heavy entries in a hub row
+    off = off.astype(np.int64 if bits == 64 else np.int32)
+    prob, alias = oracle.alias_build(off, w)
+    a = gs.gs_alias_build(_t(off), _t(w))
+    np.testing.assert_array_equal(a.alias.cpu().numpy(), alias)
+    np.testing.assert_array_equal(a.prob.cpu().numpy(), prob)
