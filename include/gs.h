@@ -218,7 +218,11 @@ int32_t gs_sample_edges(const gs_csr* g, const gs_alias* edge_alias, int64_t num
  *   summed in fp32 (bf16: round to nearest even).
  *   dim must be a multiple of 4 (fp32) or 8 (bf16) and at most 1024; k <= 60;
  *   num_pairs * (k+1) < 2^31.  Rows that the batch does not name are not
- *   touched.  The workspace holds the per-term coefficients, the terms
+ *   touched.  w_in and w_out must be two tables (GS_EINVAL if they are the
+ *   same address).  The ids live on the device and are checked there: an id
+ *   outside [0, num_nodes) is treated as row 0, so no access leaves the
+ *   tables, and loss_sum_out is set to NaN to report it (the tables are then
+ *   not meaningful).  The workspace holds the per-term coefficients, the terms
  *   regrouped by destination row, a counter per node, an fp32 side buffer for
  *   rows with many terms and the staged centre-row gradients.
  * ------------------------------------------------------------------------ */

@@ -102,7 +102,17 @@ struct SgnsArgs {
   int64_t forward_blocks_per_xcd;
   int32_t update_lds_bytes; // LDS for the block-level sum of long-row partials (0: not used)
   double* loss_out;
+  uint32_t* bad_ids;        // set when a centre / context / negative id is not a row of the tables
 };
+
+// Ids come from device memory the host cannot inspect.  An id outside
+// [0, num_nodes) is read as row 0 everywhere (so no access leaves the tables)
+// and flagged; the call then reports a NaN loss.
+__device__ __forceinline__ int32_t checked_row(const SgnsArgs& a, int32_t id) {
+  if ((uint32_t)id < (uint32_t)a.num_nodes) return id;
+  *a.bad_ids = 1u;
+  return 0;
+}
 
 // ---- small device helpers ---------------------------------------------------------
 // sum over the 16 lanes of a DPP row; every lane gets the total
@@ -327,8 +337,9 @@ __global__ void fill_u32_kernel(uint32_t* __restrict__ p, int64_t n, uint32_t va
   if (i < n) p[i] = value;
 }
 
-__global__ void fill_f32x4_kernel(float4* __restrict__ p, int64_t n4) {
+__global__ void fill_f32x4_kernel(float4* __restrict__ p, int64_t n4, uint32_t* __restrict__ flag) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i == 0) *flag = 0u;
   if (i < n4) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
@@ -377,19 +388,19 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
   int32_t* cen_s = idx_s + group_in_block * (kChunkPairs * (K1 + 1));
   int32_t* rows_s = cen_s + kChunkPairs;
   for (int h = threadIdx.x; h < kHotSlots; h += kSgnsThreads) { hot_key[h] = -1; hot_cnt[h] = 0u; }
-  if (l16 < count) cen_s[l16] = a.centers[first + l16];
+  if (l16 < count) cen_s[l16] = checked_row(a, a.centers[first + l16]);
   for (int t = l16; t < count * K1; t += kGroupLanes) {
     const int p = t / K1, j = t - p * K1;
     int32_t row;
     if (j == 0) {
-      row = a.contexts[first + p];
+      row = checked_row(a, a.contexts[first + p]);
     } else if (a.draw_negs) {
       const Block4 b = philox_at(a.neg_seed, a.neg_pair_base + (uint64_t)(first + p), (uint32_t)(j - 1),
                                  0x80000000u);
       row = (int32_t)table_draw(a.noise_prob, a.noise_alias, a.noise_packed, (uint64_t)a.num_nodes, b);
       a.negs_draw[(first + p) * (int64_t)K + (j - 1)] = row;
     } else {
-      row = a.negs[(first + p) * (int64_t)K + (j - 1)];
+      row = checked_row(a, a.negs[(first + p) * (int64_t)K + (j - 1)]);
     }
     rows_s[t] = row;
   }
@@ -589,12 +600,12 @@ __global__ __launch_bounds__(256) void sgns_place_kernel(SgnsArgs a) {
   const int K1 = a.k + 1;
   const int64_t i = e / K1;
   const int j = (int)(e - i * K1);
-  const int32_t row = (j == 0) ? a.contexts[i] : a.negs[i * (int64_t)a.k + (j - 1)];
+  const int32_t row = checked_row(a, (j == 0) ? a.contexts[i] : a.negs[i * (int64_t)a.k + (j - 1)]);
   const uint32_t begin = a.cnt[row], len = a.cnt[row + 1] - begin;
   const uint32_t rk = a.rank[e];
   Term t;
   t.row = row;
-  t.center = a.centers[i];
+  t.center = checked_row(a, a.centers[i]);
   t.coef = -a.lr * a.g[e];
   t.where = min(len, 65535u) | (min(rk, 65535u) << 16);
   a.sorted[begin + rk] = t;
@@ -840,7 +851,9 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_apply_kernel(SgnsArgs a) {
 }
 
 __global__ __launch_bounds__(256) void sgns_finish_kernel(const double* __restrict__ partials,
-                                                          int64_t count, double* __restrict__ out) {
+                                                          int64_t count,
+                                                          const uint32_t* __restrict__ bad_ids,
+                                                          double* __restrict__ out) {
   __shared__ double s[256];
   double acc = 0.0;
   for (int64_t i = threadIdx.x; i < count; i += 256) acc += partials[i];
@@ -850,7 +863,7 @@ __global__ __launch_bounds__(256) void sgns_finish_kernel(const double* __restri
     if ((int)threadIdx.x < w) s[threadIdx.x] += s[threadIdx.x + w];
     __syncthreads();
   }
-  if (threadIdx.x == 0) *out = s[0];
+  if (threadIdx.x == 0) *out = (*bad_ids != 0u) ? __longlong_as_double(0x7ff8000000000000ll) : s[0];
 }
 
 // ---- host side -----------------------------------------------------------------------------
@@ -864,6 +877,7 @@ struct SgnsPlan {
   uint32_t* rank;
   uint32_t* cnt;
   uint32_t* tile_sums;
+  uint32_t* bad_ids;
   Term* sorted;
   float* long_acc;
   int32_t* stage_center;
@@ -884,6 +898,7 @@ static SgnsPlan plan_sgns(void* ws, int64_t num_pairs, int64_t num_nodes, int32_
   p.rank = cv.take<uint32_t>(terms);
   p.cnt = cv.take<uint32_t>(n1);
   p.tile_sums = cv.take<uint32_t>((size_t)ceil_div((int64_t)n1, kScanTile));
+  p.bad_ids = cv.take<uint32_t>(1);
   p.sorted = cv.take<Term>(terms);
   p.long_acc = cv.take<float>((size_t)p.long_slots * (size_t)dim);
   p.stage_center = cv.take<int32_t>(b);
@@ -899,7 +914,8 @@ static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
   fill_u32_kernel<<<(unsigned)ceil_div(n1, 256), 256, 0, stream>>>(a.cnt, n1, 0u);
   GS_LAUNCH_CHECK();
   const int64_t long4 = a.long_slots * (int64_t)(a.dim >> 2);
-  fill_f32x4_kernel<<<(unsigned)ceil_div(long4, 256), 256, 0, stream>>>((float4*)a.long_acc, long4);
+  fill_f32x4_kernel<<<(unsigned)ceil_div(long4, 256), 256, 0, stream>>>((float4*)a.long_acc, long4,
+                                                                     a.bad_ids);
   GS_LAUNCH_CHECK();
   const size_t idx_lds = (size_t)kGroupsPerBlock * kChunkPairs * (a.k + 2) * sizeof(int32_t);
   sgns_forward_kernel<T, VPL, RB><<<(unsigned)(a.forward_blocks_per_xcd * 8), kSgnsThreads, idx_lds,
@@ -941,7 +957,7 @@ static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
   GS_LAUNCH_CHECK();
   sgns_apply_kernel<T><<<slot_blocks, kSgnsThreads, 0, stream>>>(a);
   GS_LAUNCH_CHECK();
-  sgns_finish_kernel<<<1, 256, 0, stream>>>(a.loss_partials, a.forward_blocks, a.loss_out);
+  sgns_finish_kernel<<<1, 256, 0, stream>>>(a.loss_partials, a.forward_blocks, a.bad_ids, a.loss_out);
   GS_LAUNCH_CHECK();
   return GS_OK;
 }
@@ -1039,6 +1055,7 @@ static int32_t check_sgns_args(const void* w_in, const void* w_out, int64_t num_
   if (num_pairs > 0 && (!centers || !contexts || (k > 0 && !negs))) return GS_EINVAL;
   if (num_pairs * (int64_t)(k + 1) > (int64_t)0x7fffffff) return GS_EOVERFLOW;
   if (!aligned(w_in, 16) || !aligned(w_out, 16)) return GS_EINVAL;
+  if (w_in == w_out) return GS_EINVAL;   // context rows are written while input rows are still read
   if (!ws || !aligned(ws, 256)) return GS_EINVAL;
   return GS_OK;
 }
@@ -1092,6 +1109,7 @@ static int32_t run_sgns(void* w_in, void* w_out, void* dst_in, void* dst_out, in
   a.rank = p.rank;
   a.cnt = p.cnt;
   a.tile_sums = p.tile_sums;
+  a.bad_ids = p.bad_ids;
   a.sorted = p.sorted;
   a.long_acc = p.long_acc;
   a.stage_center = p.stage_center;

@@ -836,3 +836,26 @@ def test_alias_build_rows_of_hub_nodes(gs, oracle, bits):
     a = gs.gs_alias_build(_t(off), _t(w))
     np.testing.assert_array_equal(a.alias.cpu().numpy(), alias)
     np.testing.assert_array_equal(a.prob.cpu().numpy(), prob)
+
+
+def test_sgns_step_reports_ids_that_are_not_rows(gs):
+    """Ids outside [0, num_nodes) cannot be seen by the host: the kernels treat them as row 0
+    (no access outside the tables) and the loss comes back as NaN; a clean call afterwards
+    with the same workspace reports a finite loss again."""
+    n, d, b, k = 1000, 64, 4096, 3
+    rng = np.random.default_rng(0)
+    w_in = torch.zeros((n, d), dtype=torch.float32, device=DEV)
+    w_out = torch.zeros((n, d), dtype=torch.float32, device=DEV)
+    c = rng.integers(0, n, b).astype(np.int32)
+    o = rng.integers(0, n, b).astype(np.int32)
+    neg = rng.integers(0, n, (b, k)).astype(np.int32)
+    ws = torch.empty(gs.gs_sgns_step_workspace_bytes(b, n, k, d), dtype=torch.uint8, device=DEV)
+    for which in range(3):
+        bad = [c.copy(), o.copy(), neg.copy()]
+        bad[which].reshape(-1)[17] = n if which != 1 else -1
+        loss = gs.gs_sgns_step(w_in, w_out, _t(bad[0]), _t(bad[1]), _t(bad[2]), 0.01, ws=ws)
+        assert np.isnan(float(loss.item()))
+    loss = gs.gs_sgns_step(w_in, w_out, _t(c), _t(o), _t(neg), 0.01, ws=ws)
+    assert np.isfinite(float(loss.item()))
+    with pytest.raises(gs.GsError):            # one table on both sides
+        gs.gs_sgns_step(w_in, w_in, _t(c), _t(o), _t(neg), 0.01, ws=ws)
