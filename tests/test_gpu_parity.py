@@ -195,7 +195,8 @@ def test_walk_argument_errors(gs, cfg0):
 
 
 # ----------------------------------------------------------------------------- pairs / negatives
-@pytest.mark.parametrize("walk_len,window", [(20, 5), (5, 3), (4, 7), (1, 2), (80, 10), (300, 2)])
+@pytest.mark.parametrize("walk_len,window", [(20, 5), (5, 3), (4, 7), (1, 2), (80, 10), (300, 2),
+                                             (4096, 3), (2, 1), (64, 64)])
 def test_make_pairs(gs, oracle, walk_len, window):
     rng = np.random.default_rng(walk_len * 31 + window)
     nw = 1500 if walk_len < 100 else 150
@@ -256,7 +257,8 @@ def _sgns_case(gs, oracle, w_in, w_out, c, o, neg, lr):
 
 
 @pytest.mark.parametrize("dim,k,b", [(64, 5, 65_536), (128, 5, 50_001), (256, 10, 9_999),
-                                     (100, 3, 7_777), (4, 1, 513), (512, 2, 2_000)])
+                                     (100, 3, 7_777), (4, 1, 513), (512, 2, 2_000),
+                                     (1024, 60, 257), (768, 0, 1_000), (32, 60, 4_000)])
 def test_sgns_step_mid_training_state(gs, oracle, dim, k, b):
     from paper_2407_15452_amd import inputs
     n = 5000
@@ -377,7 +379,8 @@ def _bf16_bits(t):
 
 
 @pytest.mark.parametrize("dim,k,b", [(256, 10, 30_011), (128, 5, 50_001), (64, 5, 9_999),
-                                     (192, 3, 5_000), (8, 1, 513)])
+                                     (192, 3, 5_000), (8, 1, 513), (1024, 4, 1_000),
+                                     (512, 60, 300)])
 def test_sgns_step_bf16_tables(gs, oracle, dim, k, b):
     """bf16 storage, fp32 accumulation, one rounding per written element.
 
