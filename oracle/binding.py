@@ -48,7 +48,7 @@ def _load():
         for name in ("oracle_csr_build", "oracle_alias_build", "oracle_random_walk",
                      "oracle_node2vec_walk", "oracle_make_pairs", "oracle_sample_negatives",
                      "oracle_sgns_step", "oracle_sgns_momentum_step", "oracle_sample_edges", "oracle_unique_ids", "oracle_get_rows",
-                     "oracle_put_rows", "oracle_sgns_adam_step"):
+                     "oracle_put_rows", "oracle_sgns_adam_step", "oracle_line1_step"):
             getattr(_lib, name).restype = C.c_int32
         _lib.oracle_philox4x32_10.restype = None
     return _lib
@@ -291,4 +291,20 @@ def sgns_adam_step(w_in, w_out, m_in, m_out, v_in, v_out, centers, contexts, neg
         C.c_int64(num_pairs), C.c_int32(k), C.c_float(lr), C.c_float(beta1), C.c_float(beta2),
         C.c_float(eps), C.c_int64(t), C.byref(loss))
     _check(rc, "oracle_sgns_adam_step")
+    return loss.value
+
+
+def line1_step(w, sources, targets, negs, lr, dtype=F32):
+    """First-order LINE iteration on the single table w, in place; returns the summed loss."""
+    want = np.float32 if dtype == F32 else np.uint16
+    assert w.dtype == want and w.flags.c_contiguous
+    sources, targets = _i32(sources), _i32(targets)
+    negs = _i32(negs)
+    num_pairs = int(sources.shape[0])
+    k = int(negs.shape[1]) if negs.ndim == 2 else 0
+    loss = C.c_double(0.0)
+    rc = _load().oracle_line1_step(_ptr(w), C.c_int64(w.shape[0]), C.c_int32(w.shape[1]),
+                                   C.c_int32(dtype), _ptr(sources), _ptr(targets), _ptr(negs),
+                                   C.c_int64(num_pairs), C.c_int32(k), C.c_float(lr), C.byref(loss))
+    _check(rc, "oracle_line1_step")
     return loss.value

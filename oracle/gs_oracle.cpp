@@ -579,6 +579,38 @@ int32_t oracle_sgns_momentum_step(void* w_in, void* w_out, void* m_in, void* m_o
 
 
 // ---------------------------------------------------------------------------
+// LINE with first-order proximity (the LINE paper the text cites in §2.2 / §4):
+// one table w on both sides.  For sampled edge (s, t) and negatives n_k:
+//   x_0 = <w[s], w[t]>, x_k = <w[s], w[n_k]>, loss and g as in the SGNS step;
+//   gradient of w[s] += sum_j g_j w[row_j], gradient of w[row_j] += g_j w[s]
+// (a row gets both kinds of contribution when it appears on both sides), all
+// from the values before the call.  The rows are then written in two rounds,
+// each rounding once: first the contributions a row receives as target or
+// negative, then those it receives as source.
+// ---------------------------------------------------------------------------
+int32_t oracle_line1_step(void* w, int64_t num_nodes, int32_t dim, int32_t dtype,
+                          const int32_t* sources, const int32_t* targets, const int32_t* negs,
+                          int64_t num_pairs, int32_t k, float lr, double* loss_sum_out) {
+  if (!w || num_nodes < 1 || dim < 1 || num_pairs < 0 || k < 0 || !loss_sum_out) return ORACLE_EINVAL;
+  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_EINVAL;
+  if (num_pairs > 0 && (!sources || !targets || (k > 0 && !negs))) return ORACLE_EINVAL;
+  RowSums as_source, as_other;
+  int32_t rc = sgns_gradients(w, w, num_nodes, dim, dtype, sources, targets, negs, num_pairs, k,
+                              as_source, as_other, loss_sum_out);
+  if (rc != ORACLE_OK) return rc;
+  const double step = (double)lr;
+  for (auto& kv : as_other)
+    for (int32_t e = 0; e < dim; ++e)
+      write_elem(w, dtype, dim, kv.first, e,
+                 read_elem(w, dtype, dim, kv.first, e) - step * kv.second[(size_t)e]);
+  for (auto& kv : as_source)
+    for (int32_t e = 0; e < dim; ++e)
+      write_elem(w, dtype, dim, kv.first, e,
+                 read_elem(w, dtype, dim, kv.first, e) - step * kv.second[(size_t)e]);
+  return ORACLE_OK;
+}
+
+// ---------------------------------------------------------------------------
 // The same iteration with Adam (§3.2 names Adam next to SGD with momentum as an
 // optimizer kept inside the storage; the update rule is Kingma & Ba's), run the
 // same way as the momentum step: dense operations over every row around a sparse

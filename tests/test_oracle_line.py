@@ -8,6 +8,7 @@ stream whether drawn in one call or several, and a stream distinct from the
 walker's and the negative sampler's.
 """
 import numpy as np
+import pytest
 import scipy.stats as st
 
 
@@ -113,3 +114,62 @@ def test_line_batch_is_an_sgns_batch_over_edges(oracle):
     np.testing.assert_array_equal(a[same], w_in[same])
     np.testing.assert_array_equal(b[same], w_out[same])
     assert not np.array_equal(a[c[0]], w_in[c[0]])
+
+
+# ----------------------------------------------------------------------------- first order
+def _line1_dense(w, s, t, neg):
+    import torch
+    import torch.nn.functional as F
+    ws = w[torch.as_tensor(s, dtype=torch.long)]
+    pos = (ws * w[torch.as_tensor(t, dtype=torch.long)]).sum(1)
+    ng = (ws[:, None, :] * w[torch.as_tensor(neg, dtype=torch.long)]).sum(2)
+    return F.softplus(-pos).sum() + F.softplus(ng).sum()
+
+
+def test_line1_step_is_sgd_on_one_table(oracle):
+    """First-order LINE: both endpoints from the same table.  The step equals dense SGD on
+    that table with torch autograd (rows on both sides get both gradient parts; a pair with
+    s == t or a negative equal to the source is differentiated through both factors)."""
+    import torch
+    rng = np.random.default_rng(3)
+    n, d, b, k, lr = 25, 6, 80, 3, 0.05
+    w = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    s = rng.integers(0, 15, b).astype(np.int32)           # rows 15.. are never a source
+    t = rng.integers(0, 20, b).astype(np.int32)           # rows 20.. are never named
+    neg = rng.integers(0, 20, (b, k)).astype(np.int32)
+    t[:5] = s[:5]                                         # self pairs
+    neg[5:10, 0] = s[5:10]                                # the source among its negatives
+    tw = torch.tensor(w, dtype=torch.float64, requires_grad=True)
+    dense = _line1_dense(tw, s, t, neg)
+    dense.backward()
+    want = w.astype(np.float64) - np.float64(np.float32(lr)) * tw.grad.numpy()
+    got = w.copy()
+    loss = oracle.line1_step(got, s, t, neg, lr)
+    assert loss == pytest.approx(dense.item(), rel=1e-12)
+    np.testing.assert_allclose(got, want, atol=2e-7)      # two fp32 roundings per element at most
+    np.testing.assert_array_equal(got[20:], w[20:])
+
+
+def test_line1_step_writes_in_two_rounds(oracle):
+    """bf16 table: a row that is both a source and a target is rounded after the
+    contributions it gets as target/negative and again after those it gets as source."""
+    import torch
+    w = np.array([[1.0, 0.5], [0.25, -1.0], [2.0, 1.0]], dtype=np.float32)
+    bits = torch.from_numpy(w).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy()
+    s = np.array([0, 1], dtype=np.int32)
+    t = np.array([1, 0], dtype=np.int32)
+    neg = np.zeros((2, 0), dtype=np.int32)
+    lr = 0.3
+    sig = lambda x: 1.0 / (1.0 + np.exp(-x))
+    x = float(w[0] @ w[1])
+    g = sig(x) - 1.0
+    to_bf16 = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float32)).to(torch.bfloat16).to(torch.float32).numpy()
+    lr32 = np.float64(np.float32(lr))
+    # row 0: as target of pair (1, 0): g * w[1]; as source of pair (0, 1): g * w[1]
+    r0 = to_bf16(to_bf16(w[0] - lr32 * g * w[1]) - lr32 * g * w[1])
+    r1 = to_bf16(to_bf16(w[1] - lr32 * g * w[0]) - lr32 * g * w[0])
+    oracle.line1_step(bits, s, t, neg, lr, dtype=oracle.BF16)
+    got = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(got[0], r0)
+    np.testing.assert_array_equal(got[1], r1)
+    np.testing.assert_array_equal(got[2], w[2])
