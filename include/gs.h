@@ -192,8 +192,8 @@ int32_t gs_sample_negatives(const gs_alias* noise, int64_t num_nodes, int64_t nu
  * i, and returns centers_out[i] = the row that holds e, contexts_out[i] =
  * nbrs[e].  In a symmetrised graph both directions of an edge are entries.
  * The batch is then an ordinary gs_sgns_step batch (second-order proximity:
- * source rows in w_in, context rows in w_out) with negatives from
- * gs_sample_negatives.
+ * source rows in w_in, context rows in w_out) or a gs_line1_step batch
+ * (first-order proximity, one table), with negatives from gs_sample_negatives.
  *   centers_out, contexts_out  int32[num_samples] on the device.
  *   Errors: GS_EINVAL for an empty graph (num_entries < 1), offset_bits other
  *   than 32 / 64, or a prob without alias.
@@ -271,6 +271,25 @@ int32_t gs_sgns_step_fused(void* w_in, void* w_out, int64_t num_nodes, int32_t d
                            const gs_alias* noise, uint64_t pair_index_base, uint64_t neg_seed,
                            int32_t k, float lr, double* loss_sum_out, void* ws, size_t ws_bytes,
                            void* stream);
+
+/* --------------------------------------------------------------------------
+ * gs_line1_step -- LINE iteration with first-order proximity (the LINE variant
+ * with one embedding per node; Sec. 2.2 / Sec. 4 cite LINE, Sec. 3.2 gives the
+ * batch shape): one table w on both sides.  For pair i: u = w[sources[i]],
+ * v_0 = w[targets[i]], v_j = w[negs[i][j-1]]; loss and g_j as in gs_sgns_step;
+ * w[sources[i]] gets -lr * sum_j g_j v_j and w[row_j] gets -lr * g_j u, all
+ * from the values before the call.  A row is written as round(old + delta)
+ * once for what it receives as target / negative and then once more for what it
+ * receives as source (two roundings for a row that is both).
+ *   Arguments, limits, id checking and errors as for gs_sgns_step; workspace
+ *   gs_line1_step_workspace_bytes (the step's own plus a copy of one input row
+ *   and 4 bytes per pair).
+ * ------------------------------------------------------------------------ */
+size_t gs_line1_step_workspace_bytes(int64_t num_pairs, int64_t num_nodes, int32_t k, int32_t dim,
+                                     int32_t dtype);
+int32_t gs_line1_step(void* w, int64_t num_nodes, int32_t dim, int32_t dtype, const int32_t* sources,
+                      const int32_t* targets, const int32_t* negs, int64_t num_pairs, int32_t k,
+                      float lr, double* loss_sum_out, void* ws, size_t ws_bytes, void* stream);
 
 /* --------------------------------------------------------------------------
  * gs_sgns_adam_step -- the iteration with Adam kept inside the storage (Sec. 3.2

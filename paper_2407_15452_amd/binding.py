@@ -28,6 +28,7 @@ EXPORTS = (
     "gs_sample_negatives", "gs_sample_edges",
     "gs_sgns_step_workspace_bytes", "gs_sgns_step", "gs_sgns_momentum_step", "gs_sgns_adam_step",
     "gs_sgns_step_fused_workspace_bytes", "gs_sgns_step_fused",
+    "gs_line1_step_workspace_bytes", "gs_line1_step",
     "gs_unique_ids_workspace_bytes", "gs_unique_ids", "gs_get_rows", "gs_put_rows",
 )
 
@@ -412,4 +413,30 @@ def gs_sgns_step_fused(w_in, w_out, centers, contexts, noise, k: int, neg_seed: 
         C.c_int32(k), C.c_float(lr), _dev(loss_out, torch.float64), _dev(ws), C.c_size_t(ws.numel()),
         _stream())
     _check(rc, "gs_sgns_step_fused")
+    return loss_out
+
+
+def gs_line1_step_workspace_bytes(num_pairs: int, num_nodes: int, k: int, dim: int,
+                                  dtype: int = GS_F32) -> int:
+    return int(lib().gs_line1_step_workspace_bytes(C.c_int64(num_pairs), C.c_int64(num_nodes),
+                                                   C.c_int32(k), C.c_int32(dim), C.c_int32(dtype)))
+
+
+def gs_line1_step(w, sources, targets, negs, lr: float, loss_out=None, ws=None):
+    """First-order LINE iteration on the single table w, in place; returns the device loss scalar."""
+    dtype = GS_BF16 if w.dtype == torch.bfloat16 else GS_F32
+    num_nodes, dim = int(w.shape[0]), int(w.shape[1])
+    num_pairs = int(sources.numel())
+    k = int(negs.shape[1]) if negs.dim() == 2 else 0
+    dev = w.device
+    if loss_out is None:
+        loss_out = torch.zeros(1, dtype=torch.float64, device=dev)
+    if ws is None:
+        ws = _workspace(gs_line1_step_workspace_bytes(num_pairs, num_nodes, k, dim, dtype), dev)
+    rc = lib().gs_line1_step(
+        _dev(w), C.c_int64(num_nodes), C.c_int32(dim), C.c_int32(dtype),
+        _dev(sources, torch.int32, "sources"), _dev(targets, torch.int32, "targets"),
+        _dev(negs, torch.int32, "negs"), C.c_int64(num_pairs), C.c_int32(k), C.c_float(lr),
+        _dev(loss_out, torch.float64), _dev(ws), C.c_size_t(ws.numel()), _stream())
+    _check(rc, "gs_line1_step")
     return loss_out

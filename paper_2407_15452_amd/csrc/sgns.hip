@@ -55,7 +55,7 @@ typedef uint16_t bf16_t;           // bfloat16 storage
 
 struct Term {      // one (pair, j) contribution to a context-table row
   int32_t row;
-  int32_t center;
+  int32_t center;  // row of the input table (one-table mode: slot of its copy in `snap`)
   float coef;      // -lr * g
   uint32_t where;  // low 16 bits: number of terms of this row, high 16: position of this
                    // term among them; both saturate at 65535 (exact for rows <= kLongRow)
@@ -79,6 +79,12 @@ struct SgnsArgs {
   uint64_t neg_seed;
   uint64_t neg_pair_base;
   int32_t* negs_draw;
+  // one table on both sides (first-order LINE; else null): the update kernel writes rows of
+  // the table while input rows are still needed, so the forward kernel keeps a copy of every
+  // input row it loads (one per run of equal centres, at the run's staging slot) and notes
+  // the slot of every pair; the update kernel reads the copies
+  void* snap;               // [num_pairs][dim], storage type of the table
+  int32_t* pair_slot;       // [num_pairs]
   const int32_t* centers;
   const int32_t* contexts;
   const int32_t* negs;
@@ -267,6 +273,29 @@ __device__ __forceinline__ void load_raw(const bf16_t* __restrict__ table, int64
   }
 }
 
+template <int VPL>
+__device__ __forceinline__ void store_raw(float* __restrict__ table, int64_t row, int dim, int l16,
+                                          const RawRow<float, VPL>& x) {
+  float4* p = reinterpret_cast<float4*>(table + row * (int64_t)dim);
+  const int dim4 = dim >> 2;
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    const int q = v * kGroupLanes + l16;
+    if (q < dim4) p[q] = x.r[v];
+  }
+}
+template <int VPL>
+__device__ __forceinline__ void store_raw(bf16_t* __restrict__ table, int64_t row, int dim, int l16,
+                                          const RawRow<bf16_t, VPL>& x) {
+  uint4* p = reinterpret_cast<uint4*>(table + row * (int64_t)dim);
+  const int chunks = dim >> 3;
+#pragma unroll
+  for (int w = 0; w < VPL / 2; ++w) {
+    const int c = w * kGroupLanes + l16;
+    if (c < chunks) p[c] = x.r[w];
+  }
+}
+
 // Between two uses of a raw bf16 row: makes the compiler widen it again at the
 // second use instead of keeping the widened copy (twice the registers) alive.
 template <int VPL>
@@ -418,9 +447,15 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
     if (c != cur_c) {
       if (cur_c >= 0) stage_flush<T, VPL>(a, first + flushes++, cur_c, l16, du);
       load_row<VPL>(w_in, c, a.dim, l16, u);
+      if (a.snap != nullptr) {              // one-table mode: keep the row as it is now
+        RawRow<T, VPL> keep;
+        load_raw<VPL>(w_in, c, a.dim, l16, keep);
+        store_raw<VPL>(static_cast<T*>(a.snap), first + flushes, a.dim, l16, keep);
+      }
       zero<VPL>(du);
       cur_c = c;
     }
+    if (a.snap != nullptr && l16 == 0) a.pair_slot[first + p] = (int32_t)(first + flushes);
     const int64_t e0 = (first + p) * (int64_t)K1;
     const int32_t* prow = rows_s + p * K1;
     for (int j0 = 0; j0 <= K; j0 += RB) {
@@ -605,7 +640,7 @@ __global__ __launch_bounds__(256) void sgns_place_kernel(SgnsArgs a) {
   const uint32_t rk = a.rank[e];
   Term t;
   t.row = row;
-  t.center = checked_row(a, a.centers[i]);
+  t.center = (a.pair_slot != nullptr) ? a.pair_slot[i] : checked_row(a, a.centers[i]);
   t.coef = -a.lr * a.g[e];
   t.where = min(len, 65535u) | (min(rk, 65535u) << 16);
   a.sorted[begin + rk] = t;
@@ -620,7 +655,8 @@ __global__ __launch_bounds__(256) void sgns_place_kernel(SgnsArgs a) {
 template <typename T, int VPL, int UB, bool kSq>
 __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
   static_assert(!kSq || std::is_same<T, float>::value, "second-moment tables are fp32");
-  const T* __restrict__ w_in = static_cast<const T*>(a.w_in);
+  // input rows: the table, or the copies the forward kernel kept (one-table mode)
+  const T* __restrict__ w_in = static_cast<const T*>(a.snap != nullptr ? a.snap : a.w_in);
   T* w_out = static_cast<T*>(a.dst_out);   // destination rows (old value and result)
   const int l16 = threadIdx.x & (kGroupLanes - 1);
   const int64_t group = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
@@ -1046,7 +1082,7 @@ __global__ __launch_bounds__(256) void adam_apply_kernel(float4* __restrict__ w,
 static int32_t check_sgns_args(const void* w_in, const void* w_out, int64_t num_nodes, int32_t dim,
                                int32_t dtype, const int32_t* centers, const int32_t* contexts,
                                const int32_t* negs, int64_t num_pairs, int32_t k,
-                               const double* loss_sum_out, const void* ws) {
+                               const double* loss_sum_out, const void* ws, bool one_table = false) {
   if (!w_in || !w_out || num_nodes < 1 || num_nodes > (int64_t)INT32_MAX) return GS_EINVAL;
   if (dtype != GS_F32 && dtype != GS_BF16) return GS_EINVAL;
   const int granule = (dtype == GS_BF16) ? 8 : 4;   // elements per 16-byte piece
@@ -1055,7 +1091,7 @@ static int32_t check_sgns_args(const void* w_in, const void* w_out, int64_t num_
   if (num_pairs > 0 && (!centers || !contexts || (k > 0 && !negs))) return GS_EINVAL;
   if (num_pairs * (int64_t)(k + 1) > (int64_t)0x7fffffff) return GS_EOVERFLOW;
   if (!aligned(w_in, 16) || !aligned(w_out, 16)) return GS_EINVAL;
-  if (w_in == w_out) return GS_EINVAL;   // context rows are written while input rows are still read
+  if (w_in == w_out && !one_table) return GS_EINVAL;   // needs the one-table entry point
   if (!ws || !aligned(ws, 256)) return GS_EINVAL;
   return GS_OK;
 }
@@ -1068,6 +1104,8 @@ struct SgnsExtras {
   const gs_alias* noise = nullptr; // negatives drawn inside the step (negs_draw != null)
   uint64_t neg_seed = 0, neg_pair_base = 0;
   int32_t* negs_draw = nullptr;
+  void* snap = nullptr;            // one table on both sides: copies of the input rows, pair slots
+  int32_t* pair_slot = nullptr;
 };
 
 // Logits from (w_in, w_out); every touched row r of the destination tables becomes
@@ -1091,6 +1129,8 @@ static int32_t run_sgns(void* w_in, void* w_out, void* dst_in, void* dst_out, in
   a.neg_pair_base = x.neg_pair_base;
   a.negs_draw = x.negs_draw;
   if (a.draw_negs) negs = x.negs_draw;
+  a.snap = x.snap;
+  a.pair_slot = x.pair_slot;
   a.w_in = w_in;
   a.w_out = w_out;
   a.dst_in = dst_in;
@@ -1202,6 +1242,44 @@ extern "C" int32_t gs_sgns_step_fused(void* w_in, void* w_out, int64_t num_nodes
   x.negs_draw = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + p.bytes);
   return run_sgns(w_in, w_out, w_in, w_out, num_nodes, dim, dtype, centers, contexts, nullptr,
                   num_pairs, k, lr, loss_sum_out, p, stream, x);
+}
+
+// workspace of the one-table step: the step's own, the copies of the input rows, the pair slots
+static size_t line1_snap_bytes(int64_t num_pairs, int32_t dim, int32_t dtype) {
+  return align_up((size_t)(num_pairs > 0 ? num_pairs : 1) * (size_t)dim * (dtype == GS_BF16 ? 2 : 4));
+}
+static size_t line1_slot_bytes(int64_t num_pairs) {
+  return align_up((size_t)(num_pairs > 0 ? num_pairs : 1) * sizeof(int32_t));
+}
+
+extern "C" size_t gs_line1_step_workspace_bytes(int64_t num_pairs, int64_t num_nodes, int32_t k,
+                                                int32_t dim, int32_t dtype) {
+  if (num_pairs < 0 || num_nodes < 0 || k < 0 || dim < 1) return 0;
+  return plan_sgns(nullptr, num_pairs, num_nodes, k, dim).bytes +
+         line1_snap_bytes(num_pairs, dim, dtype) + line1_slot_bytes(num_pairs);
+}
+
+extern "C" int32_t gs_line1_step(void* w, int64_t num_nodes, int32_t dim, int32_t dtype,
+                                 const int32_t* sources, const int32_t* targets, const int32_t* negs,
+                                 int64_t num_pairs, int32_t k, float lr, double* loss_sum_out,
+                                 void* ws, size_t ws_bytes, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  const int32_t bad = check_sgns_args(w, w, num_nodes, dim, dtype, sources, targets, negs, num_pairs,
+                                      k, loss_sum_out, ws, true);
+  if (bad != GS_OK) return bad;
+  SgnsPlan p = plan_sgns(ws, num_pairs, num_nodes, k, dim);
+  const size_t snap_bytes = line1_snap_bytes(num_pairs, dim, dtype);
+  if (ws_bytes < p.bytes + snap_bytes + line1_slot_bytes(num_pairs)) return GS_EWORKSPACE;
+  if (num_pairs == 0) {
+    zero_double_kernel<<<1, 1, 0, stream>>>(loss_sum_out);
+    GS_LAUNCH_CHECK();
+    return GS_OK;
+  }
+  SgnsExtras x;
+  x.snap = static_cast<char*>(ws) + p.bytes;
+  x.pair_slot = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + p.bytes + snap_bytes);
+  return run_sgns(w, w, w, w, num_nodes, dim, dtype, sources, targets, negs, num_pairs, k, lr,
+                  loss_sum_out, p, stream, x);
 }
 
 extern "C" int32_t gs_sgns_momentum_step(void* w_in, void* w_out, void* m_in, void* m_out,

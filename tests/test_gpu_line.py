@@ -135,3 +135,76 @@ def test_line_batches_workload0(gs, oracle, graph0):
         assert np.abs(d_in.cpu().numpy() - h_in).max() <= EMB_ATOL * (it + 1)
         assert np.abs(d_out.cpu().numpy() - h_out).max() <= EMB_ATOL * (it + 1)
     assert last < first          # the objective goes down
+
+
+def _bf16_bits(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("dim,k,b,dtype", [(128, 5, 50_001, "f32"), (64, 3, 7_777, "f32"),
+                                           (8, 0, 300, "f32"), (256, 10, 9_999, "bf16")])
+def test_line1_step(gs, oracle, dim, k, b, dtype):
+    """First-order LINE (one table on both sides): two consecutive iterations on batches in which
+    sources also appear as targets and negatives (the reads must still see the old rows)."""
+    from paper_2407_15452_amd import inputs
+    n = 3000
+    table = inputs.random_tables(n, dim, seed=dim + k, scale=2.0 / dim ** 0.5)[0]
+    rng = np.random.default_rng(b)
+    if dtype == "bf16":
+        d_w = table.to(torch.bfloat16).to(DEV)
+        h_w = _bf16_bits(d_w).copy()
+        code = oracle.BF16
+    else:
+        d_w = table.to(DEV)
+        h_w = table.numpy().copy()
+        code = oracle.F32
+    for it in range(2):
+        s = (n * rng.random(b) ** 2).astype(np.int32)                 # hubs are sources often
+        t = rng.integers(0, n, b).astype(np.int32)
+        t[::7] = s[::7]                                               # self pairs
+        neg = (n * rng.random((b, k)) ** 3).astype(np.int32)
+        want = oracle.line1_step(h_w, s, t, neg, 0.01, dtype=code)
+        loss = gs.gs_line1_step(d_w, _t(s), _t(t), _t(neg), 0.01)
+        torch.cuda.synchronize()
+        assert abs(float(loss.item()) - want) <= LOSS_RTOL * abs(want)
+        if dtype == "bf16":
+            f32 = lambda bits: (bits.astype(np.uint32) << 16).view(np.float32)  # noqa: E731
+            got = _bf16_bits(d_w)
+            # two roundings per element: a flip in the first moves the second by one step
+            near = np.abs(got.astype(np.int32) - h_w.astype(np.int32)) <= 2
+            assert (near | (np.abs(f32(got) - f32(h_w)) <= EMB_ATOL)).all()
+            assert (got != h_w).mean() <= 2e-3
+            d_w.copy_(torch.from_numpy(h_w.view(np.int16)).view(torch.bfloat16))
+        else:
+            assert np.abs(d_w.cpu().numpy() - h_w).max() <= EMB_ATOL
+
+
+def test_line1_training_on_workload0(gs, oracle, graph0):
+    """Ten first-order LINE iterations on sampled edges of workload 0, checked step by step."""
+    from paper_2407_15452_amd import inputs
+    wl, (off, nb), g = graph0
+    n, d, K, B = wl.num_nodes, wl.dim, 5, 16_384
+    table = inputs.random_tables(n, d, 21, 0.3)[0]
+    h_w, d_w = table.numpy().copy(), table.to(DEV)
+    first = last = None
+    for it in range(10):
+        c, o = gs.gs_sample_edges(g, None, B, seed=41, sample_index_base=it * B)
+        neg = gs.gs_sample_negatives(None, n, B, K, seed=42, pair_index_base=it * B, device=DEV)
+        loss = gs.gs_line1_step(d_w, c, o, neg, 0.025)
+        want = oracle.line1_step(h_w, c.cpu().numpy(), o.cpu().numpy(), neg.cpu().numpy(), 0.025)
+        assert abs(float(loss.item()) - want) <= LOSS_RTOL * abs(want)
+        assert np.abs(d_w.cpu().numpy() - h_w).max() <= EMB_ATOL * (it + 1)
+        first = want if first is None else first
+        last = want
+    assert last < first
+
+
+def test_line1_step_argument_errors(gs):
+    w = torch.zeros((10, 8), dtype=torch.float32, device=DEV)
+    i = torch.zeros(4, dtype=torch.int32, device=DEV)
+    n = torch.zeros((4, 2), dtype=torch.int32, device=DEV)
+    small = torch.empty(256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(gs.GsError):
+        gs.gs_line1_step(w, i, i, n, 0.1, ws=small)
+    bad = i.clone(); bad[1] = 10
+    assert np.isnan(float(gs.gs_line1_step(w, bad, i, n, 0.1).item()))
