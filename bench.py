@@ -331,6 +331,31 @@ def main():
             line_ms = e0.elapsed_time(e1) / 5
             line = {"ms_per_batch": line_ms, "edges_per_s": B / (line_ms * 1e-3),
                     "what": "gs_sample_edges + gs_sample_negatives + gs_sgns_step per batch of B edges"}
+            # first order: the same batches on one table (a throw-away copy)
+            if wl.num_nodes * wl.dim * elem_bytes <= 16e9:
+                w_one = w_in.clone()
+                l1_ws = torch.empty(gs.gs_line1_step_workspace_bytes(B, wl.num_nodes, k, wl.dim,
+                                                                     sgns_dtype),
+                                    dtype=torch.uint8, device=dev)
+
+                def line1_batch(it):
+                    gs.gs_sample_edges(g, None, B, wl.walk_seed ^ 0x4c494e45, sample_index_base=it * B,
+                                       centers_out=lc, contexts_out=lo_)
+                    gs.gs_sample_negatives(noise, wl.num_nodes, B, k, wl.neg_seed ^ 0x4c494e45,
+                                           pair_index_base=it * B, out=negs)
+                    gs.gs_line1_step(w_one, lc, lo_, negs, lr, loss_out=losses[:1], ws=l1_ws)
+
+                for it in range(2):
+                    line1_batch(it)
+                torch.cuda.synchronize()
+                e0, e1 = ev(), ev()
+                e0.record()
+                for it in range(2, 7):
+                    line1_batch(it)
+                e1.record()
+                torch.cuda.synchronize()
+                line["first_order_ms_per_batch"] = e0.elapsed_time(e1) / 5
+                del w_one, l1_ws
             del lc, lo_
 
         # ------------------------------------------------------------------ get / put of a batch (extra)
