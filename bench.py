@@ -45,10 +45,15 @@ def measured_traffic(workload_name: str):
     """HBM bytes per gs_sgns_step call from the committed rocprofv3 counter runs,
     or None when there is none for this workload or the kernels have changed
     since the counters were taken."""
+    rec = traffic_record(workload_name)
+    return rec["hbm_bytes_per_call"] if rec else None
+
+
+def traffic_record(workload_name: str):
     try:
         rec = json.load(open(TRAFFIC_FILE))[workload_name]
         sha = hashlib.sha256(open(SGNS_SOURCE, "rb").read()).hexdigest()
-        return rec["hbm_bytes_per_call"] if rec["sgns_hip_sha256"] == sha else None
+        return rec if rec["sgns_hip_sha256"] == sha else None
     except (OSError, KeyError, ValueError):
         return None
 
@@ -418,6 +423,14 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "bytes_per_pair": bpp,
                      "traffic": measured_traffic(wl.name)},
     }
+    rec = traffic_record(wl.name)
+    if rec:
+        # counter-measured bytes of one call over the step time measured here: the HBM rate the
+        # step actually sustains, as a fraction of the peak, and the L2 hit rate of its kernels
+        rate = rec["hbm_bytes_per_call"] / (sgns_ms * 1e-3) / 1e9
+        result["roofline"]["traffic_GBps"] = rate
+        result["roofline"]["traffic_frac"] = rate / HBM_PEAK_GBS
+        result["roofline"]["l2_hit_rate"] = rec.get("l2_hit_rate")
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, g, row_alias, noise, w_in, w_out, lr)
