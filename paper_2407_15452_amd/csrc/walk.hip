@@ -80,6 +80,8 @@ __global__ __launch_bounds__(kWalkThreads) void walk_kernel(WalkArgs a) {
             j = alias_pick(a, lo + j, j, b.x2);
           }
           next = nbrs[lo + j];
+          // a neighbour id that is not a node (a CSR not built by gs_csr_build) ends the walk
+          if ((uint32_t)next >= (uint32_t)a.num_nodes) next = -1;
         }
       }
       cur = next;
@@ -226,6 +228,8 @@ __global__ __launch_bounds__(kWalkThreads) void node2vec_kernel(WalkArgs a) {
         break;
       case kDraw:
         x = v;
+        // a neighbour id that is not a node (a CSR not built by gs_csr_build) ends the walk
+        if ((uint32_t)x >= (uint32_t)a.num_nodes) { commit(-1); break; }
         if (t == 0 || att == kMaxAttempts - 1) { commit(x); break; }   // unbiased first step; last attempt is taken
         // accept iff s < bias(x).  For x != prev the bias is 1 or 1/q, so the
         // membership search is only needed when s falls between the two.

@@ -862,3 +862,21 @@ def test_sgns_step_reports_ids_that_are_not_rows(gs):
     assert np.isfinite(float(loss.item()))
     with pytest.raises(gs.GsError):            # one table on both sides
         gs.gs_sgns_step(w_in, w_in, _t(c), _t(o), _t(neg), 0.01, ws=ws)
+
+
+def test_walks_stop_at_neighbour_ids_that_are_not_nodes(gs):
+    """A hand-made CSR with entries outside [0, num_nodes): the walkers end the walk there
+    (-1 from then on) instead of reading past the offsets."""
+    n = 6
+    off = torch.tensor([0, 2, 3, 4, 4, 5, 6], dtype=torch.int32, device=DEV)
+    nb = torch.tensor([1, 2, 6, 0, 1_000_000, -7], dtype=torch.int32, device=DEV)   # rows 1, 4, 5 are bad
+    g = gs.Csr(off, nb)
+    starts = torch.arange(n, dtype=torch.int32, device=DEV).repeat(50)
+    for walks in (gs.gs_random_walk(g, None, starts, 12, seed=3),
+                  gs.gs_node2vec_walk(g, None, starts, 12, 0.5, 2.0, seed=3)):
+        w = walks.cpu().numpy()
+        assert ((w >= -1) & (w < n)).all()
+        assert (w[:, 0] == starts.cpu().numpy()).all()
+        dead = w == -1
+        assert (dead[:, 1:] >= dead[:, :-1]).all()             # -1 only as a suffix
+        assert (w[starts.cpu().numpy() == 1][:, 1] == -1).all()
