@@ -29,6 +29,13 @@
 // A row is handled by 16 lanes holding 16-byte pieces (256 contiguous bytes per
 // load instruction); a wave works on four rows at once and a dot product is a
 // 16-lane DPP reduction.  No matrix cores: 0.3 flop per byte moved.
+//
+// The other entry points of this file run the same kernels with a few switches
+// (SgnsArgs / SgnsExtras): the momentum and Adam steps write the row sums into
+// the optimizer's tables between dense passes over whole tables; the fused step
+// draws the negatives in the forward kernel; the one-table step (first-order
+// LINE) reads the input rows in the update kernel from copies the forward kernel
+// kept, because that kernel then writes rows of the table it would read.
 #include <cmath>
 #include <type_traits>
 
