@@ -173,3 +173,31 @@ def test_line1_step_writes_in_two_rounds(oracle):
     np.testing.assert_array_equal(got[0], r0)
     np.testing.assert_array_equal(got[1], r1)
     np.testing.assert_array_equal(got[2], w[2])
+
+
+def test_line1_round_order_target_part_first(oracle):
+    """Row 0 is the source of pair (0, 1) and the target of pair (2, 0): it is rounded after
+    its target part and again after its source part.  Recomputed by hand with torch's bf16
+    rounding; the values are chosen so that the opposite order gives another result."""
+    import torch
+    rng = np.random.default_rng(12)
+    to_bf16 = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float32)).to(torch.bfloat16).to(torch.float32).numpy()
+    sig = lambda x: 1.0 / (1.0 + np.exp(-x))
+    for trial in range(50):
+        w = to_bf16(rng.normal(0, 1.0, (3, 4))).astype(np.float64)
+        lr = np.float64(np.float32(0.37))
+        g1 = sig(w[0] @ w[1]) - 1.0          # pair (0, 1)
+        g2 = sig(w[2] @ w[0]) - 1.0          # pair (2, 0)
+        as_target = g2 * w[2]
+        as_source = g1 * w[1]
+        right = to_bf16(to_bf16(w[0] - lr * as_target).astype(np.float64) - lr * as_source)
+        wrong = to_bf16(to_bf16(w[0] - lr * as_source).astype(np.float64) - lr * as_target)
+        if not np.array_equal(right, wrong):
+            break
+    else:
+        raise AssertionError("no discriminating case found")
+    bits = torch.from_numpy(w.astype(np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy()
+    oracle.line1_step(bits, np.array([0, 2], dtype=np.int32), np.array([1, 0], dtype=np.int32),
+                      np.zeros((2, 0), dtype=np.int32), 0.37, dtype=oracle.BF16)
+    got = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(got[0], right)
