@@ -48,7 +48,8 @@ def _load():
         for name in ("oracle_csr_build", "oracle_alias_build", "oracle_random_walk",
                      "oracle_node2vec_walk", "oracle_make_pairs", "oracle_sample_negatives",
                      "oracle_sgns_step", "oracle_sgns_momentum_step", "oracle_sample_edges", "oracle_unique_ids", "oracle_get_rows",
-                     "oracle_put_rows", "oracle_sgns_adam_step", "oracle_line1_step"):
+                     "oracle_put_rows", "oracle_sgns_adam_step", "oracle_line1_step", "oracle_table_mult",
+                     "oracle_table_mult_add"):
             getattr(_lib, name).restype = C.c_int32
         _lib.oracle_philox4x32_10.restype = None
     return _lib
@@ -308,3 +309,22 @@ def line1_step(w, sources, targets, negs, lr, dtype=F32):
                                    C.c_int64(num_pairs), C.c_int32(k), C.c_float(lr), C.byref(loss))
     _check(rc, "oracle_line1_step")
     return loss.value
+
+
+def table_mult(table, factor, dtype=F32):
+    """table *= factor in place (one rounding per element)."""
+    want = np.float32 if dtype == F32 else np.uint16
+    assert table.dtype == want and table.flags.c_contiguous
+    rc = _load().oracle_table_mult(_ptr(table), C.c_int64(table.shape[0]), C.c_int32(table.shape[1]),
+                                   C.c_int32(dtype), C.c_float(factor))
+    _check(rc, "oracle_table_mult")
+
+
+def table_mult_add(dst, src, factor, dtype=F32):
+    """dst += factor * src in place (one rounding per element)."""
+    want = np.float32 if dtype == F32 else np.uint16
+    assert dst.dtype == want and src.dtype == want and dst.shape == src.shape
+    assert dst.flags.c_contiguous and src.flags.c_contiguous
+    rc = _load().oracle_table_mult_add(_ptr(dst), _ptr(src), C.c_int64(dst.shape[0]),
+                                       C.c_int32(dst.shape[1]), C.c_int32(dtype), C.c_float(factor))
+    _check(rc, "oracle_table_mult_add")

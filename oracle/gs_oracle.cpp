@@ -723,4 +723,28 @@ int32_t oracle_put_rows(void* table, int64_t num_nodes, int32_t dim, int32_t dty
   return ORACLE_OK;
 }
 
+
+// The two dense storage operations of §3.2 (model update for SGD with momentum):
+// mult: every element of a table times a factor; mult_add: dst <- dst + factor * src
+// for two tables of the same shape.  One rounding per element.
+int32_t oracle_table_mult(void* table, int64_t num_nodes, int32_t dim, int32_t dtype, float factor) {
+  if (!table || num_nodes < 1 || dim < 1) return ORACLE_EINVAL;
+  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_EINVAL;
+  for (int64_t r = 0; r < num_nodes; ++r)
+    for (int32_t e = 0; e < dim; ++e)
+      write_elem(table, dtype, dim, r, e, (double)factor * read_elem(table, dtype, dim, r, e));
+  return ORACLE_OK;
+}
+
+int32_t oracle_table_mult_add(void* dst, const void* src, int64_t num_nodes, int32_t dim,
+                              int32_t dtype, float factor) {
+  if (!dst || !src || num_nodes < 1 || dim < 1) return ORACLE_EINVAL;
+  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_EINVAL;
+  for (int64_t r = 0; r < num_nodes; ++r)
+    for (int32_t e = 0; e < dim; ++e)
+      write_elem(dst, dtype, dim, r, e,
+                 read_elem(dst, dtype, dim, r, e) + (double)factor * read_elem(src, dtype, dim, r, e));
+  return ORACLE_OK;
+}
+
 }  // extern "C"

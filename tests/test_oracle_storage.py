@@ -106,3 +106,48 @@ def test_unique_get_put_give_the_sparse_sgd_step(oracle):
     oracle.put_rows(got_out, u, new_out.astype(np.float64) - blk_out, 1.0)
     np.testing.assert_allclose(got_in, full_in, atol=1e-6)
     np.testing.assert_allclose(got_out, full_out, atol=1e-6)
+
+
+def test_dense_mult_and_mult_add(oracle):
+    rng = np.random.default_rng(5)
+    a = rng.normal(size=(7, 5)).astype(np.float32)
+    b = rng.normal(size=(7, 5)).astype(np.float32)
+    got = a.copy()
+    oracle.table_mult(got, 0.9)
+    np.testing.assert_array_equal(got, (a.astype(np.float64) * np.float64(np.float32(0.9))).astype(np.float32))
+    got = a.copy()
+    oracle.table_mult_add(got, b, -0.05)
+    want = a.astype(np.float64) + np.float64(np.float32(-0.05)) * b.astype(np.float64)
+    np.testing.assert_array_equal(got, want.astype(np.float32))
+    ba, bb = _bf16_bits(a), _bf16_bits(b)
+    got = ba.copy()
+    oracle.table_mult_add(got, bb, 0.5, dtype=oracle.BF16)
+    want = _bf16_vals(ba).astype(np.float64) + 0.5 * _bf16_vals(bb).astype(np.float64)
+    np.testing.assert_array_equal(got, _bf16_bits(want.astype(np.float32)))
+
+
+def test_momentum_step_is_mult_put_mult_add(oracle):
+    """The paper's model update composed from the storage operations: mult on the momentum,
+    put of the batch's gradient rows, mult_add onto the model, equals the momentum step."""
+    rng = np.random.default_rng(6)
+    n, d, b, k, lr, mu = 40, 6, 50, 3, 0.05, 0.9
+    w_in = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    w_out = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    m_in = rng.normal(0, 0.1, (n, d)).astype(np.float32)
+    m_out = rng.normal(0, 0.1, (n, d)).astype(np.float32)
+    c = rng.integers(0, n, b).astype(np.int32)
+    o = rng.integers(0, n, b).astype(np.int32)
+    neg = rng.integers(0, n, (b, k)).astype(np.int32)
+    want = [t.copy() for t in (w_in, w_out, m_in, m_out)]
+    oracle.sgns_momentum_step(*want, c, o, neg, lr, mu)
+    # gradient rows from a plain step with lr = 1: old - new
+    s_in, s_out = w_in.copy(), w_out.copy()
+    oracle.sgns_step(s_in, s_out, c, o, neg, 1.0)
+    got = [t.copy() for t in (w_in, w_out, m_in, m_out)]
+    for model, moment, stepped, before in ((got[0], got[2], s_in, w_in), (got[1], got[3], s_out, w_out)):
+        oracle.table_mult(moment, mu)
+        rows, _ = oracle.unique_ids(np.nonzero((stepped != before).any(1))[0].astype(np.int32), n)
+        oracle.put_rows(moment, rows, before[rows].astype(np.float64) - stepped[rows], 1.0)
+        oracle.table_mult_add(model, moment, -lr)
+    for g, w in zip(got, want):
+        np.testing.assert_allclose(g, w, atol=1e-6)
