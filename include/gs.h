@@ -349,6 +349,20 @@ int32_t gs_put_rows(void* table, int64_t num_nodes, int32_t dim, int32_t dtype, 
                     int64_t n, const int64_t* count_dev, const float* rows, float scale,
                     void* stream);
 
+/* --------------------------------------------------------------------------
+ * gs_table_mult, gs_table_mult_add -- the two dense storage operations of Sec.
+ * 3.2 (model update for SGD with momentum): every element of a table times a
+ * factor (the momentum table times the momentum value), and dst <- dst +
+ * factor * src for two tables of the same shape (the model minus the learning
+ * rate times the momentum).  One rounding per element (bf16: through fp32,
+ * nearest even).  Tables [num_nodes][dim], GS_F32 | GS_BF16, 16-byte aligned;
+ * dim a multiple of 4 (fp32) or 8 (bf16); dst != src.
+ * ------------------------------------------------------------------------ */
+int32_t gs_table_mult(void* table, int64_t num_nodes, int32_t dim, int32_t dtype, float factor,
+                      void* stream);
+int32_t gs_table_mult_add(void* dst, const void* src, int64_t num_nodes, int32_t dim, int32_t dtype,
+                          float factor, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -30,6 +30,7 @@ EXPORTS = (
     "gs_sgns_step_fused_workspace_bytes", "gs_sgns_step_fused",
     "gs_line1_step_workspace_bytes", "gs_line1_step",
     "gs_unique_ids_workspace_bytes", "gs_unique_ids", "gs_get_rows", "gs_put_rows",
+    "gs_table_mult", "gs_table_mult_add",
 )
 
 
@@ -440,3 +441,20 @@ def gs_line1_step(w, sources, targets, negs, lr: float, loss_out=None, ws=None):
         _dev(loss_out, torch.float64), _dev(ws), C.c_size_t(ws.numel()), _stream())
     _check(rc, "gs_line1_step")
     return loss_out
+
+
+def gs_table_mult(table, factor: float):
+    """table *= factor in place, every row."""
+    rc = lib().gs_table_mult(_dev(table), C.c_int64(table.shape[0]), C.c_int32(table.shape[1]),
+                             C.c_int32(_table_dtype(table)), C.c_float(factor), _stream())
+    _check(rc, "gs_table_mult")
+
+
+def gs_table_mult_add(dst, src, factor: float):
+    """dst += factor * src in place, every row (two tables of the same shape and dtype)."""
+    if dst.shape != src.shape or dst.dtype != src.dtype:
+        raise TypeError("gs_table_mult_add needs two tables of the same shape and dtype")
+    rc = lib().gs_table_mult_add(_dev(dst), _dev(src), C.c_int64(dst.shape[0]),
+                                 C.c_int32(dst.shape[1]), C.c_int32(_table_dtype(dst)),
+                                 C.c_float(factor), _stream())
+    _check(rc, "gs_table_mult_add")

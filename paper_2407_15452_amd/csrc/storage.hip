@@ -1,6 +1,8 @@
 // Storage operations on a batch of vertex ids (GraphScale Sec. 3.1 / 3.2): merge
 // equal ids into one request (gs_unique_ids), fetch one n x d block of rows
 // (gs_get_rows), add one block of gradient rows to the table (gs_put_rows).
+// And the two dense operations of the model update of Sec. 3.2: a table times a
+// factor (gs_table_mult), one table plus a factor times another (gs_table_mult_add).
 #include "common.h"
 
 namespace gs {
@@ -132,6 +134,65 @@ __global__ __launch_bounds__(kRowThreads) void put_rows_bf16_kernel(
   }
 }
 
+// ---- dense operations over a whole table: 16 bytes per lane, grid-stride ----------------
+__global__ __launch_bounds__(256) void table_mult_f32_kernel(float4* __restrict__ t, int64_t n4,
+                                                             float factor) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    float4 x = t[i];
+    x.x *= factor; x.y *= factor; x.z *= factor; x.w *= factor;    // one exact product, rounded once
+    t[i] = x;
+  }
+}
+__global__ __launch_bounds__(256) void table_mult_bf16_kernel(uint4* __restrict__ t, int64_t n8,
+                                                              float factor) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    uint4 x = t[i];
+    x.x = round_bf16(widen_lo(x.x) * factor) | (round_bf16(widen_hi(x.x) * factor) << 16);
+    x.y = round_bf16(widen_lo(x.y) * factor) | (round_bf16(widen_hi(x.y) * factor) << 16);
+    x.z = round_bf16(widen_lo(x.z) * factor) | (round_bf16(widen_hi(x.z) * factor) << 16);
+    x.w = round_bf16(widen_lo(x.w) * factor) | (round_bf16(widen_hi(x.w) * factor) << 16);
+    t[i] = x;
+  }
+}
+__global__ __launch_bounds__(256) void table_mult_add_f32_kernel(float4* __restrict__ dst,
+                                                                 const float4* __restrict__ src,
+                                                                 int64_t n4, float factor) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const float4 o = dst[i], r = src[i];
+    dst[i] = make_float4(sum_once(o.x, factor, r.x), sum_once(o.y, factor, r.y),
+                         sum_once(o.z, factor, r.z), sum_once(o.w, factor, r.w));
+  }
+}
+__device__ __forceinline__ uint32_t mult_add_pair(uint32_t o, uint32_t r, float factor) {
+  return round_bf16(sum_once(widen_lo(o), factor, widen_lo(r))) |
+         (round_bf16(sum_once(widen_hi(o), factor, widen_hi(r))) << 16);
+}
+__global__ __launch_bounds__(256) void table_mult_add_bf16_kernel(uint4* __restrict__ dst,
+                                                                  const uint4* __restrict__ src,
+                                                                  int64_t n8, float factor) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const uint4 o = dst[i], r = src[i];
+    uint4 x;
+    x.x = mult_add_pair(o.x, r.x, factor);
+    x.y = mult_add_pair(o.y, r.y, factor);
+    x.z = mult_add_pair(o.z, r.z, factor);
+    x.w = mult_add_pair(o.w, r.w, factor);
+    dst[i] = x;
+  }
+}
+
+int32_t check_table_args(const void* table, int64_t num_nodes, int32_t dim, int32_t dtype) {
+  if (!table || num_nodes < 1 || num_nodes > (int64_t)INT32_MAX) return GS_EINVAL;
+  if (dtype != GS_F32 && dtype != GS_BF16) return GS_EINVAL;
+  if (dim < 1 || dim % (dtype == GS_BF16 ? 8 : 4) != 0) return GS_EINVAL;
+  if (!aligned(table, 16)) return GS_EINVAL;
+  return GS_OK;
+}
+
 struct UniquePlan {
   uint64_t *keys, *keys_alt;
   uint32_t *index, *index_alt;
@@ -246,6 +307,41 @@ extern "C" int32_t gs_put_rows(void* table, int64_t num_nodes, int32_t dim, int3
   else
     put_rows_bf16_kernel<<<blocks, kRowThreads, 0, stream>>>(static_cast<uint16_t*>(table), num_nodes,
                                                              dim, ids, n, count_dev, rows, scale);
+  GS_LAUNCH_CHECK();
+  return GS_OK;
+}
+
+extern "C" int32_t gs_table_mult(void* table, int64_t num_nodes, int32_t dim, int32_t dtype,
+                                 float factor, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  const int32_t rc = check_table_args(table, num_nodes, dim, dtype);
+  if (rc != GS_OK) return rc;
+  const int64_t pieces = num_nodes * (int64_t)dim / (dtype == GS_BF16 ? 8 : 4);
+  const unsigned blocks = (unsigned)min((int64_t)(256 * 64), ceil_div(pieces, 256));
+  if (dtype == GS_F32)
+    table_mult_f32_kernel<<<blocks, 256, 0, stream>>>(static_cast<float4*>(table), pieces, factor);
+  else
+    table_mult_bf16_kernel<<<blocks, 256, 0, stream>>>(static_cast<uint4*>(table), pieces, factor);
+  GS_LAUNCH_CHECK();
+  return GS_OK;
+}
+
+extern "C" int32_t gs_table_mult_add(void* dst, const void* src, int64_t num_nodes, int32_t dim,
+                                     int32_t dtype, float factor, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  int32_t rc = check_table_args(dst, num_nodes, dim, dtype);
+  if (rc != GS_OK) return rc;
+  rc = check_table_args(src, num_nodes, dim, dtype);
+  if (rc != GS_OK) return rc;
+  if (dst == src) return GS_EINVAL;
+  const int64_t pieces = num_nodes * (int64_t)dim / (dtype == GS_BF16 ? 8 : 4);
+  const unsigned blocks = (unsigned)min((int64_t)(256 * 64), ceil_div(pieces, 256));
+  if (dtype == GS_F32)
+    table_mult_add_f32_kernel<<<blocks, 256, 0, stream>>>(static_cast<float4*>(dst),
+                                                          static_cast<const float4*>(src), pieces, factor);
+  else
+    table_mult_add_bf16_kernel<<<blocks, 256, 0, stream>>>(static_cast<uint4*>(dst),
+                                                           static_cast<const uint4*>(src), pieces, factor);
   GS_LAUNCH_CHECK();
   return GS_OK;
 }

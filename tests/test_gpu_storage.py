@@ -134,3 +134,55 @@ def test_storage_argument_errors(gs):
     small = torch.empty(256, dtype=torch.uint8, device=DEV)
     with pytest.raises(gs.GsError):
         gs.gs_unique_ids(torch.zeros(100_000, dtype=torch.int32, device=DEV), 10, ws=small)
+
+
+@pytest.mark.parametrize("dtype,dim", [("f32", 128), ("f32", 4), ("bf16", 256), ("bf16", 8)])
+def test_dense_mult_and_mult_add(gs, oracle, dtype, dim):
+    from paper_2407_15452_amd import inputs
+    n = 30_011
+    a, b = inputs.random_tables(n, dim, 9, 1.5)
+    if dtype == "bf16":
+        d_a, d_b = a.to(torch.bfloat16).to(DEV), b.to(torch.bfloat16).to(DEV)
+        h_a, h_b = _bits(d_a).copy(), _bits(d_b).copy()
+        code = oracle.BF16
+    else:
+        d_a, d_b = a.to(DEV), b.to(DEV)
+        h_a, h_b = a.numpy().copy(), b.numpy().copy()
+        code = oracle.F32
+    gs.gs_table_mult(d_a, 0.9)
+    oracle.table_mult(h_a, 0.9, dtype=code)
+    gs.gs_table_mult_add(d_b, d_a, -0.025)
+    oracle.table_mult_add(h_b, h_a, -0.025, dtype=code)
+    view = _bits if dtype == "bf16" else (lambda t: t.cpu().numpy())
+    np.testing.assert_array_equal(view(d_a), h_a)
+    np.testing.assert_array_equal(view(d_b), h_b)
+    with pytest.raises(gs.GsError):
+        gs.gs_table_mult_add(d_a, d_a, 1.0)
+
+
+def test_momentum_update_from_the_storage_operations(gs, oracle):
+    """mult, put of the gradient rows, mult_add: the paper's model update composed from the
+    exported operations, against gs_sgns_momentum_step."""
+    from paper_2407_15452_amd import inputs
+    n, d, B, K, lr, mu = 20_000, 64, 8_192, 5, 0.05, 0.9
+    w_in, w_out = inputs.random_tables(n, d, 8, 0.3)
+    m_in, m_out = inputs.random_tables(n, d, 9, 0.05)
+    rng = np.random.default_rng(2)
+    c = _t(rng.integers(0, n, B).astype(np.int32))
+    o = _t(rng.integers(0, n, B).astype(np.int32))
+    neg = _t(rng.integers(0, n, (B, K)).astype(np.int32))
+    want = [t.to(DEV) for t in (w_in, w_out, m_in, m_out)]
+    gs.gs_sgns_momentum_step(*want, c, o, neg, lr, mu)
+    got = [t.to(DEV) for t in (w_in, w_out, m_in, m_out)]
+    # gradient rows of the batch: a plain step with lr = 1 on copies, old - new
+    s_in, s_out = got[0].clone(), got[1].clone()
+    gs.gs_sgns_step(s_in, s_out, c, o, neg, 1.0)
+    for model, moment, stepped, ids in ((got[0], got[2], s_in, c),
+                                        (got[1], got[3], s_out, torch.cat([o, neg.reshape(-1)]))):
+        u, count, _ = gs.gs_unique_ids(ids, n, want_inverse=False)
+        grads = gs.gs_get_rows(model, u, count=count) - gs.gs_get_rows(stepped, u, count=count)
+        gs.gs_table_mult(moment, mu)
+        gs.gs_put_rows(moment, u, grads, 1.0, count=count)
+        gs.gs_table_mult_add(model, moment, -lr)
+    for g_t, w_t in zip(got, want):
+        assert (g_t - w_t).abs().max().item() <= 1e-5
