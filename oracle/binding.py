@@ -49,7 +49,7 @@ def _load():
                      "oracle_node2vec_walk", "oracle_make_pairs", "oracle_sample_negatives",
                      "oracle_sgns_step", "oracle_sgns_momentum_step", "oracle_sample_edges", "oracle_unique_ids", "oracle_get_rows",
                      "oracle_put_rows", "oracle_sgns_adam_step", "oracle_line1_step", "oracle_table_mult",
-                     "oracle_table_mult_add"):
+                     "oracle_table_mult_add", "oracle_sort_pairs"):
             getattr(_lib, name).restype = C.c_int32
         _lib.oracle_philox4x32_10.restype = None
     return _lib
@@ -328,3 +328,15 @@ def table_mult_add(dst, src, factor, dtype=F32):
     rc = _load().oracle_table_mult_add(_ptr(dst), _ptr(src), C.c_int64(dst.shape[0]),
                                        C.c_int32(dst.shape[1]), C.c_int32(dtype), C.c_float(factor))
     _check(rc, "oracle_table_mult_add")
+
+
+def sort_pairs(centers, contexts, num_nodes):
+    """Pairs reordered by centre id, stable; returns (centers, contexts)."""
+    centers, contexts = _i32(centers), _i32(contexts)
+    n = int(centers.shape[0])
+    oc = np.zeros(max(1, n), dtype=np.int32)
+    oo = np.zeros(max(1, n), dtype=np.int32)
+    rc = _load().oracle_sort_pairs(_ptr(centers), _ptr(contexts), C.c_int64(n), C.c_int64(num_nodes),
+                                   _ptr(oc), _ptr(oo))
+    _check(rc, "oracle_sort_pairs")
+    return oc[:n], oo[:n]

@@ -747,4 +747,27 @@ int32_t oracle_table_mult_add(void* dst, const void* src, int64_t num_nodes, int
   return ORACLE_OK;
 }
 
+
+// Reorders a batch of (centre, context) pairs by centre id, keeping the input
+// order among pairs of equal centre (a stable sort).  The order of the pairs
+// inside a batch does not change an iteration's result (sums over the batch);
+// equal centres next to each other let the step load and write a centre row
+// once per run.  Ids outside [0, num_nodes) go last, in input order.
+int32_t oracle_sort_pairs(const int32_t* centers, const int32_t* contexts, int64_t n,
+                          int64_t num_nodes, int32_t* centers_out, int32_t* contexts_out) {
+  if (n < 0 || num_nodes < 1 || (n > 0 && (!centers || !contexts || !centers_out || !contexts_out)))
+    return ORACLE_EINVAL;
+  std::vector<int64_t> order((size_t)n);
+  for (int64_t i = 0; i < n; ++i) order[(size_t)i] = i;
+  auto key = [&](int64_t i) -> int64_t {
+    return (centers[i] >= 0 && (int64_t)centers[i] < num_nodes) ? (int64_t)centers[i] : num_nodes;
+  };
+  std::stable_sort(order.begin(), order.end(), [&](int64_t a, int64_t b) { return key(a) < key(b); });
+  for (int64_t j = 0; j < n; ++j) {
+    centers_out[j] = centers[order[(size_t)j]];
+    contexts_out[j] = contexts[order[(size_t)j]];
+  }
+  return ORACLE_OK;
+}
+
 }  // extern "C"

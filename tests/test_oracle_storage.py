@@ -151,3 +151,37 @@ def test_momentum_step_is_mult_put_mult_add(oracle):
         oracle.table_mult_add(model, moment, -lr)
     for g, w in zip(got, want):
         np.testing.assert_allclose(g, w, atol=1e-6)
+
+
+def test_sort_pairs_is_a_stable_argsort(oracle):
+    rng = np.random.default_rng(7)
+    c = rng.integers(0, 30, 500).astype(np.int32)
+    o = rng.integers(0, 1000, 500).astype(np.int32)
+    c[[3, 77]] = [-1, 30]                                  # not rows: last, in input order
+    sc, so = oracle.sort_pairs(c, o, 30)
+    key = np.where((c >= 0) & (c < 30), c, 30)
+    order = np.argsort(key, kind="stable")
+    np.testing.assert_array_equal(sc, c[order])
+    np.testing.assert_array_equal(so, o[order])
+    assert list(sc[-2:]) == [-1, 30]
+
+
+def test_sorting_a_batch_does_not_change_the_step(oracle):
+    rng = np.random.default_rng(8)
+    n, d, b, k = 30, 4, 200, 3
+    w_in = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    w_out = rng.normal(0, 0.5, (n, d)).astype(np.float32)
+    c = rng.integers(0, n, b).astype(np.int32)
+    o = rng.integers(0, n, b).astype(np.int32)
+    neg = rng.integers(0, n, (b, k)).astype(np.int32)
+    a_in, a_out = w_in.copy(), w_out.copy()
+    la = oracle.sgns_step(a_in, a_out, c, o, neg, 0.05)
+    # the same multiset of (centre, context, negatives) triples in sorted order
+    order = np.argsort(c, kind="stable")
+    sc, so = oracle.sort_pairs(c, o, n)
+    np.testing.assert_array_equal(sc, c[order])
+    b_in, b_out = w_in.copy(), w_out.copy()
+    lb = oracle.sgns_step(b_in, b_out, sc, so, neg[order], 0.05)
+    assert la == pytest.approx(lb, rel=1e-12)
+    np.testing.assert_allclose(a_in, b_in, atol=1e-7)
+    np.testing.assert_allclose(a_out, b_out, atol=1e-7)
