@@ -350,6 +350,22 @@ int32_t gs_put_rows(void* table, int64_t num_nodes, int32_t dim, int32_t dtype, 
                     void* stream);
 
 /* --------------------------------------------------------------------------
+ * gs_sort_pairs -- reorders a batch of (centre, context) pairs by centre id,
+ * keeping the input order among equal centres (stable).  An iteration sums
+ * over its batch, so the order of the pairs does not change its result; with
+ * equal centres next to each other gs_sgns_step / gs_line1_step load and write
+ * each centre row once per run.  Walk batches (gs_make_pairs) already come in
+ * runs; a LINE batch (gs_sample_edges) does not.  Ids outside [0, num_nodes)
+ * go last, in input order.
+ *   centers, contexts int32[n] (n < 2^31); outputs int32[n], distinct from the
+ *   inputs.  Negatives are drawn by position afterwards (gs_sample_negatives).
+ * ------------------------------------------------------------------------ */
+size_t gs_sort_pairs_workspace_bytes(int64_t n);
+int32_t gs_sort_pairs(const int32_t* centers, const int32_t* contexts, int64_t n, int64_t num_nodes,
+                      int32_t* centers_out, int32_t* contexts_out, void* ws, size_t ws_bytes,
+                      void* stream);
+
+/* --------------------------------------------------------------------------
  * gs_table_mult, gs_table_mult_add -- the two dense storage operations of Sec.
  * 3.2 (model update for SGD with momentum): every element of a table times a
  * factor (the momentum table times the momentum value), and dst <- dst +

@@ -30,7 +30,7 @@ EXPORTS = (
     "gs_sgns_step_fused_workspace_bytes", "gs_sgns_step_fused",
     "gs_line1_step_workspace_bytes", "gs_line1_step",
     "gs_unique_ids_workspace_bytes", "gs_unique_ids", "gs_get_rows", "gs_put_rows",
-    "gs_table_mult", "gs_table_mult_add",
+    "gs_table_mult", "gs_table_mult_add", "gs_sort_pairs_workspace_bytes", "gs_sort_pairs",
 )
 
 
@@ -458,3 +458,24 @@ def gs_table_mult_add(dst, src, factor: float):
                                  C.c_int32(dst.shape[1]), C.c_int32(_table_dtype(dst)),
                                  C.c_float(factor), _stream())
     _check(rc, "gs_table_mult_add")
+
+
+def gs_sort_pairs_workspace_bytes(n: int) -> int:
+    return int(lib().gs_sort_pairs_workspace_bytes(C.c_int64(n)))
+
+
+def gs_sort_pairs(centers, contexts, num_nodes: int, centers_out=None, contexts_out=None, ws=None):
+    """Pairs reordered by centre id (stable); returns (centers_out, contexts_out)."""
+    n = int(centers.numel())
+    dev = centers.device
+    if centers_out is None:
+        centers_out = torch.empty(max(n, 1), dtype=torch.int32, device=dev)[:n]
+    if contexts_out is None:
+        contexts_out = torch.empty(max(n, 1), dtype=torch.int32, device=dev)[:n]
+    if ws is None:
+        ws = _workspace(gs_sort_pairs_workspace_bytes(n), dev)
+    rc = lib().gs_sort_pairs(_dev(centers, torch.int32, "centers"), _dev(contexts, torch.int32, "contexts"),
+                             C.c_int64(n), C.c_int64(num_nodes), _dev(centers_out, torch.int32),
+                             _dev(contexts_out, torch.int32), _dev(ws), C.c_size_t(ws.numel()), _stream())
+    _check(rc, "gs_sort_pairs")
+    return centers_out, contexts_out

@@ -134,6 +134,19 @@ __global__ __launch_bounds__(kRowThreads) void put_rows_bf16_kernel(
   }
 }
 
+// pairs in sorted order: entry j comes from input position index[j]
+__global__ void sort_pairs_gather_kernel(const uint32_t* __restrict__ index,
+                                         const int32_t* __restrict__ centers,
+                                         const int32_t* __restrict__ contexts, int64_t n,
+                                         int32_t* __restrict__ centers_out,
+                                         int32_t* __restrict__ contexts_out) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  const uint32_t from = index[j];
+  centers_out[j] = centers[from];
+  contexts_out[j] = contexts[from];
+}
+
 // ---- dense operations over a whole table: 16 bytes per lane, grid-stride ----------------
 __global__ __launch_bounds__(256) void table_mult_f32_kernel(float4* __restrict__ t, int64_t n4,
                                                              float factor) {
@@ -211,6 +224,26 @@ UniquePlan plan_unique(void* ws, int64_t n) {
   p.index_alt = cv.take<uint32_t>(m);
   p.head = cv.take<int64_t>(m);
   p.scan_scratch = cv.take<int64_t>(scan_scratch_elems((int64_t)m));
+  p.sort_scratch = cv.take<char>(radix_sort_scratch_bytes((int64_t)m));
+  p.bytes = cv.used;
+  return p;
+}
+
+struct SortPairsPlan {
+  uint64_t *keys, *keys_alt;
+  uint32_t *index, *index_alt;
+  void* sort_scratch;
+  size_t bytes;
+};
+
+SortPairsPlan plan_sort_pairs(void* ws, int64_t n) {
+  Carver cv(ws);
+  SortPairsPlan p;
+  const size_t m = (size_t)(n > 0 ? n : 1);
+  p.keys = cv.take<uint64_t>(m);
+  p.keys_alt = cv.take<uint64_t>(m);
+  p.index = cv.take<uint32_t>(m);
+  p.index_alt = cv.take<uint32_t>(m);
   p.sort_scratch = cv.take<char>(radix_sort_scratch_bytes((int64_t)m));
   p.bytes = cv.used;
   return p;
@@ -342,6 +375,35 @@ extern "C" int32_t gs_table_mult_add(void* dst, const void* src, int64_t num_nod
   else
     table_mult_add_bf16_kernel<<<blocks, 256, 0, stream>>>(static_cast<uint4*>(dst),
                                                            static_cast<const uint4*>(src), pieces, factor);
+  GS_LAUNCH_CHECK();
+  return GS_OK;
+}
+
+extern "C" size_t gs_sort_pairs_workspace_bytes(int64_t n) {
+  if (n < 0) return 0;
+  return plan_sort_pairs(nullptr, n).bytes;
+}
+
+extern "C" int32_t gs_sort_pairs(const int32_t* centers, const int32_t* contexts, int64_t n,
+                                 int64_t num_nodes, int32_t* centers_out, int32_t* contexts_out,
+                                 void* ws, size_t ws_bytes, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  if (n < 0 || n >= ((int64_t)1 << 31) || num_nodes < 1 || num_nodes > (int64_t)INT32_MAX)
+    return GS_EINVAL;
+  if (n > 0 && (!centers || !contexts || !centers_out || !contexts_out)) return GS_EINVAL;
+  if (n > 0 && (centers_out == centers || contexts_out == contexts)) return GS_EINVAL;
+  if (!ws || !aligned(ws, 256)) return GS_EINVAL;
+  SortPairsPlan p = plan_sort_pairs(ws, n);
+  if (ws_bytes < p.bytes) return GS_EWORKSPACE;
+  if (n == 0) return GS_OK;
+  const unsigned blocks = (unsigned)ceil_div(n, 256);
+  unique_keys_kernel<<<blocks, 256, 0, stream>>>(centers, n, num_nodes, p.keys, p.index);
+  GS_LAUNCH_CHECK();
+  const int32_t rc = radix_sort_u64_u32(p.keys, p.index, p.keys_alt, p.index_alt, n, 0,
+                                        bits_for((uint64_t)num_nodes), 0, 0, p.sort_scratch, stream);
+  if (rc != GS_OK) return rc;
+  sort_pairs_gather_kernel<<<blocks, 256, 0, stream>>>(p.index, centers, contexts, n, centers_out,
+                                                       contexts_out);
   GS_LAUNCH_CHECK();
   return GS_OK;
 }

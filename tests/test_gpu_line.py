@@ -208,3 +208,41 @@ def test_line1_step_argument_errors(gs):
         gs.gs_line1_step(w, i, i, n, 0.1, ws=small)
     bad = i.clone(); bad[1] = 10
     assert np.isnan(float(gs.gs_line1_step(w, bad, i, n, 0.1).item()))
+
+
+@pytest.mark.parametrize("n,num_nodes", [(0, 10), (1, 10), (4097, 300), (200_003, 1_000_000),
+                                         (50_000, (1 << 31) - 1)])
+def test_sort_pairs(gs, oracle, n, num_nodes):
+    rng = np.random.default_rng(n + 1)
+    c = rng.integers(0, min(num_nodes, 1 << 22), n).astype(np.int32)
+    o = rng.integers(0, 1 << 30, n).astype(np.int32)
+    if n > 100:
+        c[::97] = -3                                          # not rows: go last
+        if num_nodes < (1 << 31) - 1:
+            c[5::101] = num_nodes
+    want_c, want_o = oracle.sort_pairs(c, o, num_nodes)
+    got_c, got_o = gs.gs_sort_pairs(_t(c).reshape(-1), _t(o).reshape(-1), num_nodes)
+    np.testing.assert_array_equal(got_c.cpu().numpy(), want_c)
+    np.testing.assert_array_equal(got_o.cpu().numpy(), want_o)
+
+
+def test_sorted_line_batch_gives_the_same_step(gs, oracle, graph0):
+    """A LINE batch reordered by source id: the step's result is that of the unsorted batch
+    with the negatives permuted alike (sums over the batch), within the step's tolerance."""
+    from paper_2407_15452_amd import inputs
+    wl, (off, nb), g = graph0
+    n, d, K, B = wl.num_nodes, wl.dim, 5, 30_000
+    c, o = gs.gs_sample_edges(g, None, B, seed=51)
+    sc, so = gs.gs_sort_pairs(c, o, n)
+    assert bool((sc[1:] >= sc[:-1]).all())
+    neg = gs.gs_sample_negatives(None, n, B, K, seed=52, device=DEV)
+    w_in, w_out = inputs.random_tables(n, d, 3, 0.3)
+    d_in, d_out = w_in.to(DEV), w_out.to(DEV)
+    loss = gs.gs_sgns_step(d_in, d_out, sc, so, neg, 0.02)
+    h_in, h_out = w_in.numpy().copy(), w_out.numpy().copy()
+    want = oracle.sgns_step(h_in, h_out, sc.cpu().numpy(), so.cpu().numpy(), neg.cpu().numpy(), 0.02)
+    assert abs(float(loss.item()) - want) <= LOSS_RTOL * abs(want)
+    assert np.abs(d_in.cpu().numpy() - h_in).max() <= EMB_ATOL
+    assert np.abs(d_out.cpu().numpy() - h_out).max() <= EMB_ATOL
+    with pytest.raises(gs.GsError):
+        gs.gs_sort_pairs(c, o, n, centers_out=c, contexts_out=o)
