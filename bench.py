@@ -326,9 +326,19 @@ def main():
             lc = torch.empty(B, dtype=torch.int32, device=dev)
             lo_ = torch.empty(B, dtype=torch.int32, device=dev)
 
-            def line_batch(it):
+            lc_raw = torch.empty(B, dtype=torch.int32, device=dev)
+            lo_raw = torch.empty(B, dtype=torch.int32, device=dev)
+            sort_ws = torch.empty(gs.gs_sort_pairs_workspace_bytes(B), dtype=torch.uint8, device=dev)
+
+            def sample_sorted(it):
+                """B sampled edges, reordered by source id so that equal sources form runs."""
                 gs.gs_sample_edges(g, None, B, wl.walk_seed ^ 0x4c494e45, sample_index_base=it * B,
-                                   centers_out=lc, contexts_out=lo_)
+                                   centers_out=lc_raw, contexts_out=lo_raw)
+                gs.gs_sort_pairs(lc_raw, lo_raw, wl.num_nodes, centers_out=lc, contexts_out=lo_,
+                                 ws=sort_ws)
+
+            def line_batch(it):
+                sample_sorted(it)
                 gs.gs_sample_negatives(noise, wl.num_nodes, B, k, wl.neg_seed ^ 0x4c494e45,
                                        pair_index_base=it * B, out=negs)
                 gs.gs_sgns_step(w_in, w_out, lc, lo_, negs, lr, loss_out=losses[:1], ws=sgns_ws)
@@ -344,7 +354,8 @@ def main():
             torch.cuda.synchronize()
             line_ms = e0.elapsed_time(e1) / 5
             line = {"ms_per_batch": line_ms, "edges_per_s": B / (line_ms * 1e-3),
-                    "what": "gs_sample_edges + gs_sample_negatives + gs_sgns_step per batch of B edges"}
+                    "what": "gs_sample_edges + gs_sort_pairs + gs_sample_negatives + gs_sgns_step per batch of "
+                            "B edges"}
             # first order: the same batches on one table (a throw-away copy)
             if wl.num_nodes * wl.dim * elem_bytes <= 16e9:
                 w_one = w_in.clone()
@@ -353,8 +364,7 @@ def main():
                                     dtype=torch.uint8, device=dev)
 
                 def line1_batch(it):
-                    gs.gs_sample_edges(g, None, B, wl.walk_seed ^ 0x4c494e45, sample_index_base=it * B,
-                                       centers_out=lc, contexts_out=lo_)
+                    sample_sorted(it)
                     gs.gs_sample_negatives(noise, wl.num_nodes, B, k, wl.neg_seed ^ 0x4c494e45,
                                            pair_index_base=it * B, out=negs)
                     gs.gs_line1_step(w_one, lc, lo_, negs, lr, loss_out=losses[:1], ws=l1_ws)
@@ -370,7 +380,7 @@ def main():
                 torch.cuda.synchronize()
                 line["first_order_ms_per_batch"] = e0.elapsed_time(e1) / 5
                 del w_one, l1_ws
-            del lc, lo_
+            del lc, lo_, lc_raw, lo_raw, sort_ws
 
         # ------------------------------------------------------------------ get / put of a batch (extra)
         # the ids of the last batch: merge, fetch the block of distinct rows, add a block back
