@@ -21,10 +21,12 @@
  *    *_workspace_bytes() function (host, O(1)) returns the size to provide.
  *    ws must be 256-byte aligned.  Its contents are undefined afterwards.
  *  - Return value: GS_OK or a negative gs_status.  Arguments are validated on
- *    the host only; nothing is enqueued when a call fails validation.  The
- *    contents of index arrays are not validated: node ids outside
- *    [0, num_nodes) in CSR rows, centers, contexts or negatives are undefined
- *    behaviour (ids in edge lists and in `starts` are checked by the kernels).
+ *    the host only; nothing is enqueued when a call fails validation.  Node
+ *    ids live in device memory and are checked by the kernels that use them as
+ *    row numbers: edge lists drop them, walks stop at them (`starts`, CSR
+ *    neighbours), the training steps read row 0 instead and report a NaN loss,
+ *    the storage operations skip them.  CSR offsets and the alias[] entries of
+ *    a table are trusted as built by gs_csr_build / gs_alias_build.
  *  - Node ids are int32.  CSR offsets are int32 or int64 (`offset_bits`).
  *  - Random numbers are Philox4x32-10 blocks keyed by the caller's 64-bit
  *    seed; the counter is (index low, index high, c2, c3) as stated per call,
