@@ -386,7 +386,7 @@ def main():
         # the ids of the last batch: merge, fetch the block of distinct rows, add a block back
         lo = (K - 1) * B
         batch_ids = torch.cat([centers[lo:lo + B], contexts[lo:lo + B], negs.reshape(-1)])
-        uniq_ws = torch.empty(gs.gs_unique_ids_workspace_bytes(batch_ids.numel()), dtype=torch.uint8,
+        uniq_ws = torch.empty(gs.gs_unique_ids_workspace_bytes(batch_ids.numel(), wl.num_nodes), dtype=torch.uint8,
                               device=dev)
         uniq, ucount, _ = gs.gs_unique_ids(batch_ids, wl.num_nodes, ws=uniq_ws)
         n_uniq = int(ucount.item())

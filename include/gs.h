@@ -324,6 +324,8 @@ int32_t gs_sgns_adam_step(float* w_in, float* w_out, float* m_in, float* m_out, 
  *   entries are written), num_unique_out int64[1] on the device, inverse_out
  *   int32[n] or NULL: position of ids[i] in unique_out.  Ids outside
  *   [0, num_nodes) are left out of unique_out and get inverse -1.
+ *   Workspace: gs_unique_ids_workspace_bytes(n, num_nodes) (a bitmap of the node
+ *   ids, or sort buffers for the batch when the graph is far larger).
  *
  * gs_get_rows -- out[i] = table[ids[i]] for i < n, as fp32 (bf16 rows widened
  *   exactly); a zero row for an id outside [0, num_nodes).  out float[n][dim].
@@ -340,7 +342,7 @@ int32_t gs_sgns_adam_step(float* w_in, float* w_out, float* m_in, float* m_out, 
  *   table [num_nodes][dim] of dtype GS_F32 | GS_BF16, 16-byte aligned; dim a
  *   multiple of 4 (fp32) or 8 (bf16).  Errors: GS_EINVAL otherwise.
  * ------------------------------------------------------------------------ */
-size_t gs_unique_ids_workspace_bytes(int64_t n);
+size_t gs_unique_ids_workspace_bytes(int64_t n, int64_t num_nodes);
 int32_t gs_unique_ids(const int32_t* ids, int64_t n, int64_t num_nodes, int32_t* unique_out,
                       int64_t* num_unique_out, int32_t* inverse_out, void* ws, size_t ws_bytes,
                       void* stream);

@@ -316,8 +316,8 @@ def gs_sgns_momentum_step(w_in, w_out, m_in, m_out, centers, contexts, negs, lr:
     return loss_out
 
 
-def gs_unique_ids_workspace_bytes(n: int) -> int:
-    return int(lib().gs_unique_ids_workspace_bytes(C.c_int64(n)))
+def gs_unique_ids_workspace_bytes(n: int, num_nodes: int) -> int:
+    return int(lib().gs_unique_ids_workspace_bytes(C.c_int64(n), C.c_int64(num_nodes)))
 
 
 def gs_unique_ids(ids, num_nodes: int, want_inverse: bool = True, ws=None):
@@ -329,7 +329,7 @@ def gs_unique_ids(ids, num_nodes: int, want_inverse: bool = True, ws=None):
     count = torch.zeros(1, dtype=torch.int64, device=dev)
     inverse = torch.empty(max(n, 1), dtype=torch.int32, device=dev) if want_inverse else None
     if ws is None:
-        ws = _workspace(gs_unique_ids_workspace_bytes(n), dev)
+        ws = _workspace(gs_unique_ids_workspace_bytes(n, num_nodes), dev)
     rc = lib().gs_unique_ids(_dev(ids, torch.int32, "ids"), C.c_int64(n), C.c_int64(num_nodes),
                              _dev(unique_out, torch.int32), _dev(count, torch.int64),
                              _dev(inverse, torch.int32) if inverse is not None else None,

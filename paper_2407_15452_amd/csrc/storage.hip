@@ -46,6 +46,57 @@ __global__ void unique_emit_kernel(const uint64_t* __restrict__ keys, const uint
   if (inverse_out) inverse_out[index[j]] = valid ? (int32_t)(is_head ? b : b - 1) : -1;
 }
 
+// ---- merged ids through a bitmap of the node ids (when the batch is not small next to the
+// graph): mark, count the bits of every word, scan, then read the ids off in ascending order
+__global__ void bitmap_mark_kernel(const int32_t* __restrict__ ids, int64_t n, int64_t num_nodes,
+                                   uint32_t* __restrict__ bitmap) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int32_t v = ids[i];
+  if (v < 0 || (int64_t)v >= num_nodes) return;
+  const uint32_t bit = 1u << (v & 31);
+  // bits are only ever set: a word read as already holding the bit needs no atomic (a stale
+  // read merely costs a redundant one)
+  if ((bitmap[v >> 5] & bit) == 0u) atomicOr(bitmap + (v >> 5), bit);
+}
+
+__global__ void bitmap_count_kernel(const uint32_t* __restrict__ bitmap, int64_t words,
+                                    int64_t* __restrict__ counts) {
+  const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (w < words) counts[w] = (int64_t)__popc(bitmap[w]);
+}
+
+// before[w] = number of set bits in the words before w
+__global__ void bitmap_emit_kernel(const uint32_t* __restrict__ bitmap, const int64_t* __restrict__ before,
+                                   int64_t words, int32_t* __restrict__ unique_out) {
+  const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (w >= words) return;
+  uint32_t bits = bitmap[w];
+  int64_t at = before[w];
+  while (bits != 0u) {
+    const int b = __ffs((int)bits) - 1;
+    unique_out[at++] = (int32_t)(w * 32 + b);
+    bits &= bits - 1u;
+  }
+}
+
+__global__ void bitmap_inverse_kernel(const int32_t* __restrict__ ids, int64_t n, int64_t num_nodes,
+                                      const uint32_t* __restrict__ bitmap,
+                                      const int64_t* __restrict__ before,
+                                      int32_t* __restrict__ inverse_out) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int32_t v = ids[i];
+  if (v < 0 || (int64_t)v >= num_nodes) { inverse_out[i] = -1; return; }
+  const uint32_t below = bitmap[v >> 5] & ((1u << (v & 31)) - 1u);
+  inverse_out[i] = (int32_t)(before[v >> 5] + (int64_t)__popc(below));
+}
+
+__global__ void fill_words_kernel(uint32_t* __restrict__ p, int64_t n, uint32_t value) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = value;
+}
+
 __device__ __forceinline__ int64_t live_count(int64_t n, const int64_t* count_dev) {
   if (count_dev == nullptr) return n;
   const int64_t c = *count_dev;
@@ -206,6 +257,28 @@ int32_t check_table_args(const void* table, int64_t num_nodes, int32_t dim, int3
   return GS_OK;
 }
 
+// The bitmap route costs a pass over num_nodes / 32 words, the sort route a few passes over the
+// n ids: bitmap unless the graph is far larger than the batch.
+bool unique_by_bitmap(int64_t n, int64_t num_nodes) { return ceil_div(num_nodes, 32) <= 8 * n; }
+
+struct BitmapPlan {
+  uint32_t* bitmap;
+  int64_t *counts, *scan_scratch;
+  int64_t words;
+  size_t bytes;
+};
+
+BitmapPlan plan_bitmap(void* ws, int64_t num_nodes) {
+  Carver cv(ws);
+  BitmapPlan p;
+  p.words = ceil_div(num_nodes > 0 ? num_nodes : 1, 32);
+  p.bitmap = cv.take<uint32_t>((size_t)p.words);
+  p.counts = cv.take<int64_t>((size_t)p.words);
+  p.scan_scratch = cv.take<int64_t>(scan_scratch_elems(p.words));
+  p.bytes = cv.used;
+  return p;
+}
+
 struct UniquePlan {
   uint64_t *keys, *keys_alt;
   uint32_t *index, *index_alt;
@@ -272,8 +345,9 @@ int32_t check_rows_args(const void* table, int64_t num_nodes, int32_t dim, int32
 
 using namespace gs;
 
-extern "C" size_t gs_unique_ids_workspace_bytes(int64_t n) {
-  if (n < 0) return 0;
+extern "C" size_t gs_unique_ids_workspace_bytes(int64_t n, int64_t num_nodes) {
+  if (n < 0 || num_nodes < 1) return 0;
+  if (unique_by_bitmap(n, num_nodes)) return plan_bitmap(nullptr, num_nodes).bytes;
   return plan_unique(nullptr, n).bytes;
 }
 
@@ -286,6 +360,28 @@ extern "C" int32_t gs_unique_ids(const int32_t* ids, int64_t n, int64_t num_node
     return GS_EINVAL;
   if (n > 0 && (!ids || !unique_out)) return GS_EINVAL;
   if (!ws || !aligned(ws, 256)) return GS_EINVAL;
+  if (unique_by_bitmap(n, num_nodes)) {
+    BitmapPlan b = plan_bitmap(ws, num_nodes);
+    if (ws_bytes < b.bytes) return GS_EWORKSPACE;
+    const unsigned word_blocks = (unsigned)ceil_div(b.words, 256);
+    const unsigned id_blocks = (unsigned)ceil_div(n, 256);
+    fill_words_kernel<<<word_blocks, 256, 0, stream>>>(b.bitmap, b.words, 0u);
+    GS_LAUNCH_CHECK();
+    bitmap_mark_kernel<<<id_blocks, 256, 0, stream>>>(ids, n, num_nodes, b.bitmap);
+    GS_LAUNCH_CHECK();
+    bitmap_count_kernel<<<word_blocks, 256, 0, stream>>>(b.bitmap, b.words, b.counts);
+    GS_LAUNCH_CHECK();
+    const int32_t rc = exclusive_scan_i64(b.counts, b.words, b.scan_scratch, num_unique_out, stream);
+    if (rc != GS_OK) return rc;
+    bitmap_emit_kernel<<<word_blocks, 256, 0, stream>>>(b.bitmap, b.counts, b.words, unique_out);
+    GS_LAUNCH_CHECK();
+    if (inverse_out) {
+      bitmap_inverse_kernel<<<id_blocks, 256, 0, stream>>>(ids, n, num_nodes, b.bitmap, b.counts,
+                                                          inverse_out);
+      GS_LAUNCH_CHECK();
+    }
+    return GS_OK;
+  }
   UniquePlan p = plan_unique(ws, n);
   if (ws_bytes < p.bytes) return GS_EWORKSPACE;
   const unsigned blocks = (unsigned)ceil_div(n, 256);
