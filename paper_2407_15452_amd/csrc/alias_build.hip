@@ -347,6 +347,9 @@ extern "C" int32_t gs_alias_build(const void* seg_offsets, int32_t offset_bits, 
   if (!ws || !aligned(ws, 256)) return GS_EINVAL;
   AliasPlan p = plan_alias(ws, total_entries);
   if (ws_bytes < p.bytes) return GS_EWORKSPACE;
+  // alias[] holds 32-bit positions inside a segment; one segment over everything is the
+  // one case the host can see
+  if (num_segments == 1 && total_entries > (int64_t)INT32_MAX) return GS_EOVERFLOW;
   if (num_segments == 0 || total_entries == 0) return GS_OK;
   if (offset_bits == 64)
     return launch_alias_build((const int64_t*)seg_offsets, num_segments, total_entries, weights,

@@ -65,3 +65,28 @@ def test_inputs_are_deterministic():
     assert inputs.pairs_per_full_walk(20, 5) == 170 and inputs.pairs_per_full_walk(80, 10) == 1490
     w_in, w_out = inputs.init_tables(100, 64, 5)
     assert float(w_in.abs().max()) <= 0.5 / 64 and float(w_out.abs().max()) == 0
+
+
+def test_argument_checks_that_need_no_gpu(lib):
+    """Rejected on the host before anything is enqueued (no device pointer is touched)."""
+    fake = C.c_void_p(256)                       # non-null, aligned; never dereferenced
+    # one alias segment longer than a 32-bit position
+    rc = lib.gs_alias_build(fake, C.c_int32(64), C.c_int64(1), C.c_int64(1 << 31), fake, fake, fake,
+                            fake, C.c_size_t(1 << 62), None)
+    assert rc == -3
+    # 32-bit offsets cannot hold the symmetrised capacity
+    rc = lib.gs_csr_build(fake, fake, None, C.c_int64((1 << 30) + 1), C.c_int64(10), C.c_uint32(1),
+                          C.c_int32(32), fake, fake, None, fake, fake, C.c_size_t(1 << 62), None)
+    assert rc == -3
+    # dim not a multiple of the 16-byte piece; k beyond the limit; one table on both sides
+    step = lambda w_in, w_out, dim, k: lib.gs_sgns_step(  # noqa: E731
+        w_in, w_out, C.c_int64(10), C.c_int32(dim), C.c_int32(0), fake, fake, fake, C.c_int64(4),
+        C.c_int32(k), C.c_float(0.1), fake, fake, C.c_size_t(1 << 62), None)
+    other = C.c_void_p(512)
+    assert step(fake, other, 6, 2) == -1
+    assert step(fake, other, 8, 61) == -1
+    assert step(fake, fake, 8, 2) == -1
+    assert lib.gs_unique_ids_workspace_bytes(C.c_int64(1000), C.c_int64(100)) < \
+        lib.gs_unique_ids_workspace_bytes(C.c_int64(1000), C.c_int64(10**9))
+    assert lib.gs_sgns_step_fused_workspace_bytes(C.c_int64(1000), C.c_int64(10), C.c_int32(5), C.c_int32(128), C.c_int32(0)) > \
+        lib.gs_sgns_step_workspace_bytes(C.c_int64(1000), C.c_int64(10), C.c_int32(5), C.c_int32(128), C.c_int32(0))
