@@ -26,6 +26,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "sgns_step_hbm_traffic.json")
 SGNS_SOURCE = os.path.join(ROOT, "paper_2407_15452_amd", "csrc", "sgns.hip")
+WALK_SOURCE = os.path.join(ROOT, "paper_2407_15452_amd", "csrc", "walk.hip")
 
 
 def sgns_bytes_per_pair(k: int, dim: int, elem_bytes: int, window: int) -> float:
@@ -57,6 +58,17 @@ def code_hash(path: str) -> str:
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     text = re.sub(r"//[^\n]*", "", text)
     return hashlib.sha256(re.sub(r"\s+", "", text).encode()).hexdigest()
+
+
+def walk_record(workload_name: str):
+    """Counter record of the walker (bytes fetched per transition), or None when there is none
+    for this workload or walk.hip has changed since."""
+    try:
+        rec = json.load(open(TRAFFIC_FILE))[workload_name]
+        ok = rec["walk_hip_code_sha256"] == code_hash(WALK_SOURCE)
+        return rec if ok and "walk_fetch_bytes_per_transition" in rec else None
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def traffic_record(workload_name: str):
@@ -442,6 +454,15 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "bytes_per_pair": bpp,
                      "traffic": measured_traffic(wl.name)},
     }
+    wrec = walk_record(wl.name)
+    if wrec:
+        # counter-measured bytes fetched per transition times the transition rate measured here
+        rate = wrec["walk_fetch_bytes_per_transition"] * walk_steps_per_s / 1e9
+        result["walk_roofline"] = {"bound": "hbm", "kernel": "node2vec / walk kernel, stand-alone launch",
+                                   "achieved": rate, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                   "frac": rate / HBM_PEAK_GBS,
+                                   "fetch_bytes_per_transition": wrec["walk_fetch_bytes_per_transition"],
+                                   "l2_hit_rate": wrec.get("walk_l2_hit_rate")}
     rec = traffic_record(wl.name)
     if rec:
         # counter-measured bytes of one call over the step time measured here: the HBM rate the
