@@ -202,3 +202,59 @@ def test_storage_ops_full_size(gs, oracle, big):
     untouched = torch.ones(n, dtype=torch.bool, device=DEV)
     untouched[u[:k].long()] = False
     assert torch.equal(table[untouched], before[untouched])
+
+
+def test_line_first_order_and_optimizer_steps_full_batch(gs, oracle, big):
+    """At the full batch size of the benchmark (2,000,000 pairs over 4 M rows of 128 floats), each
+    recomputed whole by the oracle: a first-order LINE iteration on sorted sampled edges, a
+    momentum iteration and an Adam iteration on the same batch."""
+    wl, g, off, nb, _, _ = big
+    from paper_2407_15452_amd import inputs
+    n, d, B, K = wl.num_nodes, wl.dim, wl.batch_pairs, wl.num_neg
+    c_raw, o_raw = gs.gs_sample_edges(g, None, B, seed=61)
+    c, o = gs.gs_sort_pairs(c_raw, o_raw, n)
+    want_c, want_o = oracle.sort_pairs(c_raw.cpu().numpy(), o_raw.cpu().numpy(), n)
+    np.testing.assert_array_equal(c.cpu().numpy(), want_c)
+    np.testing.assert_array_equal(o.cpu().numpy(), want_o)
+    negs = gs.gs_sample_negatives(None, n, B, K, seed=62, device=DEV)
+    hc, ho, hn = c.cpu().numpy(), o.cpu().numpy(), negs.cpu().numpy()
+
+    w = inputs.random_tables(n, d, seed=7, scale=0.15, device=DEV)[0]
+    h_w = w.cpu().numpy()
+    loss = gs.gs_line1_step(w, c, o, negs, 0.025)
+    want = oracle.line1_step(h_w, hc, ho, hn, 0.025)
+    assert abs(float(loss.item()) - want) <= 1e-5 * abs(want)
+    assert np.abs(w.cpu().numpy() - h_w).max() <= 1e-5
+    del w, h_w
+
+    tabs = list(inputs.random_tables(n, d, seed=8, scale=0.15, device=DEV))
+    tabs += list(inputs.random_tables(n, d, seed=9, scale=0.01, device=DEV))
+    host = [t.cpu().numpy() for t in tabs]
+    loss = gs.gs_sgns_momentum_step(*tabs, c, o, negs, 0.025, 0.9)
+    want = oracle.sgns_momentum_step(*host, hc, ho, hn, 0.025, 0.9)
+    assert abs(float(loss.item()) - want) <= 1e-5 * abs(want)
+    for t, h in zip(tabs, host):
+        assert (np.abs(t.cpu().numpy() - h) <= 1e-5 + 1e-6 * np.abs(h)).all()
+
+    # Adam, first iteration (moments from zero), on the model the momentum step left (the
+    # oracle's copy on both sides)
+    for t, h in zip(tabs[:2], host[:2]):
+        t.copy_(torch.from_numpy(h))
+    tabs = tabs[:2] + [torch.zeros_like(tabs[0]) for _ in range(4)]
+    host = host[:2] + [np.zeros_like(host[0]) for _ in range(4)]
+    before = [h.copy() for h in host[:2]]
+    loss = gs.gs_sgns_adam_step(*tabs, c, o, negs, 0.01, 0.9, 0.999, 1e-8, 1)
+    want = oracle.sgns_adam_step(*host, hc, ho, hn, 0.01, 0.9, 0.999, 1e-8, 1)
+    assert abs(float(loss.item()) - want) <= 1e-5 * abs(want)
+    got = [t.cpu().numpy() for t in tabs]
+    for which in (2, 3, 4, 5):
+        assert (np.abs(got[which] - host[which]) <= 1e-6 + 1e-5 * np.abs(host[which])).all()
+    step = np.float64(np.float32(0.01)) / (1.0 - np.float64(np.float32(0.9)))
+    root = np.sqrt(1.0 - np.float64(np.float32(0.999)))
+    for which in (0, 1):
+        safe = (np.sqrt(host[which + 4].astype(np.float64)) / root + 1e-8) >= 1e-3
+        assert np.abs(got[which] - host[which])[safe].max() <= 1e-5
+        assert np.abs(got[which] - host[which]).max() <= 2.0 * step + 1e-5
+        m, v = got[which + 2].astype(np.float64), got[which + 4].astype(np.float64)
+        expect = before[which] - step * m / (np.sqrt(v) / root + np.float64(np.float32(1e-8)))
+        assert np.abs(got[which] - expect).max() <= 1e-6
