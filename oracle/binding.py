@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gs_oracle.cpp")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 SYMMETRIZE, DROP_SELF_LOOPS, DEDUPE = 1, 2, 4
 
 
@@ -52,6 +52,8 @@ def _load():
                      "oracle_table_mult_add", "oracle_sort_pairs"):
             getattr(_lib, name).restype = C.c_int32
         _lib.oracle_philox4x32_10.restype = None
+        _lib.oracle_f16_to_float.restype = None
+        _lib.oracle_float_to_f16.restype = None
     return _lib
 
 
@@ -340,3 +342,17 @@ def sort_pairs(centers, contexts, num_nodes):
                                    _ptr(oc), _ptr(oo))
     _check(rc, "oracle_sort_pairs")
     return oc[:n], oo[:n]
+
+
+def f16_to_float(bits):
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    out = np.zeros(bits.shape, dtype=np.float32)
+    _load().oracle_f16_to_float(_ptr(bits), C.c_int64(bits.size), _ptr(out))
+    return out
+
+
+def float_to_f16(values):
+    values = np.ascontiguousarray(values, dtype=np.float32)
+    out = np.zeros(values.shape, dtype=np.uint16)
+    _load().oracle_float_to_f16(_ptr(values), C.c_int64(values.size), _ptr(out))
+    return out

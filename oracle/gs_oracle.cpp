@@ -53,7 +53,7 @@ typedef struct {
 
 enum { ORACLE_OK = 0, ORACLE_EINVAL = -1, ORACLE_EOVERFLOW = -3 };
 enum { ORACLE_SYMMETRIZE = 1, ORACLE_DROP_SELF_LOOPS = 2, ORACLE_DEDUPE = 4 };
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
 
 }  // extern "C"
 
@@ -137,6 +137,36 @@ uint16_t float_to_bf16(float f) {
   return (uint16_t)(bits >> 16);
 }
 
+// IEEE binary16 (1 sign, 5 exponent, 10 fraction bits), widened exactly
+float f16_to_float(uint16_t h) {
+  const int sign = (h >> 15) & 1, ex = (h >> 10) & 31, frac = h & 1023;
+  double v;
+  if (ex == 0) v = std::ldexp((double)frac, -24);                       // subnormal
+  else if (ex == 31) v = frac ? std::nan("") : INFINITY;
+  else v = std::ldexp(1.0 + (double)frac / 1024.0, ex - 15);
+  return (float)(sign ? -v : v);
+}
+
+// fp32 -> binary16, round to nearest even (overflow to infinity)
+uint16_t float_to_f16(float f) {
+  const uint16_t sign = std::signbit(f) ? 0x8000u : 0u;
+  const double a = std::fabs((double)f);
+  if (std::isnan(f)) return (uint16_t)(sign | 0x7e00u);
+  if (a == 0.0) return sign;
+  if (std::isinf(f)) return (uint16_t)(sign | 0x7c00u);
+  int ex;
+  std::frexp(a, &ex);                          // a = m * 2^ex, m in [0.5, 1)
+  int e = ex - 1;                              // a = 1.xxx * 2^e
+  if (e < -14) {                               // subnormal range: units of 2^-24
+    const double q = std::nearbyint(std::ldexp(a, 24));
+    return (uint16_t)(sign | (uint16_t)q);     // q == 1024 is the smallest normal number
+  }
+  double q = std::nearbyint(std::ldexp(a, 10 - e));   // in [1024, 2048]
+  if (q == 2048.0) { q = 1024.0; ++e; }
+  if (e > 15) return (uint16_t)(sign | 0x7c00u);
+  return (uint16_t)(sign | ((uint16_t)(e + 15) << 10) | (uint16_t)(q - 1024.0));
+}
+
 double softplus(double z) {  // log(1 + exp(z)), stable for both signs
   return std::max(z, 0.0) + std::log1p(std::exp(-std::fabs(z)));
 }
@@ -149,11 +179,13 @@ double sigmoid(double z) {
 
 double read_elem(const void* table, int32_t dtype, int32_t dim, int64_t row, int32_t e) {
   if (dtype == ORACLE_F32) return (double)((const float*)table)[row * dim + e];
+  if (dtype == ORACLE_F16) return (double)f16_to_float(((const uint16_t*)table)[row * dim + e]);
   return (double)bf16_to_float(((const uint16_t*)table)[row * dim + e]);
 }
 
 void write_elem(void* table, int32_t dtype, int32_t dim, int64_t row, int32_t e, double value) {
   if (dtype == ORACLE_F32) ((float*)table)[row * dim + e] = (float)value;
+  else if (dtype == ORACLE_F16) ((uint16_t*)table)[row * dim + e] = float_to_f16((float)value);
   else ((uint16_t*)table)[row * dim + e] = float_to_bf16((float)value);
 }
 
@@ -515,7 +547,7 @@ int32_t oracle_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int32_t dim
                          const int32_t* centers, const int32_t* contexts, const int32_t* negs,
                          int64_t num_pairs, int32_t k, float lr, double* loss_sum_out) {
   if (!w_in || !w_out || num_nodes < 1 || dim < 1 || num_pairs < 0 || k < 0) return ORACLE_EINVAL;
-  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_EINVAL;
+  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F16) return ORACLE_EINVAL;
   if (num_pairs > 0 && (!centers || !contexts || (k > 0 && !negs))) return ORACLE_EINVAL;
   if (!loss_sum_out) return ORACLE_EINVAL;
   RowSums d_in, d_out;
@@ -550,7 +582,7 @@ int32_t oracle_sgns_momentum_step(void* w_in, void* w_out, void* m_in, void* m_o
                                   float mu, double* loss_sum_out) {
   if (!w_in || !w_out || !m_in || !m_out || num_nodes < 1 || dim < 1 || num_pairs < 0 || k < 0)
     return ORACLE_EINVAL;
-  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_EINVAL;
+  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F16) return ORACLE_EINVAL;
   if (num_pairs > 0 && (!centers || !contexts || (k > 0 && !negs))) return ORACLE_EINVAL;
   if (!loss_sum_out) return ORACLE_EINVAL;
   RowSums d_in, d_out;
@@ -592,7 +624,7 @@ int32_t oracle_line1_step(void* w, int64_t num_nodes, int32_t dim, int32_t dtype
                           const int32_t* sources, const int32_t* targets, const int32_t* negs,
                           int64_t num_pairs, int32_t k, float lr, double* loss_sum_out) {
   if (!w || num_nodes < 1 || dim < 1 || num_pairs < 0 || k < 0 || !loss_sum_out) return ORACLE_EINVAL;
-  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_EINVAL;
+  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F16) return ORACLE_EINVAL;
   if (num_pairs > 0 && (!sources || !targets || (k > 0 && !negs))) return ORACLE_EINVAL;
   RowSums as_source, as_other;
   int32_t rc = sgns_gradients(w, w, num_nodes, dim, dtype, sources, targets, negs, num_pairs, k,
@@ -695,7 +727,7 @@ int32_t oracle_unique_ids(const int32_t* ids, int64_t n, int64_t num_nodes, int3
 int32_t oracle_get_rows(const void* table, int64_t num_nodes, int32_t dim, int32_t dtype,
                         const int32_t* ids, int64_t n, float* out) {
   if (!table || num_nodes < 1 || dim < 1 || n < 0 || (n > 0 && (!ids || !out))) return ORACLE_EINVAL;
-  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_EINVAL;
+  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F16) return ORACLE_EINVAL;
   for (int64_t i = 0; i < n; ++i)
     for (int32_t e = 0; e < dim; ++e) {
       const bool ok = ids[i] >= 0 && (int64_t)ids[i] < num_nodes;
@@ -709,7 +741,7 @@ int32_t oracle_get_rows(const void* table, int64_t num_nodes, int32_t dim, int32
 int32_t oracle_put_rows(void* table, int64_t num_nodes, int32_t dim, int32_t dtype, const int32_t* ids,
                         int64_t n, const float* rows, float scale) {
   if (!table || num_nodes < 1 || dim < 1 || n < 0 || (n > 0 && (!ids || !rows))) return ORACLE_EINVAL;
-  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_EINVAL;
+  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F16) return ORACLE_EINVAL;
   std::vector<int32_t> seen(ids, ids + n);
   std::sort(seen.begin(), seen.end());
   for (size_t j = 1; j < seen.size(); ++j)
@@ -729,7 +761,7 @@ int32_t oracle_put_rows(void* table, int64_t num_nodes, int32_t dim, int32_t dty
 // for two tables of the same shape.  One rounding per element.
 int32_t oracle_table_mult(void* table, int64_t num_nodes, int32_t dim, int32_t dtype, float factor) {
   if (!table || num_nodes < 1 || dim < 1) return ORACLE_EINVAL;
-  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_EINVAL;
+  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F16) return ORACLE_EINVAL;
   for (int64_t r = 0; r < num_nodes; ++r)
     for (int32_t e = 0; e < dim; ++e)
       write_elem(table, dtype, dim, r, e, (double)factor * read_elem(table, dtype, dim, r, e));
@@ -739,7 +771,7 @@ int32_t oracle_table_mult(void* table, int64_t num_nodes, int32_t dim, int32_t d
 int32_t oracle_table_mult_add(void* dst, const void* src, int64_t num_nodes, int32_t dim,
                               int32_t dtype, float factor) {
   if (!dst || !src || num_nodes < 1 || dim < 1) return ORACLE_EINVAL;
-  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_EINVAL;
+  if (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F16) return ORACLE_EINVAL;
   for (int64_t r = 0; r < num_nodes; ++r)
     for (int32_t e = 0; e < dim; ++e)
       write_elem(dst, dtype, dim, r, e,
@@ -768,6 +800,15 @@ int32_t oracle_sort_pairs(const int32_t* centers, const int32_t* contexts, int64
     contexts_out[j] = contexts[order[(size_t)j]];
   }
   return ORACLE_OK;
+}
+
+
+// binary16 conversions, exported for their pins
+void oracle_f16_to_float(const uint16_t* in, int64_t n, float* out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = f16_to_float(in[i]);
+}
+void oracle_float_to_f16(const float* in, int64_t n, uint16_t* out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = float_to_f16(in[i]);
 }
 
 }  // extern "C"

@@ -183,6 +183,41 @@ def test_bf16_tables_round_to_nearest_even_once(oracle):
     assert torch.equal(got_in, want_in) and torch.equal(got_out, want_out)
 
 
+def test_f16_conversions_match_numpy(oracle):
+    """binary16 storage: every bit pattern widens as numpy's float16 does; fp32 -> binary16
+    rounds to nearest even like numpy, subnormals, ties, overflow and signed zero included."""
+    bits = np.arange(65536, dtype=np.uint16)
+    got = oracle.f16_to_float(bits)
+    want = bits.view(np.float16).astype(np.float32)
+    finite = np.isfinite(want)
+    np.testing.assert_array_equal(got[finite], want[finite])
+    np.testing.assert_array_equal(np.isnan(got), np.isnan(want))
+    np.testing.assert_array_equal(got[np.isinf(want)], want[np.isinf(want)])
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.normal(0, 1, 100_000), rng.normal(0, 1e-6, 50_000),
+                        rng.normal(0, 3e4, 50_000),
+                        [0.0, -0.0, 65504, 65519.99, 65520, 1e9, -1e9, 6e-8, 2.98e-8, 2.9802322e-8,
+                         5.96e-8, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, np.inf, -np.inf]]).astype(np.float32)
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).view(np.uint16)
+    np.testing.assert_array_equal(oracle.float_to_f16(x), want)
+
+
+def test_f16_tables_round_to_nearest_even_once(oracle):
+    rng = np.random.default_rng(14)
+    n, d, b, k, lr = 20, 8, 100, 4, 0.05
+    f_in = rng.normal(0, 0.5, (n, d)).astype(np.float16)
+    f_out = rng.normal(0, 0.5, (n, d)).astype(np.float16)
+    c, o, neg = _batch(rng, n, b, k)
+    bits_in, bits_out = f_in.view(np.uint16).copy(), f_out.view(np.uint16).copy()
+    w_in, w_out = f_in.astype(np.float32), f_out.astype(np.float32)   # exactly widened copies
+    l32 = oracle.sgns_step(w_in, w_out, c, o, neg, lr)
+    l16 = oracle.sgns_step(bits_in, bits_out, c, o, neg, lr, dtype=oracle.F16)
+    assert l16 == l32
+    np.testing.assert_array_equal(bits_in, w_in.astype(np.float16).view(np.uint16))
+    np.testing.assert_array_equal(bits_out, w_out.astype(np.float16).view(np.uint16))
+
+
 # ----------------------------------------------------------------------------- SGD with momentum
 def test_momentum_step_matches_torch_sgd(oracle):
     """mult / put / mult_add (GraphScale §3.2) is torch.optim.SGD(momentum=mu) on the dense
