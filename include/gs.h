@@ -54,7 +54,7 @@ typedef enum {
 } gs_status;
 
 enum { GS_SYMMETRIZE = 1, GS_DROP_SELF_LOOPS = 2, GS_DEDUPE = 4 };
-enum { GS_F32 = 0, GS_BF16 = 1 };
+enum { GS_F32 = 0, GS_BF16 = 1, GS_F16 = 2 };  /* table storage: float, bfloat16, IEEE binary16 */
 
 /* Graph topology in CSR form; every row sorted ascending by neighbour id. */
 typedef struct {
@@ -208,8 +208,10 @@ int32_t gs_sample_edges(const gs_csr* g, const gs_alias* edge_alias, int64_t num
  * gs_sgns_step -- one training iteration of Sec. 3.2: fetch the batch's rows,
  * loss and sparse gradient on them, write those rows back; reads see the
  * tables as they were before the call (the barrier of "Synchronization").
- *   w_in, w_out  [num_nodes][dim] row-major, float (GS_F32) or bfloat16
- *   (GS_BF16, fp32 arithmetic), updated in place.
+ *   w_in, w_out  [num_nodes][dim] row-major, float (GS_F32), bfloat16 (GS_BF16)
+ *   or IEEE binary16 (GS_F16; Sec. 4.2 keeps the industry-scale table in fp16);
+ *   the 16-bit formats are widened exactly and computed on in fp32.  Updated in
+ *   place.
  *   For pair i: u = w_in[centers[i]], v_0 = w_out[contexts[i]], v_j =
  *   w_out[negs[i][j-1]], x_j = <u, v_j>; loss_i = softplus(-x_0) + sum_j
  *   softplus(x_j); g_0 = sigmoid(x_0) - 1, g_j = sigmoid(x_j);
@@ -218,7 +220,7 @@ int32_t gs_sample_edges(const gs_csr* g, const gs_alias* edge_alias, int64_t num
  *   the sum of loss_i (overwritten).
  *   Every touched element is written once, as round(old + delta) with delta
  *   summed in fp32 (bf16: round to nearest even).
- *   dim must be a multiple of 4 (fp32) or 8 (bf16) and at most 1024; k <= 60;
+ *   dim must be a multiple of 4 (fp32) or 8 (16-bit) and at most 1024; k <= 60;
  *   num_pairs * (k+1) < 2^31.  Rows that the batch does not name are not
  *   touched.  w_in and w_out must be two tables (GS_EINVAL if they are the
  *   same address).  The ids live on the device and are checked there: an id

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libgs.so")
 
 GS_OK, GS_EINVAL, GS_EWORKSPACE, GS_EOVERFLOW, GS_EHIP = 0, -1, -2, -3, -4
 GS_SYMMETRIZE, GS_DROP_SELF_LOOPS, GS_DEDUPE = 1, 2, 4
-GS_F32, GS_BF16 = 0, 1
+GS_F32, GS_BF16, GS_F16 = 0, 1, 2
 
 EXPORTS = (
     "gs_last_hip_error",
@@ -272,7 +272,7 @@ def gs_sgns_step_workspace_bytes(num_pairs: int, num_nodes: int, k: int, dim: in
 
 def gs_sgns_step(w_in, w_out, centers, contexts, negs, lr: float, loss_out=None, ws=None):
     """Updates w_in / w_out in place; returns the device scalar holding the summed loss."""
-    dtype = GS_BF16 if w_in.dtype == torch.bfloat16 else GS_F32
+    dtype = _table_dtype(w_in)
     num_nodes, dim = int(w_in.shape[0]), int(w_in.shape[1])
     num_pairs = int(centers.numel())
     k = int(negs.shape[1]) if negs.dim() == 2 else 0
@@ -296,7 +296,7 @@ def gs_sgns_step(w_in, w_out, centers, contexts, negs, lr: float, loss_out=None,
 def gs_sgns_momentum_step(w_in, w_out, m_in, m_out, centers, contexts, negs, lr: float, mu: float,
                           loss_out=None, ws=None):
     """SGD-with-momentum iteration (see gs.h); the four tables are updated in place."""
-    dtype = GS_BF16 if w_in.dtype == torch.bfloat16 else GS_F32
+    dtype = _table_dtype(w_in)
     num_nodes, dim = int(w_in.shape[0]), int(w_in.shape[1])
     num_pairs = int(centers.numel())
     k = int(negs.shape[1]) if negs.dim() == 2 else 0
@@ -339,7 +339,13 @@ def gs_unique_ids(ids, num_nodes: int, want_inverse: bool = True, ws=None):
 
 
 def _table_dtype(table):
-    return GS_BF16 if table.dtype == torch.bfloat16 else GS_F32
+    if table.dtype == torch.float32:
+        return GS_F32
+    if table.dtype == torch.bfloat16:
+        return GS_BF16
+    if table.dtype == torch.float16:
+        return GS_F16
+    raise TypeError(f"tables are float32, bfloat16 or float16, not {table.dtype}")
 
 
 def gs_get_rows(table, ids, count=None, out=None):
@@ -399,7 +405,7 @@ def gs_sgns_step_fused_workspace_bytes(num_pairs: int, num_nodes: int, k: int, d
 def gs_sgns_step_fused(w_in, w_out, centers, contexts, noise, k: int, neg_seed: int, lr: float,
                        pair_index_base: int = 0, loss_out=None, ws=None):
     """gs_sample_negatives + gs_sgns_step in one call; returns the device loss scalar."""
-    dtype = GS_BF16 if w_in.dtype == torch.bfloat16 else GS_F32
+    dtype = _table_dtype(w_in)
     num_nodes, dim = int(w_in.shape[0]), int(w_in.shape[1])
     num_pairs = int(centers.numel())
     dev = w_in.device
@@ -425,7 +431,7 @@ def gs_line1_step_workspace_bytes(num_pairs: int, num_nodes: int, k: int, dim: i
 
 def gs_line1_step(w, sources, targets, negs, lr: float, loss_out=None, ws=None):
     """First-order LINE iteration on the single table w, in place; returns the device loss scalar."""
-    dtype = GS_BF16 if w.dtype == torch.bfloat16 else GS_F32
+    dtype = _table_dtype(w)
     num_nodes, dim = int(w.shape[0]), int(w.shape[1])
     num_pairs = int(sources.numel())
     k = int(negs.shape[1]) if negs.dim() == 2 else 0

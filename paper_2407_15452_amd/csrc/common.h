@@ -1,6 +1,7 @@
 // Shared host/device helpers of libgs (gfx950 only).
 #pragma once
 
+#include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
@@ -104,6 +105,38 @@ __device__ __forceinline__ int64_t table_draw(const float* __restrict__ prob,
     if (!(unit_float(b.x2) < prob[s])) s = (int64_t)alias[s];
   }
   return s;
+}
+
+// 16-bit storage formats of the embedding tables.  lo / hi widen the two halves of a
+// 32-bit word exactly; round() gives the 16 bits nearest to an fp32 value (ties to even).
+struct bf16_t {
+  uint16_t bits;
+  static __device__ __forceinline__ float lo(uint32_t w) { return __uint_as_float(w << 16); }
+  static __device__ __forceinline__ float hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+  static __device__ __forceinline__ uint32_t round(float f) {      // finite inputs
+    const uint32_t b = __float_as_uint(f);
+    return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
+  }
+};
+struct f16_t {                                                      // IEEE binary16
+  uint16_t bits;
+  static __device__ __forceinline__ float lo(uint32_t w) {
+    return __half2float(__ushort_as_half((unsigned short)(w & 0xffffu)));
+  }
+  static __device__ __forceinline__ float hi(uint32_t w) {
+    return __half2float(__ushort_as_half((unsigned short)(w >> 16)));
+  }
+  static __device__ __forceinline__ uint32_t round(float f) {
+    // The value is an fp32 result first and becomes 16 bits by a second rounding.  Left to
+    // itself the compiler may merge the producing multiply / add into one mixed-precision
+    // instruction that rounds the exact result once, which gives other bits on ties.
+    asm("" : "+v"(f));
+    return (uint32_t)__half_as_ushort(__float2half_rn(f));
+  }
+};
+template <typename T>
+__device__ __forceinline__ uint32_t pack16(float lo, float hi) {
+  return T::round(lo) | (T::round(hi) << 16);
 }
 
 template <typename OffT>

@@ -58,7 +58,6 @@ constexpr int kHotBits = 8;                      // block-local rank counters in
 constexpr int kHotSlots = 1 << kHotBits;
 constexpr uint32_t kRankPending = 0x80000000u;   // rank still relative to the block (ranks < 2^31)
 
-typedef uint16_t bf16_t;           // bfloat16 storage
 
 struct Term {      // one (pair, j) contribution to a context-table row
   int32_t row;
@@ -137,29 +136,20 @@ __device__ __forceinline__ float row_sum16(float x) {
   return x;
 }
 
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-// round-to-nearest-even fp32 -> bf16 bits (finite inputs)
-__device__ __forceinline__ uint32_t to_bf16(float f) {
-  const uint32_t b = __float_as_uint(f);
-  return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
-}
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  return to_bf16(lo) | (to_bf16(hi) << 16);
-}
+// every table type other than float is one of the 16-bit formats (bf16_t, f16_t)
+template <typename T>
+using if_16bit = std::enable_if_t<!std::is_same<T, float>::value, int>;
 
 // Register image of a row: VPL float4 per lane.  Register v of lane l holds the
 // elements [4q, 4q+4) with q = natural_q(v, l):
 //   fp32 rows   one float4 per 16-byte load,  q = v*16 + l
-//   bf16 rows   two float4 per 16-byte load (8 elements), q = 2*((v/2)*16 + l) + (v&1)
+//   16-bit rows two float4 per 16-byte load (8 elements), q = 2*((v/2)*16 + l) + (v&1)
 template <typename T>
-__device__ __forceinline__ int natural_q(int v, int l16);
-template <>
-__device__ __forceinline__ int natural_q<float>(int v, int l16) { return v * kGroupLanes + l16; }
-template <>
-__device__ __forceinline__ int natural_q<bf16_t>(int v, int l16) {
+__device__ __forceinline__ int natural_q(int v, int l16) {
   return 2 * ((v >> 1) * kGroupLanes + l16) + (v & 1);
 }
+template <>
+__device__ __forceinline__ int natural_q<float>(int v, int l16) { return v * kGroupLanes + l16; }
 
 template <int VPL>
 __device__ __forceinline__ void zero(float4 (&a)[VPL]) {
@@ -179,10 +169,10 @@ __device__ __forceinline__ void load_row(const float* __restrict__ table, int64_
   }
 }
 
-template <int VPL>
-__device__ __forceinline__ void load_row(const bf16_t* __restrict__ table, int64_t row, int dim,
+template <int VPL, typename T, if_16bit<T> = 0>
+__device__ __forceinline__ void load_row(const T* __restrict__ table, int64_t row, int dim,
                                          int l16, float4 (&r)[VPL]) {
-  static_assert(VPL % 2 == 0, "bf16 rows are held as pairs of float4");
+  static_assert(VPL % 2 == 0, "16-bit rows are held as pairs of float4");
   const uint4* p = reinterpret_cast<const uint4*>(table + row * (int64_t)dim);
   const int chunks = dim >> 3;
 #pragma unroll
@@ -190,8 +180,8 @@ __device__ __forceinline__ void load_row(const bf16_t* __restrict__ table, int64
     const int c = w * kGroupLanes + l16;
     if (c < chunks) {
       const uint4 x = p[c];
-      r[2 * w] = make_float4(bf16_lo(x.x), bf16_hi(x.x), bf16_lo(x.y), bf16_hi(x.y));
-      r[2 * w + 1] = make_float4(bf16_lo(x.z), bf16_hi(x.z), bf16_lo(x.w), bf16_hi(x.w));
+      r[2 * w] = make_float4(T::lo(x.x), T::hi(x.x), T::lo(x.y), T::hi(x.y));
+      r[2 * w + 1] = make_float4(T::lo(x.z), T::hi(x.z), T::lo(x.w), T::hi(x.w));
     } else {
       r[2 * w] = make_float4(0.f, 0.f, 0.f, 0.f);
       r[2 * w + 1] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -213,8 +203,8 @@ __device__ __forceinline__ void store_row_sum(float* __restrict__ table, int64_t
   }
 }
 
-template <int VPL>
-__device__ __forceinline__ void store_row_sum(bf16_t* __restrict__ table, int64_t row, int dim, int l16,
+template <int VPL, typename T, if_16bit<T> = 0>
+__device__ __forceinline__ void store_row_sum(T* __restrict__ table, int64_t row, int dim, int l16,
                                               const float4 (&old)[VPL], const float4 (&d)[VPL]) {
   uint4* p = reinterpret_cast<uint4*>(table + row * (int64_t)dim);
   const int chunks = dim >> 3;
@@ -224,10 +214,10 @@ __device__ __forceinline__ void store_row_sum(bf16_t* __restrict__ table, int64_
     if (c < chunks) {
       const float4 a = old[2 * w], b = old[2 * w + 1], da = d[2 * w], db = d[2 * w + 1];
       uint4 x;
-      x.x = pack_bf16(a.x + da.x, a.y + da.y);
-      x.y = pack_bf16(a.z + da.z, a.w + da.w);
-      x.z = pack_bf16(b.x + db.x, b.y + db.y);
-      x.w = pack_bf16(b.z + db.z, b.w + db.w);
+      x.x = pack16<T>(a.x + da.x, a.y + da.y);
+      x.y = pack16<T>(a.z + da.z, a.w + da.w);
+      x.z = pack16<T>(b.x + db.x, b.y + db.y);
+      x.w = pack16<T>(b.z + db.z, b.w + db.w);
       p[c] = x;
     }
   }
@@ -252,25 +242,23 @@ __device__ __forceinline__ void axpy(float4 (&acc)[VPL], float c, const float4 (
 }
 
 // A row as it was loaded, kept in as few registers as its storage type needs:
-// fp32 rows VPL float4, bf16 rows VPL/2 uint4 (widened element by element where
+// fp32 rows VPL float4, 16-bit rows VPL/2 uint4 (widened element by element where
 // they are used).  Rows that wait in registers for their turn are held this way,
-// so a bf16 group keeps twice as many of them in flight.
+// so a 16-bit group keeps twice as many of them in flight.
 template <typename T, int VPL>
-struct RawRow;
+struct RawRow { uint4 r[VPL / 2]; };
 template <int VPL>
 struct RawRow<float, VPL> { float4 r[VPL]; };
-template <int VPL>
-struct RawRow<bf16_t, VPL> { uint4 r[VPL / 2]; };
 
 template <int VPL>
 __device__ __forceinline__ void load_raw(const float* __restrict__ table, int64_t row, int dim, int l16,
                                          RawRow<float, VPL>& x) {
   load_row<VPL>(table, row, dim, l16, x.r);
 }
-template <int VPL>
-__device__ __forceinline__ void load_raw(const bf16_t* __restrict__ table, int64_t row, int dim, int l16,
-                                         RawRow<bf16_t, VPL>& x) {
-  static_assert(VPL % 2 == 0, "bf16 rows are held as pairs of float4");
+template <int VPL, typename T, if_16bit<T> = 0>
+__device__ __forceinline__ void load_raw(const T* __restrict__ table, int64_t row, int dim, int l16,
+                                         RawRow<T, VPL>& x) {
+  static_assert(VPL % 2 == 0, "16-bit rows are held as pairs of float4");
   const uint4* p = reinterpret_cast<const uint4*>(table + row * (int64_t)dim);
   const int chunks = dim >> 3;
 #pragma unroll
@@ -291,9 +279,9 @@ __device__ __forceinline__ void store_raw(float* __restrict__ table, int64_t row
     if (q < dim4) p[q] = x.r[v];
   }
 }
-template <int VPL>
-__device__ __forceinline__ void store_raw(bf16_t* __restrict__ table, int64_t row, int dim, int l16,
-                                          const RawRow<bf16_t, VPL>& x) {
+template <int VPL, typename T, if_16bit<T> = 0>
+__device__ __forceinline__ void store_raw(T* __restrict__ table, int64_t row, int dim, int l16,
+                                          const RawRow<T, VPL>& x) {
   uint4* p = reinterpret_cast<uint4*>(table + row * (int64_t)dim);
   const int chunks = dim >> 3;
 #pragma unroll
@@ -303,12 +291,12 @@ __device__ __forceinline__ void store_raw(bf16_t* __restrict__ table, int64_t ro
   }
 }
 
-// Between two uses of a raw bf16 row: makes the compiler widen it again at the
+// Between two uses of a raw 16-bit row: makes the compiler widen it again at the
 // second use instead of keeping the widened copy (twice the registers) alive.
 template <int VPL>
 __device__ __forceinline__ void rewiden_later(RawRow<float, VPL>&) {}
-template <int VPL>
-__device__ __forceinline__ void rewiden_later(RawRow<bf16_t, VPL>& x) {
+template <int VPL, typename T, if_16bit<T> = 0>
+__device__ __forceinline__ void rewiden_later(RawRow<T, VPL>& x) {
 #pragma unroll
   for (int w = 0; w < VPL / 2; ++w)
     asm volatile("" : "+v"(x.r[w].x), "+v"(x.r[w].y), "+v"(x.r[w].z), "+v"(x.r[w].w));
@@ -318,16 +306,16 @@ template <int VPL>
 __device__ __forceinline__ float dot_partial(const float4 (&a)[VPL], const RawRow<float, VPL>& b) {
   return dot_partial<VPL>(a, b.r);
 }
-template <int VPL>
-__device__ __forceinline__ float dot_partial(const float4 (&a)[VPL], const RawRow<bf16_t, VPL>& b) {
+template <int VPL, typename T, if_16bit<T> = 0>
+__device__ __forceinline__ float dot_partial(const float4 (&a)[VPL], const RawRow<T, VPL>& b) {
   float s = 0.f;
 #pragma unroll
   for (int w = 0; w < VPL / 2; ++w) {
     const uint4 x = b.r[w];
-    s += a[2 * w].x * bf16_lo(x.x) + a[2 * w].y * bf16_hi(x.x) + a[2 * w].z * bf16_lo(x.y) +
-         a[2 * w].w * bf16_hi(x.y);
-    s += a[2 * w + 1].x * bf16_lo(x.z) + a[2 * w + 1].y * bf16_hi(x.z) + a[2 * w + 1].z * bf16_lo(x.w) +
-         a[2 * w + 1].w * bf16_hi(x.w);
+    s += a[2 * w].x * T::lo(x.x) + a[2 * w].y * T::hi(x.x) + a[2 * w].z * T::lo(x.y) +
+         a[2 * w].w * T::hi(x.y);
+    s += a[2 * w + 1].x * T::lo(x.z) + a[2 * w + 1].y * T::hi(x.z) + a[2 * w + 1].z * T::lo(x.w) +
+         a[2 * w + 1].w * T::hi(x.w);
   }
   return s;
 }
@@ -336,15 +324,15 @@ template <int VPL>
 __device__ __forceinline__ void axpy(float4 (&acc)[VPL], float c, const RawRow<float, VPL>& x) {
   axpy<VPL>(acc, c, x.r);
 }
-template <int VPL>
-__device__ __forceinline__ void axpy(float4 (&acc)[VPL], float c, const RawRow<bf16_t, VPL>& b) {
+template <int VPL, typename T, if_16bit<T> = 0>
+__device__ __forceinline__ void axpy(float4 (&acc)[VPL], float c, const RawRow<T, VPL>& b) {
 #pragma unroll
   for (int w = 0; w < VPL / 2; ++w) {
     const uint4 x = b.r[w];
-    acc[2 * w].x += c * bf16_lo(x.x); acc[2 * w].y += c * bf16_hi(x.x);
-    acc[2 * w].z += c * bf16_lo(x.y); acc[2 * w].w += c * bf16_hi(x.y);
-    acc[2 * w + 1].x += c * bf16_lo(x.z); acc[2 * w + 1].y += c * bf16_hi(x.z);
-    acc[2 * w + 1].z += c * bf16_lo(x.w); acc[2 * w + 1].w += c * bf16_hi(x.w);
+    acc[2 * w].x += c * T::lo(x.x); acc[2 * w].y += c * T::hi(x.x);
+    acc[2 * w].z += c * T::lo(x.y); acc[2 * w].w += c * T::hi(x.y);
+    acc[2 * w + 1].x += c * T::lo(x.z); acc[2 * w + 1].y += c * T::hi(x.z);
+    acc[2 * w + 1].z += c * T::lo(x.w); acc[2 * w + 1].w += c * T::hi(x.w);
   }
 }
 
@@ -795,11 +783,11 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
 
 // element-wise row helpers for the small follow-up kernels (natural order)
 __device__ __forceinline__ float elem_load(const float* row, int e) { return row[e]; }
-__device__ __forceinline__ float elem_load(const bf16_t* row, int e) {
-  return __uint_as_float((uint32_t)row[e] << 16);
-}
+template <typename T, if_16bit<T> = 0>
+__device__ __forceinline__ float elem_load(const T* row, int e) { return T::lo((uint32_t)row[e].bits); }
 __device__ __forceinline__ void elem_store(float* row, int e, float v) { row[e] = v; }
-__device__ __forceinline__ void elem_store(bf16_t* row, int e, float v) { row[e] = (bf16_t)to_bf16(v); }
+template <typename T, if_16bit<T> = 0>
+__device__ __forceinline__ void elem_store(T* row, int e, float v) { row[e].bits = (uint16_t)T::round(v); }
 
 // ---- long_rows: w_out[row] = round(old + side buffer) --------------------------------------
 // Side-buffer slot s belongs to the long row whose first term lies in
@@ -1017,14 +1005,15 @@ __global__ __launch_bounds__(256) void table_scale_kernel(float4* __restrict__ m
     m[i] = x;
   }
 }
-__global__ __launch_bounds__(256) void table_scale_kernel(uint4* __restrict__ m, int64_t n8, float mu) {
+template <typename T>
+__global__ __launch_bounds__(256) void table_scale16_kernel(uint4* __restrict__ m, int64_t n8, float mu) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8;
        i += (int64_t)gridDim.x * blockDim.x) {
     uint4 x = m[i];
-    x.x = pack_bf16(bf16_lo(x.x) * mu, bf16_hi(x.x) * mu);
-    x.y = pack_bf16(bf16_lo(x.y) * mu, bf16_hi(x.y) * mu);
-    x.z = pack_bf16(bf16_lo(x.z) * mu, bf16_hi(x.z) * mu);
-    x.w = pack_bf16(bf16_lo(x.w) * mu, bf16_hi(x.w) * mu);
+    x.x = pack16<T>(T::lo(x.x) * mu, T::hi(x.x) * mu);
+    x.y = pack16<T>(T::lo(x.y) * mu, T::hi(x.y) * mu);
+    x.z = pack16<T>(T::lo(x.z) * mu, T::hi(x.z) * mu);
+    x.w = pack16<T>(T::lo(x.w) * mu, T::hi(x.w) * mu);
     m[i] = x;
   }
 }
@@ -1040,17 +1029,18 @@ __global__ __launch_bounds__(256) void table_axpy_kernel(float4* __restrict__ w,
     w[i] = x;
   }
 }
-__global__ __launch_bounds__(256) void table_axpy_kernel(uint4* __restrict__ w,
-                                                         const uint4* __restrict__ m, int64_t n8,
-                                                         float lr) {
+template <typename T>
+__global__ __launch_bounds__(256) void table_axpy16_kernel(uint4* __restrict__ w,
+                                                           const uint4* __restrict__ m, int64_t n8,
+                                                           float lr) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8;
        i += (int64_t)gridDim.x * blockDim.x) {
     uint4 x = w[i];
     const uint4 y = m[i];
-    x.x = pack_bf16(bf16_lo(x.x) - lr * bf16_lo(y.x), bf16_hi(x.x) - lr * bf16_hi(y.x));
-    x.y = pack_bf16(bf16_lo(x.y) - lr * bf16_lo(y.y), bf16_hi(x.y) - lr * bf16_hi(y.y));
-    x.z = pack_bf16(bf16_lo(x.z) - lr * bf16_lo(y.z), bf16_hi(x.z) - lr * bf16_hi(y.z));
-    x.w = pack_bf16(bf16_lo(x.w) - lr * bf16_lo(y.w), bf16_hi(x.w) - lr * bf16_hi(y.w));
+    x.x = pack16<T>(T::lo(x.x) - lr * T::lo(y.x), T::hi(x.x) - lr * T::hi(y.x));
+    x.y = pack16<T>(T::lo(x.y) - lr * T::lo(y.y), T::hi(x.y) - lr * T::hi(y.y));
+    x.z = pack16<T>(T::lo(x.z) - lr * T::lo(y.z), T::hi(x.z) - lr * T::hi(y.z));
+    x.w = pack16<T>(T::lo(x.w) - lr * T::lo(y.w), T::hi(x.w) - lr * T::hi(y.w));
     w[i] = x;
   }
 }
@@ -1091,8 +1081,8 @@ static int32_t check_sgns_args(const void* w_in, const void* w_out, int64_t num_
                                const int32_t* negs, int64_t num_pairs, int32_t k,
                                const double* loss_sum_out, const void* ws, bool one_table = false) {
   if (!w_in || !w_out || num_nodes < 1 || num_nodes > (int64_t)INT32_MAX) return GS_EINVAL;
-  if (dtype != GS_F32 && dtype != GS_BF16) return GS_EINVAL;
-  const int granule = (dtype == GS_BF16) ? 8 : 4;   // elements per 16-byte piece
+  if (dtype != GS_F32 && dtype != GS_BF16 && dtype != GS_F16) return GS_EINVAL;
+  const int granule = (dtype == GS_F32) ? 4 : 8;   // elements per 16-byte piece
   if (dim < granule || dim > 1024 || (dim % granule) != 0) return GS_EINVAL;
   if (num_pairs < 0 || k < 0 || k > 60 || !loss_sum_out) return GS_EINVAL;
   if (num_pairs > 0 && (!centers || !contexts || (k > 0 && !negs))) return GS_EINVAL;
@@ -1175,11 +1165,17 @@ static int32_t run_sgns(void* w_in, void* w_out, void* dst_in, void* dst_out, in
     if (vpl <= 8) return launch_sgns<float, 8, 2, 2>(a, stream);
     return launch_sgns<float, 16, 1, 1>(a, stream);
   }
-  // bf16: a 16-byte piece is 8 elements = two float4, so the register count is even
-  if (vpl <= 2) return launch_sgns<bf16_t, 2, 6, 16>(a, stream);
-  if (vpl <= 4) return launch_sgns<bf16_t, 4, 6, 8>(a, stream);
-  if (vpl <= 8) return launch_sgns<bf16_t, 8, 4, 4>(a, stream);
-  return launch_sgns<bf16_t, 16, 2, 2>(a, stream);
+  // 16-bit rows: a 16-byte piece is 8 elements = two float4, so the register count is even
+  if (dtype == GS_BF16) {
+    if (vpl <= 2) return launch_sgns<bf16_t, 2, 6, 16>(a, stream);
+    if (vpl <= 4) return launch_sgns<bf16_t, 4, 6, 8>(a, stream);
+    if (vpl <= 8) return launch_sgns<bf16_t, 8, 4, 4>(a, stream);
+    return launch_sgns<bf16_t, 16, 2, 2>(a, stream);
+  }
+  if (vpl <= 2) return launch_sgns<f16_t, 2, 6, 16>(a, stream);
+  if (vpl <= 4) return launch_sgns<f16_t, 4, 6, 8>(a, stream);
+  if (vpl <= 8) return launch_sgns<f16_t, 8, 4, 4>(a, stream);
+  return launch_sgns<f16_t, 16, 2, 2>(a, stream);
 }
 
 }  // namespace gs
@@ -1253,7 +1249,7 @@ extern "C" int32_t gs_sgns_step_fused(void* w_in, void* w_out, int64_t num_nodes
 
 // workspace of the one-table step: the step's own, the copies of the input rows, the pair slots
 static size_t line1_snap_bytes(int64_t num_pairs, int32_t dim, int32_t dtype) {
-  return align_up((size_t)(num_pairs > 0 ? num_pairs : 1) * (size_t)dim * (dtype == GS_BF16 ? 2 : 4));
+  return align_up((size_t)(num_pairs > 0 ? num_pairs : 1) * (size_t)dim * (dtype == GS_F32 ? 4 : 2));
 }
 static size_t line1_slot_bytes(int64_t num_pairs) {
   return align_up((size_t)(num_pairs > 0 ? num_pairs : 1) * sizeof(int32_t));
@@ -1304,16 +1300,19 @@ extern "C" int32_t gs_sgns_momentum_step(void* w_in, void* w_out, void* m_in, vo
     return GS_EINVAL;
   SgnsPlan p = plan_sgns(ws, num_pairs, num_nodes, k, dim);
   if (ws_bytes < p.bytes) return GS_EWORKSPACE;
-  const int per16 = (dtype == GS_BF16) ? 8 : 4;
+  const int per16 = (dtype == GS_F32) ? 4 : 8;
   const int64_t pieces = num_nodes * (int64_t)dim / per16;
   const unsigned blocks = (unsigned)min((int64_t)(256 * 64), ceil_div(pieces, 256));
   // mult: momentum <- mu * momentum, every row
   if (dtype == GS_F32) {
     table_scale_kernel<<<blocks, 256, 0, stream>>>((float4*)m_in, pieces, mu);
     table_scale_kernel<<<blocks, 256, 0, stream>>>((float4*)m_out, pieces, mu);
+  } else if (dtype == GS_BF16) {
+    table_scale16_kernel<bf16_t><<<blocks, 256, 0, stream>>>((uint4*)m_in, pieces, mu);
+    table_scale16_kernel<bf16_t><<<blocks, 256, 0, stream>>>((uint4*)m_out, pieces, mu);
   } else {
-    table_scale_kernel<<<blocks, 256, 0, stream>>>((uint4*)m_in, pieces, mu);
-    table_scale_kernel<<<blocks, 256, 0, stream>>>((uint4*)m_out, pieces, mu);
+    table_scale16_kernel<f16_t><<<blocks, 256, 0, stream>>>((uint4*)m_in, pieces, mu);
+    table_scale16_kernel<f16_t><<<blocks, 256, 0, stream>>>((uint4*)m_out, pieces, mu);
   }
   GS_LAUNCH_CHECK();
   // put: momentum[rows of the batch] += gradient (the update machinery with step -1)
@@ -1329,9 +1328,12 @@ extern "C" int32_t gs_sgns_momentum_step(void* w_in, void* w_out, void* m_in, vo
   if (dtype == GS_F32) {
     table_axpy_kernel<<<blocks, 256, 0, stream>>>((float4*)w_in, (const float4*)m_in, pieces, lr);
     table_axpy_kernel<<<blocks, 256, 0, stream>>>((float4*)w_out, (const float4*)m_out, pieces, lr);
+  } else if (dtype == GS_BF16) {
+    table_axpy16_kernel<bf16_t><<<blocks, 256, 0, stream>>>((uint4*)w_in, (const uint4*)m_in, pieces, lr);
+    table_axpy16_kernel<bf16_t><<<blocks, 256, 0, stream>>>((uint4*)w_out, (const uint4*)m_out, pieces, lr);
   } else {
-    table_axpy_kernel<<<blocks, 256, 0, stream>>>((uint4*)w_in, (const uint4*)m_in, pieces, lr);
-    table_axpy_kernel<<<blocks, 256, 0, stream>>>((uint4*)w_out, (const uint4*)m_out, pieces, lr);
+    table_axpy16_kernel<f16_t><<<blocks, 256, 0, stream>>>((uint4*)w_in, (const uint4*)m_in, pieces, lr);
+    table_axpy16_kernel<f16_t><<<blocks, 256, 0, stream>>>((uint4*)w_out, (const uint4*)m_out, pieces, lr);
   }
   GS_LAUNCH_CHECK();
   return GS_OK;

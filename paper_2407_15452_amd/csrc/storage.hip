@@ -103,14 +103,8 @@ __device__ __forceinline__ int64_t live_count(int64_t n, const int64_t* count_de
   return c < 0 ? 0 : (c < n ? c : n);
 }
 
-__device__ __forceinline__ float widen_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float widen_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-__device__ __forceinline__ uint32_t round_bf16(float f) {   // nearest even, finite inputs
-  const uint32_t b = __float_as_uint(f);
-  return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
-}
 // round(old + scale * r): exact product and one rounding of the sum in fp64,
-// then to fp32 (and from there to bf16 for bf16 tables)
+// then to fp32 (and from there to the table's 16-bit format)
 __device__ __forceinline__ float sum_once(float old, float scale, float r) {
   return (float)((double)old + (double)scale * (double)r);
 }
@@ -129,7 +123,8 @@ __global__ __launch_bounds__(kRowThreads) void get_rows_f32_kernel(
     dst[q] = ok ? src[q] : make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
-__global__ __launch_bounds__(kRowThreads) void get_rows_bf16_kernel(
+template <typename T>
+__global__ __launch_bounds__(kRowThreads) void get_rows16_kernel(
     const uint16_t* __restrict__ table, int64_t num_nodes, int32_t dim, const int32_t* __restrict__ ids,
     int64_t n, const int64_t* __restrict__ count_dev, float* __restrict__ out) {
   const int l16 = threadIdx.x & (kRowLanes - 1);
@@ -141,8 +136,8 @@ __global__ __launch_bounds__(kRowThreads) void get_rows_bf16_kernel(
   float4* dst = reinterpret_cast<float4*>(out + i * (int64_t)dim);
   for (int c = l16; c < (dim >> 3); c += kRowLanes) {
     const uint4 x = ok ? src[c] : make_uint4(0u, 0u, 0u, 0u);
-    dst[2 * c] = make_float4(widen_lo(x.x), widen_hi(x.x), widen_lo(x.y), widen_hi(x.y));
-    dst[2 * c + 1] = make_float4(widen_lo(x.z), widen_hi(x.z), widen_lo(x.w), widen_hi(x.w));
+    dst[2 * c] = make_float4(T::lo(x.x), T::hi(x.x), T::lo(x.y), T::hi(x.y));
+    dst[2 * c + 1] = make_float4(T::lo(x.z), T::hi(x.z), T::lo(x.w), T::hi(x.w));
   }
 }
 
@@ -163,7 +158,8 @@ __global__ __launch_bounds__(kRowThreads) void put_rows_f32_kernel(
   }
 }
 
-__global__ __launch_bounds__(kRowThreads) void put_rows_bf16_kernel(
+template <typename T>
+__global__ __launch_bounds__(kRowThreads) void put_rows16_kernel(
     uint16_t* __restrict__ table, int64_t num_nodes, int32_t dim, const int32_t* __restrict__ ids,
     int64_t n, const int64_t* __restrict__ count_dev, const float* __restrict__ rows, float scale) {
   const int l16 = threadIdx.x & (kRowLanes - 1);
@@ -177,10 +173,10 @@ __global__ __launch_bounds__(kRowThreads) void put_rows_bf16_kernel(
     const uint4 o = dst[c];
     const float4 a = src[2 * c], b = src[2 * c + 1];
     uint4 x;
-    x.x = round_bf16(sum_once(widen_lo(o.x), scale, a.x)) | (round_bf16(sum_once(widen_hi(o.x), scale, a.y)) << 16);
-    x.y = round_bf16(sum_once(widen_lo(o.y), scale, a.z)) | (round_bf16(sum_once(widen_hi(o.y), scale, a.w)) << 16);
-    x.z = round_bf16(sum_once(widen_lo(o.z), scale, b.x)) | (round_bf16(sum_once(widen_hi(o.z), scale, b.y)) << 16);
-    x.w = round_bf16(sum_once(widen_lo(o.w), scale, b.z)) | (round_bf16(sum_once(widen_hi(o.w), scale, b.w)) << 16);
+    x.x = T::round(sum_once(T::lo(o.x), scale, a.x)) | (T::round(sum_once(T::hi(o.x), scale, a.y)) << 16);
+    x.y = T::round(sum_once(T::lo(o.y), scale, a.z)) | (T::round(sum_once(T::hi(o.y), scale, a.w)) << 16);
+    x.z = T::round(sum_once(T::lo(o.z), scale, b.x)) | (T::round(sum_once(T::hi(o.z), scale, b.y)) << 16);
+    x.w = T::round(sum_once(T::lo(o.w), scale, b.z)) | (T::round(sum_once(T::hi(o.w), scale, b.w)) << 16);
     dst[c] = x;
   }
 }
@@ -208,15 +204,16 @@ __global__ __launch_bounds__(256) void table_mult_f32_kernel(float4* __restrict_
     t[i] = x;
   }
 }
-__global__ __launch_bounds__(256) void table_mult_bf16_kernel(uint4* __restrict__ t, int64_t n8,
-                                                              float factor) {
+template <typename T>
+__global__ __launch_bounds__(256) void table_mult16_kernel(uint4* __restrict__ t, int64_t n8,
+                                                           float factor) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8;
        i += (int64_t)gridDim.x * blockDim.x) {
     uint4 x = t[i];
-    x.x = round_bf16(widen_lo(x.x) * factor) | (round_bf16(widen_hi(x.x) * factor) << 16);
-    x.y = round_bf16(widen_lo(x.y) * factor) | (round_bf16(widen_hi(x.y) * factor) << 16);
-    x.z = round_bf16(widen_lo(x.z) * factor) | (round_bf16(widen_hi(x.z) * factor) << 16);
-    x.w = round_bf16(widen_lo(x.w) * factor) | (round_bf16(widen_hi(x.w) * factor) << 16);
+    x.x = T::round(T::lo(x.x) * factor) | (T::round(T::hi(x.x) * factor) << 16);
+    x.y = T::round(T::lo(x.y) * factor) | (T::round(T::hi(x.y) * factor) << 16);
+    x.z = T::round(T::lo(x.z) * factor) | (T::round(T::hi(x.z) * factor) << 16);
+    x.w = T::round(T::lo(x.w) * factor) | (T::round(T::hi(x.w) * factor) << 16);
     t[i] = x;
   }
 }
@@ -230,29 +227,31 @@ __global__ __launch_bounds__(256) void table_mult_add_f32_kernel(float4* __restr
                          sum_once(o.z, factor, r.z), sum_once(o.w, factor, r.w));
   }
 }
+template <typename T>
 __device__ __forceinline__ uint32_t mult_add_pair(uint32_t o, uint32_t r, float factor) {
-  return round_bf16(sum_once(widen_lo(o), factor, widen_lo(r))) |
-         (round_bf16(sum_once(widen_hi(o), factor, widen_hi(r))) << 16);
+  return T::round(sum_once(T::lo(o), factor, T::lo(r))) |
+         (T::round(sum_once(T::hi(o), factor, T::hi(r))) << 16);
 }
-__global__ __launch_bounds__(256) void table_mult_add_bf16_kernel(uint4* __restrict__ dst,
-                                                                  const uint4* __restrict__ src,
-                                                                  int64_t n8, float factor) {
+template <typename T>
+__global__ __launch_bounds__(256) void table_mult_add16_kernel(uint4* __restrict__ dst,
+                                                               const uint4* __restrict__ src,
+                                                               int64_t n8, float factor) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8;
        i += (int64_t)gridDim.x * blockDim.x) {
     const uint4 o = dst[i], r = src[i];
     uint4 x;
-    x.x = mult_add_pair(o.x, r.x, factor);
-    x.y = mult_add_pair(o.y, r.y, factor);
-    x.z = mult_add_pair(o.z, r.z, factor);
-    x.w = mult_add_pair(o.w, r.w, factor);
+    x.x = mult_add_pair<T>(o.x, r.x, factor);
+    x.y = mult_add_pair<T>(o.y, r.y, factor);
+    x.z = mult_add_pair<T>(o.z, r.z, factor);
+    x.w = mult_add_pair<T>(o.w, r.w, factor);
     dst[i] = x;
   }
 }
 
 int32_t check_table_args(const void* table, int64_t num_nodes, int32_t dim, int32_t dtype) {
   if (!table || num_nodes < 1 || num_nodes > (int64_t)INT32_MAX) return GS_EINVAL;
-  if (dtype != GS_F32 && dtype != GS_BF16) return GS_EINVAL;
-  if (dim < 1 || dim % (dtype == GS_BF16 ? 8 : 4) != 0) return GS_EINVAL;
+  if (dtype != GS_F32 && dtype != GS_BF16 && dtype != GS_F16) return GS_EINVAL;
+  if (dim < 1 || dim % (dtype == GS_F32 ? 4 : 8) != 0) return GS_EINVAL;
   if (!aligned(table, 16)) return GS_EINVAL;
   return GS_OK;
 }
@@ -331,8 +330,8 @@ int bits_for(uint64_t max_value) {
 int32_t check_rows_args(const void* table, int64_t num_nodes, int32_t dim, int32_t dtype,
                         const int32_t* ids, int64_t n, const void* block) {
   if (!table || num_nodes < 1 || num_nodes > (int64_t)INT32_MAX || n < 0) return GS_EINVAL;
-  if (dtype != GS_F32 && dtype != GS_BF16) return GS_EINVAL;
-  if (dim < 1 || dim % (dtype == GS_BF16 ? 8 : 4) != 0) return GS_EINVAL;
+  if (dtype != GS_F32 && dtype != GS_BF16 && dtype != GS_F16) return GS_EINVAL;
+  if (dim < 1 || dim % (dtype == GS_F32 ? 4 : 8) != 0) return GS_EINVAL;
   if (n > 0 && (!ids || !block)) return GS_EINVAL;
   if (!aligned(table, 16) || (n > 0 && !aligned(block, 16))) return GS_EINVAL;
   if (ceil_div(n, kRowsPerBlock) > (int64_t)INT32_MAX) return GS_EOVERFLOW;
@@ -415,9 +414,12 @@ extern "C" int32_t gs_get_rows(const void* table, int64_t num_nodes, int32_t dim
   if (dtype == GS_F32)
     get_rows_f32_kernel<<<blocks, kRowThreads, 0, stream>>>(static_cast<const float*>(table), num_nodes,
                                                             dim, ids, n, count_dev, out);
+  else if (dtype == GS_BF16)
+    get_rows16_kernel<bf16_t><<<blocks, kRowThreads, 0, stream>>>(static_cast<const uint16_t*>(table),
+                                                                  num_nodes, dim, ids, n, count_dev, out);
   else
-    get_rows_bf16_kernel<<<blocks, kRowThreads, 0, stream>>>(static_cast<const uint16_t*>(table),
-                                                             num_nodes, dim, ids, n, count_dev, out);
+    get_rows16_kernel<f16_t><<<blocks, kRowThreads, 0, stream>>>(static_cast<const uint16_t*>(table),
+                                                                 num_nodes, dim, ids, n, count_dev, out);
   GS_LAUNCH_CHECK();
   return GS_OK;
 }
@@ -433,9 +435,12 @@ extern "C" int32_t gs_put_rows(void* table, int64_t num_nodes, int32_t dim, int3
   if (dtype == GS_F32)
     put_rows_f32_kernel<<<blocks, kRowThreads, 0, stream>>>(static_cast<float*>(table), num_nodes, dim,
                                                             ids, n, count_dev, rows, scale);
+  else if (dtype == GS_BF16)
+    put_rows16_kernel<bf16_t><<<blocks, kRowThreads, 0, stream>>>(static_cast<uint16_t*>(table), num_nodes,
+                                                                  dim, ids, n, count_dev, rows, scale);
   else
-    put_rows_bf16_kernel<<<blocks, kRowThreads, 0, stream>>>(static_cast<uint16_t*>(table), num_nodes,
-                                                             dim, ids, n, count_dev, rows, scale);
+    put_rows16_kernel<f16_t><<<blocks, kRowThreads, 0, stream>>>(static_cast<uint16_t*>(table), num_nodes,
+                                                                 dim, ids, n, count_dev, rows, scale);
   GS_LAUNCH_CHECK();
   return GS_OK;
 }
@@ -445,12 +450,14 @@ extern "C" int32_t gs_table_mult(void* table, int64_t num_nodes, int32_t dim, in
   hipStream_t stream = (hipStream_t)stream_;
   const int32_t rc = check_table_args(table, num_nodes, dim, dtype);
   if (rc != GS_OK) return rc;
-  const int64_t pieces = num_nodes * (int64_t)dim / (dtype == GS_BF16 ? 8 : 4);
+  const int64_t pieces = num_nodes * (int64_t)dim / (dtype == GS_F32 ? 4 : 8);
   const unsigned blocks = (unsigned)min((int64_t)(256 * 64), ceil_div(pieces, 256));
   if (dtype == GS_F32)
     table_mult_f32_kernel<<<blocks, 256, 0, stream>>>(static_cast<float4*>(table), pieces, factor);
+  else if (dtype == GS_BF16)
+    table_mult16_kernel<bf16_t><<<blocks, 256, 0, stream>>>(static_cast<uint4*>(table), pieces, factor);
   else
-    table_mult_bf16_kernel<<<blocks, 256, 0, stream>>>(static_cast<uint4*>(table), pieces, factor);
+    table_mult16_kernel<f16_t><<<blocks, 256, 0, stream>>>(static_cast<uint4*>(table), pieces, factor);
   GS_LAUNCH_CHECK();
   return GS_OK;
 }
@@ -463,14 +470,17 @@ extern "C" int32_t gs_table_mult_add(void* dst, const void* src, int64_t num_nod
   rc = check_table_args(src, num_nodes, dim, dtype);
   if (rc != GS_OK) return rc;
   if (dst == src) return GS_EINVAL;
-  const int64_t pieces = num_nodes * (int64_t)dim / (dtype == GS_BF16 ? 8 : 4);
+  const int64_t pieces = num_nodes * (int64_t)dim / (dtype == GS_F32 ? 4 : 8);
   const unsigned blocks = (unsigned)min((int64_t)(256 * 64), ceil_div(pieces, 256));
   if (dtype == GS_F32)
     table_mult_add_f32_kernel<<<blocks, 256, 0, stream>>>(static_cast<float4*>(dst),
                                                           static_cast<const float4*>(src), pieces, factor);
+  else if (dtype == GS_BF16)
+    table_mult_add16_kernel<bf16_t><<<blocks, 256, 0, stream>>>(
+        static_cast<uint4*>(dst), static_cast<const uint4*>(src), pieces, factor);
   else
-    table_mult_add_bf16_kernel<<<blocks, 256, 0, stream>>>(static_cast<uint4*>(dst),
-                                                           static_cast<const uint4*>(src), pieces, factor);
+    table_mult_add16_kernel<f16_t><<<blocks, 256, 0, stream>>>(
+        static_cast<uint4*>(dst), static_cast<const uint4*>(src), pieces, factor);
   GS_LAUNCH_CHECK();
   return GS_OK;
 }

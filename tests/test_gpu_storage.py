@@ -50,7 +50,8 @@ def test_unique_ids(gs, oracle, n, num_nodes, bad):
 
 
 @pytest.mark.parametrize("dtype,dim", [("f32", 128), ("f32", 4), ("f32", 100), ("bf16", 256),
-                                       ("bf16", 8), ("bf16", 72), ("f32", 1024)])
+                                       ("bf16", 8), ("bf16", 72), ("f32", 1024), ("f16", 128),
+                                       ("f16", 8)])
 def test_get_and_put_rows(gs, oracle, dtype, dim):
     from paper_2407_15452_amd import inputs
     n_nodes, n = 20_011, 7_003
@@ -59,10 +60,10 @@ def test_get_and_put_rows(gs, oracle, dtype, dim):
     ids = rng.permutation(n_nodes)[:n].astype(np.int32)
     ids[5], ids[77] = -1, n_nodes                                   # not rows: zero / skipped
     rows = rng.normal(size=(n, dim)).astype(np.float32)
-    if dtype == "bf16":
-        d_table = table.to(torch.bfloat16).to(DEV)
+    if dtype in ("bf16", "f16"):
+        d_table = table.to(torch.bfloat16 if dtype == "bf16" else torch.float16).to(DEV)
         h_table = _bits(d_table).copy()
-        code = oracle.BF16
+        code = oracle.BF16 if dtype == "bf16" else oracle.F16
     else:
         d_table = table.to(DEV)
         h_table = table.numpy().copy()
@@ -71,7 +72,7 @@ def test_get_and_put_rows(gs, oracle, dtype, dim):
     np.testing.assert_array_equal(got.cpu().numpy(), oracle.get_rows(h_table, ids, dtype=code))
     gs.gs_put_rows(d_table, _t(ids), _t(rows), -0.37)
     oracle.put_rows(h_table, ids, rows, -0.37, dtype=code)
-    after = _bits(d_table) if dtype == "bf16" else d_table.cpu().numpy()
+    after = _bits(d_table) if dtype != "f32" else d_table.cpu().numpy()
     np.testing.assert_array_equal(after, h_table)
 
 
@@ -136,15 +137,17 @@ def test_storage_argument_errors(gs):
         gs.gs_unique_ids(torch.zeros(100_000, dtype=torch.int32, device=DEV), 10, ws=small)
 
 
-@pytest.mark.parametrize("dtype,dim", [("f32", 128), ("f32", 4), ("bf16", 256), ("bf16", 8)])
+@pytest.mark.parametrize("dtype,dim", [("f32", 128), ("f32", 4), ("bf16", 256), ("bf16", 8),
+                                       ("f16", 64)])
 def test_dense_mult_and_mult_add(gs, oracle, dtype, dim):
     from paper_2407_15452_amd import inputs
     n = 30_011
     a, b = inputs.random_tables(n, dim, 9, 1.5)
-    if dtype == "bf16":
-        d_a, d_b = a.to(torch.bfloat16).to(DEV), b.to(torch.bfloat16).to(DEV)
+    if dtype in ("bf16", "f16"):
+        tdt = torch.bfloat16 if dtype == "bf16" else torch.float16
+        d_a, d_b = a.to(tdt).to(DEV), b.to(tdt).to(DEV)
         h_a, h_b = _bits(d_a).copy(), _bits(d_b).copy()
-        code = oracle.BF16
+        code = oracle.BF16 if dtype == "bf16" else oracle.F16
     else:
         d_a, d_b = a.to(DEV), b.to(DEV)
         h_a, h_b = a.numpy().copy(), b.numpy().copy()
@@ -153,7 +156,7 @@ def test_dense_mult_and_mult_add(gs, oracle, dtype, dim):
     oracle.table_mult(h_a, 0.9, dtype=code)
     gs.gs_table_mult_add(d_b, d_a, -0.025)
     oracle.table_mult_add(h_b, h_a, -0.025, dtype=code)
-    view = _bits if dtype == "bf16" else (lambda t: t.cpu().numpy())
+    view = _bits if dtype != "f32" else (lambda t: t.cpu().numpy())
     np.testing.assert_array_equal(view(d_a), h_a)
     np.testing.assert_array_equal(view(d_b), h_b)
     with pytest.raises(gs.GsError):
