@@ -7,7 +7,7 @@ from hypothesis import HealthCheck, given, settings, strategies as st
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-COMMON = dict(deadline=None, suppress_health_check=[HealthCheck.function_scoped_fixture,
+COMMON = dict(deadline=None, derandomize=True, suppress_health_check=[HealthCheck.function_scoped_fixture,
                                                     HealthCheck.too_slow])
 
 
