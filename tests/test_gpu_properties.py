@@ -112,14 +112,16 @@ def test_sgns_step_random(gs, oracle, dim, k, b, n, fmt, seed):
     for d_t, h_t in ((d_in, h_in), (d_out, h_out)):
         got = bits(d_t.cpu())
         if fmt == "f32":
-            assert np.abs(got - h_t).max() <= 1e-5
+            # 1e-5 at the magnitudes of embeddings; a degenerate case (one node: a thousand terms
+            # on one row, values of 10) adds a few fp32 steps of the value itself
+            assert (np.abs(got - h_t) <= 1e-5 + 2e-6 * np.abs(h_t)).all()
         else:
             if fmt == "bf16":
                 val = lambda x: (x.astype(np.uint32) << 16).view(np.float32)  # noqa: E731
             else:
                 val = lambda x: x.view(np.float16).astype(np.float32)  # noqa: E731
             near = np.abs(got.astype(np.int32) - h_t.astype(np.int32)) <= 1
-            assert (near | (np.abs(val(got) - val(h_t)) <= 1e-5)).all()
+            assert (near | (np.abs(val(got) - val(h_t)) <= 1e-5 + 2e-6 * np.abs(val(h_t)))).all()
 
 
 @settings(max_examples=40, **COMMON)
