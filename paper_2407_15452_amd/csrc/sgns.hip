@@ -9,7 +9,7 @@
 // per destination row and every touched row is written exactly once, as
 // round(old + delta) with delta accumulated in fp32.
 //
-//   clear      cnt[0..N] = 0
+//   clear      cnt[0..N] = 0, owner[0..N] = none, side buffer = 0
 //   forward    read-only on both tables: logits, g = dLoss/dx, loss, the
 //              centre-row gradients staged per run of equal centres, and
 //              rank[e] = cnt[row_e]++ (position of term e among the terms of
@@ -21,10 +21,10 @@
 //              handled whole by one 16-lane group and written once; longer
 //              rows are summed slice by slice into an fp32 side buffer
 //   long_rows  w_out[row] = round(old + side buffer) for the long rows
-//   owners     owner[centre] = lowest staging slot holding that centre
+//   owners     owner[centre] = lowest staging slot holding that centre; one extra block
+//              sums the per-block loss partials in a fixed order
 //   merge      staged gradients of the other slots are added into the owner's
 //   apply      w_in[centre] = round(old - lr * merged gradient)
-//   finish     deterministic sum of the per-block loss partials
 //
 // A row is handled by 16 lanes holding 16-byte pieces (256 contiguous bytes per
 // load instruction); a wave works on four rows at once and a dot product is a
@@ -53,6 +53,7 @@ constexpr int kLongShift = 8;      // log2(kLongRow): side-buffer slot = first t
 constexpr int kScanThreads = 256;
 constexpr int kScanPerThread = 16;
 constexpr int kScanTile = kScanThreads * kScanPerThread;
+constexpr int64_t kFewTiles = 4096;   // up to this many scan tiles, blocks add up the earlier tile sums themselves
 constexpr uint32_t kNoOwner = 0xffffffffu;
 constexpr int kHotBits = 8;                      // block-local rank counters in forward
 constexpr int kHotSlots = 1 << kHotBits;
@@ -103,7 +104,8 @@ struct SgnsArgs {
   float lr;
   float* g;                 // [num_terms]
   uint32_t* rank;           // [num_terms]
-  uint32_t* cnt;            // [num_nodes + 1]; after scan: offsets; later: owner slot per centre
+  uint32_t* cnt;            // [num_nodes + 1]; after scan: offsets
+  uint32_t* owner;          // [num_nodes + 1]; lowest staging slot that holds a centre
   uint32_t* tile_sums;      // scan scratch
   Term* sorted;             // [num_terms]
   float* long_acc;          // [long_slots][dim] fp32 sums of the long rows
@@ -356,15 +358,14 @@ __device__ __forceinline__ int64_t xcd_contiguous_block(int64_t bid, int64_t per
 }
 
 // ---- clear / fill ---------------------------------------------------------------------
-__global__ void fill_u32_kernel(uint32_t* __restrict__ p, int64_t n, uint32_t value) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = value;
-}
-
-__global__ void fill_f32x4_kernel(float4* __restrict__ p, int64_t n4, uint32_t* __restrict__ flag) {
+// everything a call starts from: counters 0, no owners, side buffer 0, no bad id seen
+__global__ void sgns_clear_kernel(uint32_t* __restrict__ cnt, uint32_t* __restrict__ owner, int64_t n1,
+                                  float4* __restrict__ long_acc, int64_t long4,
+                                  uint32_t* __restrict__ flag) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i == 0) *flag = 0u;
-  if (i < n4) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i < n1) { cnt[i] = 0u; owner[i] = kNoOwner; }
+  if (i < long4) long_acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
 // ---- forward ------------------------------------------------------------------------------
@@ -569,10 +570,29 @@ __global__ __launch_bounds__(1024) void scan_tiles_kernel(uint32_t* __restrict__
   }
 }
 
+// tile_offsets: exclusive prefix sums of the tile sums (raw_sums == 0), or the tile sums
+// themselves (raw_sums != 0: each block adds up the sums of the tiles before it, which is
+// cheaper than a kernel of its own while there are few tiles)
 __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(uint32_t* __restrict__ data, int64_t n,
-                                                                  const uint32_t* __restrict__ tile_offsets) {
+                                                                  const uint32_t* __restrict__ tile_offsets,
+                                                                  int raw_sums) {
   __shared__ uint32_t wave_tot[kScanThreads / 64];
+  __shared__ uint32_t before_s[kScanThreads / 64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t tile_base;
+  if (raw_sums) {
+    uint32_t part = 0;
+    for (int64_t i = threadIdx.x; i < (int64_t)blockIdx.x; i += kScanThreads) part += tile_offsets[i];
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) part += __shfl_xor(part, d, 64);
+    if (lane == 0) before_s[wave] = part;
+    __syncthreads();
+    tile_base = 0;
+#pragma unroll
+    for (int w = 0; w < kScanThreads / 64; ++w) tile_base += before_s[w];
+  } else {
+    tile_base = tile_offsets[blockIdx.x];
+  }
   // thread t owns kScanPerThread consecutive values
   const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanPerThread;
   uint32_t v[kScanPerThread];
@@ -599,7 +619,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(uint32_t* __re
   }
   if (lane == 63) wave_tot[wave] = incl;
   __syncthreads();
-  uint32_t run = tile_offsets[blockIdx.x] + incl - local;
+  uint32_t run = tile_base + incl - local;
 #pragma unroll
   for (int w = 0; w < kScanThreads / 64; ++w)
     if (w < wave) run += wave_tot[w];
@@ -819,11 +839,27 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_long_rows_kernel(SgnsArgs a
 }
 
 // ---- owners / merge / apply: staged centre-row gradients into w_in -----------------------
-__global__ void sgns_owner_kernel(SgnsArgs a) {
+// The last block of the launch adds up the per-block loss partials instead (in a fixed
+// order, so the loss is reproducible); a bad id seen by an earlier kernel turns it into NaN.
+__global__ __launch_bounds__(256) void sgns_owner_kernel(SgnsArgs a) {
+  if (blockIdx.x == gridDim.x - 1) {
+    __shared__ double sum_s[256];
+    double acc = 0.0;
+    for (int64_t i = threadIdx.x; i < a.forward_blocks; i += 256) acc += a.loss_partials[i];
+    sum_s[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+      if ((int)threadIdx.x < w) sum_s[threadIdx.x] += sum_s[threadIdx.x + w];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0)
+      *a.loss_out = (*a.bad_ids != 0u) ? __longlong_as_double(0x7ff8000000000000ll) : sum_s[0];
+    return;
+  }
   const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (s >= a.num_pairs) return;
   const int32_t c = a.stage_center[s];
-  if (c >= 0) atomicMin(a.cnt + c, (uint32_t)s);
+  if (c >= 0) atomicMin(a.owner + c, (uint32_t)s);
 }
 
 // Every staged slot that does not own its centre adds its gradient into the
@@ -838,7 +874,7 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_merge_kernel(SgnsArgs a) {
   if (s_mine < a.num_pairs) {
     const int32_t c = a.stage_center[s_mine];
     if (c >= 0) {
-      const int64_t owner = (int64_t)a.cnt[c];
+      const int64_t owner = (int64_t)a.owner[c];
       if (owner != s_mine) owner_mine = owner;
     }
   }
@@ -860,7 +896,7 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_apply_kernel(SgnsArgs a) {
   int32_t center_mine = -1;                   // >= 0: this lane's slot owns that centre
   if (s_mine < a.num_pairs) {
     const int32_t c = a.stage_center[s_mine];
-    if (c >= 0 && (int64_t)a.cnt[c] == s_mine) center_mine = c;
+    if (c >= 0 && (int64_t)a.owner[c] == s_mine) center_mine = c;
   }
   for (int b = 0; b < kGroupLanes; ++b) {
     const int32_t c = __shfl(center_mine, b, kGroupLanes);
@@ -881,22 +917,6 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_apply_kernel(SgnsArgs a) {
   }
 }
 
-__global__ __launch_bounds__(256) void sgns_finish_kernel(const double* __restrict__ partials,
-                                                          int64_t count,
-                                                          const uint32_t* __restrict__ bad_ids,
-                                                          double* __restrict__ out) {
-  __shared__ double s[256];
-  double acc = 0.0;
-  for (int64_t i = threadIdx.x; i < count; i += 256) acc += partials[i];
-  s[threadIdx.x] = acc;
-  __syncthreads();
-  for (int w = 128; w > 0; w >>= 1) {
-    if ((int)threadIdx.x < w) s[threadIdx.x] += s[threadIdx.x + w];
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) *out = (*bad_ids != 0u) ? __longlong_as_double(0x7ff8000000000000ll) : s[0];
-}
-
 // ---- host side -----------------------------------------------------------------------------
 static int64_t forward_blocks_for(int64_t num_pairs) {
   return ceil_div(ceil_div(num_pairs, kChunkPairs), kGroupsPerBlock);
@@ -907,6 +927,7 @@ struct SgnsPlan {
   float* g;
   uint32_t* rank;
   uint32_t* cnt;
+  uint32_t* owner;
   uint32_t* tile_sums;
   uint32_t* bad_ids;
   Term* sorted;
@@ -928,6 +949,7 @@ static SgnsPlan plan_sgns(void* ws, int64_t num_pairs, int64_t num_nodes, int32_
   p.g = cv.take<float>(terms);
   p.rank = cv.take<uint32_t>(terms);
   p.cnt = cv.take<uint32_t>(n1);
+  p.owner = cv.take<uint32_t>(n1);
   p.tile_sums = cv.take<uint32_t>((size_t)ceil_div((int64_t)n1, kScanTile));
   p.bad_ids = cv.take<uint32_t>(1);
   p.sorted = cv.take<Term>(terms);
@@ -942,11 +964,9 @@ template <typename T, int VPL, int RB, int UB>
 static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
   const int64_t n1 = a.num_nodes + 1;
   const int64_t tiles = ceil_div(n1, kScanTile);
-  fill_u32_kernel<<<(unsigned)ceil_div(n1, 256), 256, 0, stream>>>(a.cnt, n1, 0u);
-  GS_LAUNCH_CHECK();
   const int64_t long4 = a.long_slots * (int64_t)(a.dim >> 2);
-  fill_f32x4_kernel<<<(unsigned)ceil_div(long4, 256), 256, 0, stream>>>((float4*)a.long_acc, long4,
-                                                                     a.bad_ids);
+  sgns_clear_kernel<<<(unsigned)ceil_div(max(n1, long4), 256), 256, 0, stream>>>(
+      a.cnt, a.owner, n1, (float4*)a.long_acc, long4, a.bad_ids);
   GS_LAUNCH_CHECK();
   const size_t idx_lds = (size_t)kGroupsPerBlock * kChunkPairs * (a.k + 2) * sizeof(int32_t);
   sgns_forward_kernel<T, VPL, RB><<<(unsigned)(a.forward_blocks_per_xcd * 8), kSgnsThreads, idx_lds,
@@ -954,9 +974,12 @@ static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
   GS_LAUNCH_CHECK();
   scan_reduce_kernel<<<(unsigned)tiles, kScanThreads, 0, stream>>>(a.cnt, n1, a.tile_sums);
   GS_LAUNCH_CHECK();
-  scan_tiles_kernel<<<1, 1024, 0, stream>>>(a.tile_sums, tiles);
-  GS_LAUNCH_CHECK();
-  scan_apply_kernel<<<(unsigned)tiles, kScanThreads, 0, stream>>>(a.cnt, n1, a.tile_sums);
+  const int raw_sums = tiles <= kFewTiles ? 1 : 0;
+  if (!raw_sums) {
+    scan_tiles_kernel<<<1, 1024, 0, stream>>>(a.tile_sums, tiles);
+    GS_LAUNCH_CHECK();
+  }
+  scan_apply_kernel<<<(unsigned)tiles, kScanThreads, 0, stream>>>(a.cnt, n1, a.tile_sums, raw_sums);
   GS_LAUNCH_CHECK();
   sgns_place_kernel<<<(unsigned)ceil_div(a.num_terms, 256), 256, 0, stream>>>(a);
   GS_LAUNCH_CHECK();
@@ -977,18 +1000,13 @@ static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
   sgns_long_rows_kernel<T><<<(unsigned)ceil_div(a.long_slots, kGroupsPerBlock), kSgnsThreads, 0,
                             stream>>>(a);
   GS_LAUNCH_CHECK();
-  // the offsets are no longer needed: the same array now records, per centre,
-  // the lowest staging slot that holds it
-  fill_u32_kernel<<<(unsigned)ceil_div(n1, 256), 256, 0, stream>>>(a.cnt, n1, kNoOwner);
-  GS_LAUNCH_CHECK();
-  sgns_owner_kernel<<<(unsigned)ceil_div(a.num_pairs, 256), 256, 0, stream>>>(a);
+  // per centre, the lowest staging slot that holds it; one more block sums the loss
+  sgns_owner_kernel<<<(unsigned)ceil_div(a.num_pairs, 256) + 1, 256, 0, stream>>>(a);
   GS_LAUNCH_CHECK();
   const unsigned slot_blocks = (unsigned)ceil_div(a.num_pairs, kSgnsThreads);   // a slot per lane
   sgns_merge_kernel<<<slot_blocks, kSgnsThreads, 0, stream>>>(a);
   GS_LAUNCH_CHECK();
   sgns_apply_kernel<T><<<slot_blocks, kSgnsThreads, 0, stream>>>(a);
-  GS_LAUNCH_CHECK();
-  sgns_finish_kernel<<<1, 256, 0, stream>>>(a.loss_partials, a.forward_blocks, a.bad_ids, a.loss_out);
   GS_LAUNCH_CHECK();
   return GS_OK;
 }
@@ -1145,6 +1163,7 @@ static int32_t run_sgns(void* w_in, void* w_out, void* dst_in, void* dst_out, in
   a.g = p.g;
   a.rank = p.rank;
   a.cnt = p.cnt;
+  a.owner = p.owner;
   a.tile_sums = p.tile_sums;
   a.bad_ids = p.bad_ids;
   a.sorted = p.sorted;
