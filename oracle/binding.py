@@ -29,11 +29,21 @@ class _Alias(C.Structure):
     _fields_ = [("prob", C.c_void_p), ("alias", C.c_void_p)]
 
 
+SOURCE = _SRC
+BASE_FLAGS = ["-std=c++17", "-ffp-contract=off", "-fPIC", "-shared", "-Wall", "-Wextra"]
+
+
 def build(force: bool = False) -> str:
-    """Compile the oracle with g++ (no fused multiply-add contraction)."""
+    """Compile the oracle with g++ (no fused multiply-add contraction).
+
+    ``GS_ORACLE_LIB`` in the environment names a library built elsewhere from the same
+    source (the sanitizer test builds one with -fsanitize=address,undefined and runs the
+    pins in a child process against it); it is then loaded as it is."""
+    other = os.environ.get("GS_ORACLE_LIB")
+    if other:
+        return other
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["g++", "-std=c++17", "-O2", "-ffp-contract=off", "-fPIC", "-shared",
-               "-Wall", "-Wextra", "-o", _LIB, _SRC]
+        cmd = ["g++", "-O2", *BASE_FLAGS, "-o", _LIB, _SRC]
         subprocess.run(cmd, check=True)
     return _LIB
 
