@@ -258,3 +258,73 @@ def test_line_first_order_and_optimizer_steps_full_batch(gs, oracle, big):
         m, v = got[which + 2].astype(np.float64), got[which + 4].astype(np.float64)
         expect = before[which] - step * m / (np.sqrt(v) / root + np.float64(np.float32(1e-8)))
         assert np.abs(got[which] - expect).max() <= 1e-6
+
+
+def test_workload1_full_size(gs, oracle):
+    """Workload 1 at its own shape (1 M nodes, 10 M undirected edges, uniform walks of 40
+    nodes, window 5, K = 5, dim 128 fp32, 1,048,576-pair batches): the CSR and the noise table
+    against the oracle in full, a 4 M-walk launch sampled by walk id, pair blocks by walk,
+    negatives by pair index, and one whole batch recomputed by the oracle."""
+    from paper_2407_15452_amd import inputs
+    wl = inputs.WORKLOADS[1]
+    N, B, K, L, W = wl.num_nodes, wl.batch_pairs, wl.num_neg, wl.walk_len, wl.window
+    rng = np.random.default_rng(11)
+    src, dst, _ = inputs.edge_list(wl, DEV)
+    flags = gs.GS_SYMMETRIZE | gs.GS_DROP_SELF_LOOPS | gs.GS_DEDUPE
+    g = gs.gs_csr_build(src, dst, None, N, flags)
+    torch.cuda.synchronize()
+    off, nb = g.offsets.cpu().numpy(), g.nbrs.cpu().numpy()
+    want_off, want_nb, _ = oracle.csr_build(src.cpu().numpy(), dst.cpu().numpy(), None, N, flags)
+    np.testing.assert_array_equal(off, want_off)
+    np.testing.assert_array_equal(nb, want_nb)
+    del src, dst
+
+    noise_w = inputs.noise_weights(g.offsets)
+    seg = torch.tensor([0, N], dtype=torch.int64, device=DEV)
+    noise = gs.gs_alias_build(seg, noise_w)
+    o_prob, o_alias = oracle.alias_build(np.array([0, N], dtype=np.int64), noise_w.cpu().numpy())
+    np.testing.assert_array_equal(noise.alias.cpu().numpy(), o_alias)
+    np.testing.assert_array_equal(noise.prob.cpu().numpy(), o_prob)
+
+    # the stand-alone launch bench.py times (4 M walks), sampled by walk id
+    first, count = 3_000_017, 4_000_000
+    starts = inputs.walk_starts(N, first, count, DEV)
+    walks = gs.gs_random_walk(g, None, starts, L, wl.walk_seed, walk_id_base=first)
+    pick = np.sort(rng.choice(count, 400, replace=False))
+    got = walks[torch.as_tensor(pick, device=DEV)].cpu().numpy()
+    st = starts[torch.as_tensor(pick, device=DEV)].cpu().numpy()
+    for i, s, row in zip(pick, st, got):
+        want = oracle.random_walk(off, nb, np.array([s], dtype=np.int32), L, wl.walk_seed,
+                                  walk_id_base=first + int(i))
+        np.testing.assert_array_equal(row, want[0])
+    live = torch.as_tensor(np.diff(off) > 0, device=DEV)[starts.long()]
+    assert bool((walks[live] >= 0).all()) and bool((walks[~live][:, 1:] == -1).all())
+    del walks
+
+    # a chunk of walks that holds more than one batch, whole against the oracle
+    count = 6000
+    starts = inputs.walk_starts(N, 0, count, DEV)
+    walks = gs.gs_random_walk(g, None, starts, L, wl.walk_seed)
+    h_walks = oracle.random_walk(off, nb, starts.cpu().numpy(), L, wl.walk_seed)
+    np.testing.assert_array_equal(walks.cpu().numpy(), h_walks)
+    centers, contexts, n_pairs = gs.gs_make_pairs(walks, W)
+    hc, ho = oracle.make_pairs(h_walks, W)
+    assert n_pairs == hc.size and n_pairs >= B
+    np.testing.assert_array_equal(centers[:n_pairs].cpu().numpy(), hc)
+    np.testing.assert_array_equal(contexts[:n_pairs].cpu().numpy(), ho)
+
+    pair_base = 5 * B
+    negs = gs.gs_sample_negatives(noise, N, B, K, wl.neg_seed, pair_index_base=pair_base)
+    h_negs = oracle.sample_negatives((o_prob, o_alias), N, B, K, wl.neg_seed, pair_index_base=pair_base)
+    np.testing.assert_array_equal(negs.cpu().numpy(), h_negs)
+
+    # one whole 1,048,576-pair iteration
+    w_in, w_out = inputs.random_tables(N, wl.dim, seed=15, scale=0.15, device=DEV)
+    h_in, h_out = w_in.cpu().numpy(), w_out.cpu().numpy()
+    lr = 0.025
+    loss = gs.gs_sgns_step(w_in, w_out, centers[:B], contexts[:B], negs, lr)
+    torch.cuda.synchronize()
+    want = oracle.sgns_step(h_in, h_out, hc[:B], ho[:B], h_negs, lr)
+    assert abs(float(loss.item()) - want) <= 1e-5 * abs(want)
+    assert np.abs(w_in.cpu().numpy() - h_in).max() <= 1e-5
+    assert np.abs(w_out.cpu().numpy() - h_out).max() <= 1e-5
