@@ -26,6 +26,12 @@ HIPCC_FLAGS = [
 ]
 
 
+# Files whose kernels take sampling decisions that must match the CPU reference bit for bit
+# (one multiply, one compare per decision): no fused multiply-add may ever be formed there.
+# sgns.hip keeps contraction on (its only bit-exact part, the negative draws, is a compare).
+NO_CONTRACTION = {"walk.hip", "pairs_negs.hip", "alias_build.hip", "csr_build.hip"}
+
+
 def hipcc() -> str:
     exe = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     if not os.path.exists(exe):
@@ -35,7 +41,8 @@ def hipcc() -> str:
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
-    cmd = [hipcc(), *HIPCC_FLAGS, "-c", src, "-o", obj]
+    extra = ["-ffp-contract=off"] if os.path.basename(src) in NO_CONTRACTION else []
+    cmd = [hipcc(), *HIPCC_FLAGS, *extra, "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "packed-fp32-ops' is not a recognized feature"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)

@@ -7,24 +7,35 @@
 // at ~1/5 of the plain read-modify-write rate on this chip (and do not exist
 // for a "round once" bf16 update), so contributions are first brought together
 // per destination row and every touched row is written exactly once, as
-// round(old + delta) with delta accumulated in fp32.
+// round(old + delta).
 //
-//   clear      cnt[0..N] = 0, owner[0..N] = none, side buffer = 0
+// Destination rows of both tables share one key space: key r < N is row r of
+// the context table (its terms are the (pair, j) logits that name it), key N + c
+// is row c of the input table (its terms are the staged gradients of the runs
+// of equal centres).
+//
+//   clear      cnt[0..2N] = 0
 //   forward    read-only on both tables: logits, g = dLoss/dx, loss, the
-//              centre-row gradients staged per run of equal centres, and
-//              rank[e] = cnt[row_e]++ (position of term e among the terms of
-//              its destination row)
+//              centre-row gradient of every run of equal centres staged in a
+//              slot, and rank = cnt[key]++ for every term and every used slot
 //   scan       off = exclusive prefix sum of cnt
-//   place      sorted[off[row_e] + rank[e]] = (row_e, centre_e, -lr * g_e)
-//   update     per destination row: delta = sum coef * w_in[centre] (w_in is
-//              still unmodified).  Rows with at most kLongRow terms are
-//              handled whole by one 16-lane group and written once; longer
-//              rows are summed slice by slice into an fp32 side buffer
-//   long_rows  w_out[row] = round(old + side buffer) for the long rows
-//   owners     owner[centre] = lowest staging slot holding that centre; one extra block
-//              sums the per-block loss partials in a fixed order
-//   merge      staged gradients of the other slots are added into the owner's
-//   apply      w_in[centre] = round(old - lr * merged gradient)
+//   place      sorted[off[key] + rank] = (key, source row, coefficient):
+//              (context row, centre, -lr * g) or (N + centre, slot, -lr)
+//   update     once over the context-table keys (source rows: the input table,
+//              still unmodified), then once over the input-table keys (source
+//              rows: the staged gradients): delta = sum coef * source row.
+//              Rows with at most kLongRow terms are handled whole by one
+//              16-lane group and written once; longer rows are summed slice by
+//              slice into a side buffer
+//   finish     table[row] = round(old + side buffer) for the long rows; one
+//              extra block sums the per-block loss partials in a fixed order
+//
+// delta is accumulated exactly: every product coef * element is rounded once to
+// a multiple of 2^-36 (one fp64 fused multiply-add against 1.5 * 2^52, whose
+// result bits hold the integer) and the 64-bit integers are added.  Integer
+// addition is associative, so the result does not depend on the order in which
+// the terms of a row arrive (ranks come from atomics) or on how a long row is
+// split: the same call gives the same bits every time.
 //
 // A row is handled by 16 lanes holding 16-byte pieces (256 contiguous bytes per
 // load instruction); a wave works on four rows at once and a dot product is a
@@ -46,24 +57,31 @@ namespace gs {
 constexpr int kSgnsThreads = 256;
 constexpr int kGroupLanes = 16;
 constexpr int kGroupsPerBlock = kSgnsThreads / kGroupLanes;
-constexpr int kChunkPairs = 16;    // consecutive pairs per 16-lane group in forward
-constexpr int kSlice = 128;        // sorted terms per 16-lane group in update
 constexpr uint32_t kLongRow = 256; // rows with more terms than this go through the side buffer
 constexpr int kLongShift = 8;      // log2(kLongRow): side-buffer slot = first term position >> 8
 constexpr int kScanThreads = 256;
 constexpr int kScanPerThread = 16;
 constexpr int kScanTile = kScanThreads * kScanPerThread;
 constexpr int64_t kFewTiles = 4096;   // up to this many scan tiles, blocks add up the earlier tile sums themselves
-constexpr uint32_t kNoOwner = 0xffffffffu;
+// Exact accumulation of the row sums: a product x = coef * element becomes the integer
+// round(x * 2^36), read off the low bits of the fp64 value x * 2^36 + kFixMagic
+// (one fused multiply-add; valid while |x| * 2^36 < 2^51, i.e. |x| < 32768).
+constexpr double kFixScale = 68719476736.0;                  // 2^36
+constexpr double kFixInvScale = 1.0 / 68719476736.0;
+constexpr double kFixMagic = 6755399441055744.0;             // 1.5 * 2^52
+constexpr unsigned long long kFixMagicBits = 0x4338000000000000ull;
+constexpr float kFixPeak = 16384.0f;   // products at or beyond this magnitude are reported (NaN loss)
 constexpr int kHotBits = 8;                      // block-local rank counters in forward
 constexpr int kHotSlots = 1 << kHotBits;
 constexpr uint32_t kRankPending = 0x80000000u;   // rank still relative to the block (ranks < 2^31)
+constexpr uint32_t kNoRow = 0xffffffffu;         // no key: keys are below 2 * num_nodes <= 2^32 - 2
 
 
-struct Term {      // one (pair, j) contribution to a context-table row
-  int32_t row;
-  int32_t center;  // row of the input table (one-table mode: slot of its copy in `snap`)
-  float coef;      // -lr * g
+struct Term {      // one contribution to a destination row
+  uint32_t row;    // key: context-table row r, or num_nodes + c for input-table row c
+  int32_t center;  // source row: row of the input table (one-table mode: slot of its copy in
+                   // `snap`), or the staging slot for an input-table key
+  float coef;      // -lr * g, or -lr for a staged gradient
   uint32_t where;  // low 16 bits: number of terms of this row, high 16: position of this
                    // term among them; both saturate at 65535 (exact for rows <= kLongRow)
 };
@@ -97,26 +115,30 @@ struct SgnsArgs {
   const int32_t* negs;
   int64_t num_pairs;
   int64_t num_nodes;
-  int64_t num_terms;        // num_pairs * (k + 1)
-  int64_t long_slots;       // (num_terms >> kLongShift) + 1
+  int64_t num_terms;        // num_pairs * (k + 1): positions [0, num_terms) of `sorted` hold the
+                            // context-table keys, the positions after them the input-table keys
+  int64_t long_slots;       // ((num_terms + num_pairs) >> kLongShift) + 1
+  int32_t chunk_pairs;      // consecutive pairs per 16-lane group in forward (<= 16)
+  int32_t slice_terms;      // sorted terms per 16-lane group in update
   int32_t k;
   int32_t dim;
   float lr;
   float* g;                 // [num_terms]
   uint32_t* rank;           // [num_terms]
-  uint32_t* cnt;            // [num_nodes + 1]; after scan: offsets
-  uint32_t* owner;          // [num_nodes + 1]; lowest staging slot that holds a centre
+  uint32_t* cnt;            // [2 * num_nodes + 1], indexed by key; after scan: offsets
   uint32_t* tile_sums;      // scan scratch
-  Term* sorted;             // [num_terms]
-  float* long_acc;          // [long_slots][dim] fp32 sums of the long rows
+  Term* sorted;             // [num_terms + num_pairs]
+  long long* long_acc;      // [long_slots][dim] exact sums of the long rows
   int32_t* stage_center;    // [num_pairs], -1 = unused slot
+  uint32_t* stage_rank;     // [num_pairs] rank of the slot among the slots of its centre
   float* stage_delta;       // [num_pairs][dim], natural element order
   double* loss_partials;    // [forward blocks]
   int64_t forward_blocks;
   int64_t forward_blocks_per_xcd;
   int32_t update_lds_bytes; // LDS for the block-level sum of long-row partials (0: not used)
   double* loss_out;
-  uint32_t* bad_ids;        // set when a centre / context / negative id is not a row of the tables
+  uint32_t* bad_ids;        // set when a centre / context / negative id is not a row of the tables,
+                            // or a product left the range of the exact accumulation
 };
 
 // Ids come from device memory the host cannot inspect.  An id outside
@@ -358,14 +380,12 @@ __device__ __forceinline__ int64_t xcd_contiguous_block(int64_t bid, int64_t per
 }
 
 // ---- clear / fill ---------------------------------------------------------------------
-// everything a call starts from: counters 0, no owners, side buffer 0, no bad id seen
-__global__ void sgns_clear_kernel(uint32_t* __restrict__ cnt, uint32_t* __restrict__ owner, int64_t n1,
-                                  float4* __restrict__ long_acc, int64_t long4,
-                                  uint32_t* __restrict__ flag) {
+// everything a call starts from: counters 0, no bad id seen (16 bytes per lane; the counter
+// array is padded to a multiple of four entries)
+__global__ void sgns_clear_kernel(uint4* __restrict__ cnt4, int64_t n4, uint32_t* __restrict__ flag) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i == 0) *flag = 0u;
-  if (i < n1) { cnt[i] = 0u; owner[i] = kNoOwner; }
-  if (i < long4) long_acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i < n4) cnt4[i] = make_uint4(0u, 0u, 0u, 0u);
 }
 
 // ---- forward ------------------------------------------------------------------------------
@@ -376,7 +396,10 @@ __global__ void sgns_clear_kernel(uint32_t* __restrict__ cnt, uint32_t* __restri
 template <typename T, int VPL>
 __device__ __forceinline__ void stage_flush(const SgnsArgs& a, int64_t slot, int32_t center, int l16,
                                             const float4 (&du)[VPL]) {
-  if (l16 == 0) a.stage_center[slot] = center;
+  if (l16 == 0) {
+    a.stage_center[slot] = center;
+    a.stage_rank[slot] = atomicAdd(a.cnt + a.num_nodes + center, 1u);
+  }
   float4* out = reinterpret_cast<float4*>(a.stage_delta + slot * (int64_t)a.dim);
   const int dim4 = a.dim >> 2;
 #pragma unroll
@@ -405,13 +428,13 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
   const int64_t block = xcd_contiguous_block(blockIdx.x, a.forward_blocks_per_xcd);
   const int K = a.k, K1 = a.k + 1;
   const int64_t group = block * kGroupsPerBlock + group_in_block;
-  const int64_t first = group * kChunkPairs;
+  const int64_t first = group * a.chunk_pairs;
   const bool block_live = block < a.forward_blocks;
-  const int64_t last = block_live ? min(first + kChunkPairs, a.num_pairs) : first;
+  const int64_t last = block_live ? min(first + a.chunk_pairs, a.num_pairs) : first;
   const int count = (int)max((int64_t)0, last - first);
 
-  int32_t* cen_s = idx_s + group_in_block * (kChunkPairs * (K1 + 1));
-  int32_t* rows_s = cen_s + kChunkPairs;
+  int32_t* cen_s = idx_s + group_in_block * (a.chunk_pairs * (K1 + 1));
+  int32_t* rows_s = cen_s + a.chunk_pairs;
   for (int h = threadIdx.x; h < kHotSlots; h += kSgnsThreads) { hot_key[h] = -1; hot_cnt[h] = 0u; }
   if (l16 < count) cen_s[l16] = checked_row(a, a.centers[first + l16]);
   for (int t = l16; t < count * K1; t += kGroupLanes) {
@@ -643,42 +666,153 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(uint32_t* __re
   }
 }
 
-// ---- place: scatter the terms into row-major order -----------------------------
+// ---- place: scatter the terms into key-major order ------------------------------
+// Entries [0, num_terms) are the (pair, j) terms, entries num_terms + s the staging slots.
+// The entry that lands first in a long row also clears the row's slot of the side buffer.
 __global__ __launch_bounds__(256) void sgns_place_kernel(SgnsArgs a) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= a.num_terms) return;
-  const int K1 = a.k + 1;
-  const int64_t i = e / K1;
-  const int j = (int)(e - i * K1);
-  const int32_t row = checked_row(a, (j == 0) ? a.contexts[i] : a.negs[i * (int64_t)a.k + (j - 1)]);
-  const uint32_t begin = a.cnt[row], len = a.cnt[row + 1] - begin;
-  const uint32_t rk = a.rank[e];
+  if (e >= a.num_terms + a.num_pairs) return;
   Term t;
-  t.row = row;
-  t.center = (a.pair_slot != nullptr) ? a.pair_slot[i] : checked_row(a, a.centers[i]);
-  t.coef = -a.lr * a.g[e];
+  uint32_t rk;
+  if (e < a.num_terms) {
+    const int K1 = a.k + 1;
+    const int64_t i = e / K1;
+    const int j = (int)(e - i * K1);
+    t.row = (uint32_t)checked_row(a, (j == 0) ? a.contexts[i] : a.negs[i * (int64_t)a.k + (j - 1)]);
+    t.center = (a.pair_slot != nullptr) ? a.pair_slot[i] : checked_row(a, a.centers[i]);
+    t.coef = -a.lr * a.g[e];
+    rk = a.rank[e];
+  } else {
+    const int64_t slot = e - a.num_terms;
+    const int32_t c = a.stage_center[slot];
+    if (c < 0) return;
+    t.row = (uint32_t)a.num_nodes + (uint32_t)c;
+    t.center = (int32_t)slot;
+    t.coef = -a.lr;
+    rk = a.stage_rank[slot];
+  }
+  const uint32_t begin = a.cnt[t.row], len = a.cnt[(int64_t)t.row + 1] - begin;
   t.where = min(len, 65535u) | (min(rk, 65535u) << 16);
   a.sorted[begin + rk] = t;
+  if (rk == 0 && len > kLongRow) {
+    long long* acc = a.long_acc + (int64_t)(begin >> kLongShift) * a.dim;
+    for (int x = 0; x < a.dim; ++x) acc[x] = 0;
+  }
 }
 
-// ---- update: one pass over the row-major terms ------------------------------------
+// ---- update: one pass over the key-major terms of one table ----------------------------
+// Exact row sums: acc holds the sum of the result bits of fma(element, coef * 2^36,
+// kFixMagic), i.e. terms * kFixMagicBits + the sum of the rounded products (mod 2^64).
+__device__ __forceinline__ void fix_add(unsigned long long& acc, double c, float x) {
+  acc += (unsigned long long)__double_as_longlong(__builtin_fma((double)x, c, kFixMagic));
+}
+
+template <int VPL>
+__device__ __forceinline__ void fix_axpy(unsigned long long (&acc)[4 * VPL], double c, float& peak,
+                                         const RawRow<float, VPL>& x) {
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    const float4 f = x.r[v];
+    fix_add(acc[4 * v + 0], c, f.x); fix_add(acc[4 * v + 1], c, f.y);
+    fix_add(acc[4 * v + 2], c, f.z); fix_add(acc[4 * v + 3], c, f.w);
+    peak = fmaxf(peak, fmaxf(fmaxf(fabsf(f.x), fabsf(f.y)), fmaxf(fabsf(f.z), fabsf(f.w))));
+  }
+}
+template <int VPL, typename T, if_16bit<T> = 0>
+__device__ __forceinline__ void fix_axpy(unsigned long long (&acc)[4 * VPL], double c, float& peak,
+                                         const RawRow<T, VPL>& b) {
+#pragma unroll
+  for (int w = 0; w < VPL / 2; ++w) {
+    const uint4 x = b.r[w];
+    const float f[8] = {T::lo(x.x), T::hi(x.x), T::lo(x.y), T::hi(x.y),
+                        T::lo(x.z), T::hi(x.z), T::lo(x.w), T::hi(x.w)};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      fix_add(acc[8 * w + i], c, f[i]);
+      peak = fmaxf(peak, fabsf(f[i]));
+    }
+  }
+}
+
+// a staged gradient row (fp32, natural element order) in the register layout of table type T
+template <typename T, int VPL>
+__device__ __forceinline__ void load_stage(const float* __restrict__ stage, int64_t slot, int dim, int l16,
+                                           RawRow<float, VPL>& x) {
+  const float4* p = reinterpret_cast<const float4*>(stage + slot * (int64_t)dim);
+  const int dim4 = dim >> 2;
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    const int q = natural_q<T>(v, l16);
+    x.r[v] = (q < dim4) ? p[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+}
+
+// the exact sum as a double: net integer (terms * magic bits taken off) times 2^-36
+__device__ __forceinline__ double fix_value(unsigned long long acc) {
+  return (double)(long long)acc * kFixInvScale;
+}
+
+// table[row] = round(old + d), d given in fp64 per register element: the fp64 sum is
+// rounded to fp32 once, and from there to the 16-bit storage type
+template <int VPL>
+__device__ __forceinline__ void store_row_delta(float* __restrict__ table, int64_t row, int dim, int l16,
+                                                const float4 (&old)[VPL], const double (&d)[4 * VPL]) {
+  float4* p = reinterpret_cast<float4*>(table + row * (int64_t)dim);
+  const int dim4 = dim >> 2;
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    const int q = v * kGroupLanes + l16;
+    if (q < dim4)
+      p[q] = make_float4((float)((double)old[v].x + d[4 * v + 0]), (float)((double)old[v].y + d[4 * v + 1]),
+                         (float)((double)old[v].z + d[4 * v + 2]), (float)((double)old[v].w + d[4 * v + 3]));
+  }
+}
+template <int VPL, typename T, if_16bit<T> = 0>
+__device__ __forceinline__ void store_row_delta(T* __restrict__ table, int64_t row, int dim, int l16,
+                                                const float4 (&old)[VPL], const double (&d)[4 * VPL]) {
+  uint4* p = reinterpret_cast<uint4*>(table + row * (int64_t)dim);
+  const int chunks = dim >> 3;
+#pragma unroll
+  for (int w = 0; w < VPL / 2; ++w) {
+    const int c = w * kGroupLanes + l16;
+    if (c < chunks) {
+      const float4 a = old[2 * w], b = old[2 * w + 1];
+      const double* s = d + 8 * w;
+      uint4 x;
+      x.x = pack16<T>((float)((double)a.x + s[0]), (float)((double)a.y + s[1]));
+      x.y = pack16<T>((float)((double)a.z + s[2]), (float)((double)a.w + s[3]));
+      x.z = pack16<T>((float)((double)b.x + s[4]), (float)((double)b.y + s[5]));
+      x.w = pack16<T>((float)((double)b.z + s[6]), (float)((double)b.w + s[7]));
+      p[c] = x;
+    }
+  }
+}
+
 // Ownership: a row with at most kLongRow terms is handled whole by the group
 // whose slice holds its first term, which writes it once.  Longer rows are
-// handled slice by slice; their partial sums meet in the fp32 side buffer at
-// slot (position of the row's first term) >> kLongShift, which no two long rows
-// can share because each of them spans more than 2^kLongShift positions.
-template <typename T, int VPL, int UB, bool kSq>
+// handled slice by slice; their partial sums meet in the side buffer at slot
+// (position of the row's first term) >> kLongShift, which no two long rows can
+// share because each of them spans more than 2^kLongShift positions.
+// kStage = false: context-table keys, positions [0, num_terms), source rows from the input
+// table; kStage = true: input-table keys, the positions after them, source rows = staged
+// gradients.
+template <typename T, int VPL, int UB, bool kSq, bool kStage>
 __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
   static_assert(!kSq || std::is_same<T, float>::value, "second-moment tables are fp32");
-  // input rows: the table, or the copies the forward kernel kept (one-table mode)
-  const T* __restrict__ w_in = static_cast<const T*>(a.snap != nullptr ? a.snap : a.w_in);
-  T* w_out = static_cast<T*>(a.dst_out);   // destination rows (old value and result)
+  using SrcT = std::conditional_t<kStage, float, T>;
+  // source rows: the input table, or the copies the forward kernel kept (one-table mode)
+  const T* __restrict__ w_src = static_cast<const T*>(a.snap != nullptr ? a.snap : a.w_in);
+  T* w_dst = static_cast<T*>(kStage ? a.dst_in : a.dst_out);   // destination rows (old value and result)
+  float* sq_dst = kStage ? a.sq_in : a.sq_out;
+  const uint32_t key_base = kStage ? (uint32_t)a.num_nodes : 0u;
+  const int64_t pos_lo = kStage ? a.num_terms : 0;
+  const int64_t pos_hi = kStage ? (int64_t)a.cnt[2 * a.num_nodes] : a.num_terms;
   const int l16 = threadIdx.x & (kGroupLanes - 1);
   const int64_t group = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
   const int group_in_block = threadIdx.x / kGroupLanes;
-  const int64_t slice_begin = group * kSlice;
-  const bool active = slice_begin < a.num_terms;
-  const int64_t slice_end = min(slice_begin + kSlice, a.num_terms);
+  const int64_t slice_begin = pos_lo + group * a.slice_terms;
+  const bool active = slice_begin < pos_hi;
+  const int64_t slice_end = min(slice_begin + a.slice_terms, pos_hi);
   const Term* __restrict__ sorted = a.sorted;
 
   int64_t begin = slice_begin, end = active ? slice_end : slice_begin;
@@ -691,117 +825,149 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
     if (len1 <= kLongRow) end = (slice_end - 1) - pos1 + len1;             // finish the row we started
   }
 
-  float4 acc[VPL], old[VPL];
-  zero<VPL>(acc);
+  unsigned long long acc[4 * VPL];
+  float4 old[VPL];
+#pragma unroll
+  for (int x = 0; x < 4 * VPL; ++x) acc[x] = 0;
   zero<VPL>(old);
-  int32_t cur_row = -1;
+  uint32_t cur_row = kNoRow;       // key of the row being summed (table row: cur_row - key_base)
   bool cur_long = false;
+  uint32_t cur_terms = 0;          // terms added into acc since it was cleared
+  float peak = 0.f, peak_c = 0.f;  // largest |element| and |coef| seen by this lane
   const int dim4 = a.dim >> 2;
 
+  // takes the magic bits of the terms off: acc becomes the net integer sum
+  auto settle = [&]() {
+    const unsigned long long off = (unsigned long long)cur_terms * kFixMagicBits;
+#pragma unroll
+    for (int x = 0; x < 4 * VPL; ++x) acc[x] -= off;
+  };
+  auto flush_long = [&]() {
+    unsigned long long* dst = reinterpret_cast<unsigned long long*>(a.long_acc) +
+                              (int64_t)(a.cnt[cur_row] >> kLongShift) * a.dim;
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      const int q = natural_q<T>(v, l16);
+      if (q < dim4) {
+#pragma unroll
+        for (int x = 0; x < 4; ++x) atomicAdd(dst + 4 * q + x, acc[4 * v + x]);
+      }
+    }
+  };
   auto flush = [&]() {
+    settle();
     if (cur_long) {
-      float* dst = a.long_acc + (int64_t)(a.cnt[cur_row] >> kLongShift) * a.dim;
-#pragma unroll
-      for (int v = 0; v < VPL; ++v) {
-        const int q = natural_q<T>(v, l16);
-        if (q < dim4) {
-          unsafeAtomicAdd(dst + 4 * q + 0, acc[v].x);
-          unsafeAtomicAdd(dst + 4 * q + 1, acc[v].y);
-          unsafeAtomicAdd(dst + 4 * q + 2, acc[v].z);
-          unsafeAtomicAdd(dst + 4 * q + 3, acc[v].w);
-        }
-      }
-    } else if constexpr (kSq) {
-      float4 old2[VPL], d1[VPL], d2[VPL];
-      load_row<VPL>(a.sq_out, cur_row, a.dim, l16, old2);
-#pragma unroll
-      for (int v = 0; v < VPL; ++v) {
-        const float4 d = acc[v];
-        d1[v] = make_float4(a.c1 * d.x, a.c1 * d.y, a.c1 * d.z, a.c1 * d.w);
-        d2[v] = make_float4(a.c2 * d.x * d.x, a.c2 * d.y * d.y, a.c2 * d.z * d.z, a.c2 * d.w * d.w);
-      }
-      store_row_sum<VPL>(w_out, cur_row, a.dim, l16, old, d1);
-      store_row_sum<VPL>(a.sq_out, cur_row, a.dim, l16, old2, d2);
+      flush_long();
     } else {
-      store_row_sum<VPL>(w_out, cur_row, a.dim, l16, old, acc);
+      const int64_t r = (int64_t)(cur_row - key_base);
+      double d[4 * VPL];
+#pragma unroll
+      for (int x = 0; x < 4 * VPL; ++x) d[x] = fix_value(acc[x]);
+      if constexpr (kSq) {
+        float4 old2[VPL];
+        load_row<VPL>(sq_dst, r, a.dim, l16, old2);
+        double d2[4 * VPL];
+#pragma unroll
+        for (int x = 0; x < 4 * VPL; ++x) {
+          d2[x] = (double)a.c2 * d[x] * d[x];
+          d[x] *= (double)a.c1;
+        }
+        store_row_delta<VPL>(w_dst, r, a.dim, l16, old, d);
+        store_row_delta<VPL>(sq_dst, r, a.dim, l16, old2, d2);
+      } else {
+        store_row_delta<VPL>(w_dst, r, a.dim, l16, old, d);
+      }
     }
   };
 
   for (int64_t q = begin; q < end; q += kGroupLanes) {
     Term t;
-    t.row = -1; t.center = 0; t.coef = 0.f; t.where = 0;
+    t.row = kNoRow; t.center = 0; t.coef = 0.f; t.where = 0;
     if (q + l16 < end) t = sorted[q + l16];
     const int n = (int)min((int64_t)kGroupLanes, end - q);
 #pragma unroll
     for (int b0 = 0; b0 < kGroupLanes; b0 += UB) {
       if (b0 < n) {
-        RawRow<T, VPL> u[UB];
-        int32_t rows[UB];
+        RawRow<SrcT, VPL> u[UB];
+        uint32_t rows[UB];
         float coefs[UB];
         uint32_t lens[UB];
 #pragma unroll
         for (int b = 0; b < UB; ++b) {
-          rows[b] = __shfl(t.row, b0 + b, kGroupLanes);
+          rows[b] = (uint32_t)__shfl((int)t.row, b0 + b, kGroupLanes);
           coefs[b] = __shfl(t.coef, b0 + b, kGroupLanes);
           lens[b] = __shfl(t.where, b0 + b, kGroupLanes) & 0xffffu;
-          const int32_t center = __shfl(t.center, b0 + b, kGroupLanes);
-          if (b0 + b < n) load_raw<VPL>(w_in, center, a.dim, l16, u[b]);
+          const int32_t src = __shfl(t.center, b0 + b, kGroupLanes);
+          if (b0 + b < n) {
+            if constexpr (kStage) load_stage<T, VPL>(a.stage_delta, src, a.dim, l16, u[b]);
+            else load_raw<VPL>(w_src, src, a.dim, l16, u[b]);
+          }
         }
 #pragma unroll
         for (int b = 0; b < UB; ++b) {
           if (b0 + b < n) {
             if (rows[b] != cur_row) {
-              if (cur_row >= 0) flush();
+              if (cur_row != kNoRow) flush();
               cur_row = rows[b];
               cur_long = lens[b] > kLongRow;
-              zero<VPL>(acc);
-              if (!cur_long) load_row<VPL>(static_cast<const T*>(w_out), cur_row, a.dim, l16, old);
+              cur_terms = 0;
+#pragma unroll
+              for (int x = 0; x < 4 * VPL; ++x) acc[x] = 0;
+              if (!cur_long)
+                load_row<VPL>(static_cast<const T*>(w_dst), (int64_t)(cur_row - key_base), a.dim, l16, old);
             }
-            axpy<VPL>(acc, coefs[b], u[b]);
+            fix_axpy<VPL>(acc, (double)coefs[b] * kFixScale, peak, u[b]);
+            peak_c = fmaxf(peak_c, fabsf(coefs[b]));
+            ++cur_terms;
           }
         }
       }
     }
   }
+  if (!(peak * peak_c < kFixPeak)) *a.bad_ids = 1u;   // (also true for NaN)
   // Last pending row of this group.  Groups of a block hold consecutive slices,
   // so a row with very many terms is pending in many of them at once: their
   // partial sums are added up in LDS first and leave the block as one update
   // of the side buffer (16 times fewer atomics on the hottest rows).
-  const bool pending_long = cur_row >= 0 && cur_long;
-  if (cur_row >= 0 && !cur_long) flush();
+  const bool pending_long = cur_row != kNoRow && cur_long;
+  if (cur_row != kNoRow && !cur_long) flush();
   if (a.update_lds_bytes == 0) {          // rows too wide for the LDS stage
     if (pending_long) flush();
     return;
   }
-  extern __shared__ float comb_s[];       // [kGroupsPerBlock][dim] partial sums, then the row ids
-  int32_t* comb_row = reinterpret_cast<int32_t*>(comb_s + kGroupsPerBlock * a.dim);
-  if (l16 == 0) comb_row[group_in_block] = pending_long ? cur_row : -1;
+  extern __shared__ unsigned long long comb_s[];   // [kGroupsPerBlock][dim] partial sums, then the row ids
+  uint32_t* comb_row = reinterpret_cast<uint32_t*>(comb_s + kGroupsPerBlock * a.dim);
+  if (l16 == 0) comb_row[group_in_block] = pending_long ? cur_row : kNoRow;
   if (pending_long) {
-    float4* mine = reinterpret_cast<float4*>(comb_s + group_in_block * a.dim);
+    settle();
+    unsigned long long* mine = comb_s + group_in_block * a.dim;
 #pragma unroll
     for (int v = 0; v < VPL; ++v) {
       const int q = natural_q<T>(v, l16);
-      if (q < dim4) mine[q] = acc[v];
+      if (q < dim4) {
+#pragma unroll
+        for (int x = 0; x < 4; ++x) mine[4 * q + x] = acc[4 * v + x];
+      }
     }
   }
   __syncthreads();
   if (pending_long && (group_in_block == 0 || comb_row[group_in_block - 1] != cur_row)) {
     for (int g2 = group_in_block + 1; g2 < kGroupsPerBlock && comb_row[g2] == cur_row; ++g2) {
-      const float4* other = reinterpret_cast<const float4*>(comb_s + g2 * a.dim);
+      const unsigned long long* other = comb_s + g2 * a.dim;
 #pragma unroll
       for (int v = 0; v < VPL; ++v) {
         const int q = natural_q<T>(v, l16);
         if (q < dim4) {
-          const float4 o = other[q];
-          acc[v].x += o.x; acc[v].y += o.y; acc[v].z += o.z; acc[v].w += o.w;
+#pragma unroll
+          for (int x = 0; x < 4; ++x) acc[4 * v + x] += other[4 * q + x];
         }
       }
     }
-    flush();
+    flush_long();
   }
 }
 
-// element-wise row helpers for the small follow-up kernels (natural order)
+// element-wise row helpers for the finishing kernel (natural order)
 __device__ __forceinline__ float elem_load(const float* row, int e) { return row[e]; }
 template <typename T, if_16bit<T> = 0>
 __device__ __forceinline__ float elem_load(const T* row, int e) { return T::lo((uint32_t)row[e].bits); }
@@ -809,46 +975,26 @@ __device__ __forceinline__ void elem_store(float* row, int e, float v) { row[e] 
 template <typename T, if_16bit<T> = 0>
 __device__ __forceinline__ void elem_store(T* row, int e, float v) { row[e].bits = (uint16_t)T::round(v); }
 
-// ---- long_rows: w_out[row] = round(old + side buffer) --------------------------------------
+// ---- finish: table[row] = round(old + side buffer) for the long rows ------------------------
 // Side-buffer slot s belongs to the long row whose first term lies in
 // [s << kLongShift, (s+1) << kLongShift): that row then also owns the last
-// position of the window.
+// position of the window.  The last block of the launch adds up the per-block
+// loss partials instead (in a fixed order, so the loss is reproducible); a bad id
+// or an out-of-range product seen by an earlier kernel turns it into NaN.
+// which: 0 = long rows of both tables and the loss; 1 = context-table keys only, no loss;
+// 2 = input-table keys and the loss.  With one table on both sides a row can be long under
+// both of its keys, and its two read-modify-writes must not overlap: the context-table keys
+// are then finished before the input-table keys are summed.
 template <typename T>
-__global__ __launch_bounds__(kSgnsThreads) void sgns_long_rows_kernel(SgnsArgs a) {
-  T* w_out = static_cast<T*>(a.dst_out);
-  const int l16 = threadIdx.x & (kGroupLanes - 1);
-  const int64_t s = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
-  const int64_t last_pos = ((s + 1) << kLongShift) - 1;
-  if (last_pos >= a.num_terms) return;
-  const Term t = a.sorted[last_pos];
-  if ((t.where & 0xffffu) <= kLongRow) return;
-  const int64_t first_pos = (int64_t)a.cnt[t.row];
-  if ((first_pos >> kLongShift) != s) return;
-  const float* src = a.long_acc + s * (int64_t)a.dim;
-  T* dst = w_out + t.row * (int64_t)a.dim;
-  if (a.sq_out != nullptr) {
-    float* sq = a.sq_out + t.row * (int64_t)a.dim;
-    for (int e = l16; e < a.dim; e += kGroupLanes) {
-      const float d = src[e];
-      elem_store(dst, e, elem_load(dst, e) + a.c1 * d);
-      sq[e] += a.c2 * d * d;
-    }
-    return;
-  }
-  for (int e = l16; e < a.dim; e += kGroupLanes) elem_store(dst, e, elem_load(dst, e) + src[e]);
-}
-
-// ---- owners / merge / apply: staged centre-row gradients into w_in -----------------------
-// The last block of the launch adds up the per-block loss partials instead (in a fixed
-// order, so the loss is reproducible); a bad id seen by an earlier kernel turns it into NaN.
-__global__ __launch_bounds__(256) void sgns_owner_kernel(SgnsArgs a) {
+__global__ __launch_bounds__(kSgnsThreads) void sgns_finish_kernel(SgnsArgs a, int which) {
   if (blockIdx.x == gridDim.x - 1) {
-    __shared__ double sum_s[256];
+    if (which == 1) return;
+    __shared__ double sum_s[kSgnsThreads];
     double acc = 0.0;
-    for (int64_t i = threadIdx.x; i < a.forward_blocks; i += 256) acc += a.loss_partials[i];
+    for (int64_t i = threadIdx.x; i < a.forward_blocks; i += kSgnsThreads) acc += a.loss_partials[i];
     sum_s[threadIdx.x] = acc;
     __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
+    for (int w = kSgnsThreads / 2; w > 0; w >>= 1) {
       if ((int)threadIdx.x < w) sum_s[threadIdx.x] += sum_s[threadIdx.x + w];
       __syncthreads();
     }
@@ -856,70 +1002,45 @@ __global__ __launch_bounds__(256) void sgns_owner_kernel(SgnsArgs a) {
       *a.loss_out = (*a.bad_ids != 0u) ? __longlong_as_double(0x7ff8000000000000ll) : sum_s[0];
     return;
   }
-  const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= a.num_pairs) return;
-  const int32_t c = a.stage_center[s];
-  if (c >= 0) atomicMin(a.owner + c, (uint32_t)s);
-}
-
-// Every staged slot that does not own its centre adds its gradient into the
-// owner's slot (fp32 atomics on the staging buffer, 64 contiguous bytes per
-// instruction of a group).  A group looks at 16 slots at once, one per lane,
-// and then walks only the slots that have work.
-__global__ __launch_bounds__(kSgnsThreads) void sgns_merge_kernel(SgnsArgs a) {
   const int l16 = threadIdx.x & (kGroupLanes - 1);
-  const int64_t group = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
-  const int64_t s_mine = group * kGroupLanes + l16;
-  int64_t owner_mine = -1;                    // >= 0: this lane's slot must be merged into owner
-  if (s_mine < a.num_pairs) {
-    const int32_t c = a.stage_center[s_mine];
-    if (c >= 0) {
-      const int64_t owner = (int64_t)a.owner[c];
-      if (owner != s_mine) owner_mine = owner;
+  const int64_t s = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
+  const int64_t last_pos = ((s + 1) << kLongShift) - 1;
+  if (last_pos >= (int64_t)a.cnt[2 * a.num_nodes]) return;
+  const Term t = a.sorted[last_pos];
+  if ((t.where & 0xffffu) <= kLongRow) return;
+  const int64_t first_pos = (int64_t)a.cnt[t.row];
+  if ((first_pos >> kLongShift) != s) return;
+  const bool input_row = (int64_t)t.row >= a.num_nodes;
+  if (which != 0 && input_row != (which == 2)) return;
+  const int64_t row = input_row ? (int64_t)t.row - a.num_nodes : (int64_t)t.row;
+  const unsigned long long* src = reinterpret_cast<const unsigned long long*>(a.long_acc) + s * (int64_t)a.dim;
+  T* dst = static_cast<T*>(input_row ? a.dst_in : a.dst_out) + row * (int64_t)a.dim;
+  float* sq = input_row ? a.sq_in : a.sq_out;
+  if (sq != nullptr) {
+    sq += row * (int64_t)a.dim;
+    for (int e = l16; e < a.dim; e += kGroupLanes) {
+      const double d = fix_value(src[e]);
+      elem_store(dst, e, (float)((double)elem_load(dst, e) + (double)a.c1 * d));
+      sq[e] = (float)((double)sq[e] + (double)a.c2 * d * d);
     }
+    return;
   }
-  for (int b = 0; b < kGroupLanes; ++b) {
-    const int64_t owner = __shfl(owner_mine, b, kGroupLanes);
-    if (owner < 0) continue;
-    const float* src = a.stage_delta + (group * kGroupLanes + b) * (int64_t)a.dim;
-    float* dst = a.stage_delta + owner * (int64_t)a.dim;
-    for (int e = l16; e < a.dim; e += kGroupLanes) unsafeAtomicAdd(dst + e, src[e]);
-  }
-}
-
-template <typename T>
-__global__ __launch_bounds__(kSgnsThreads) void sgns_apply_kernel(SgnsArgs a) {
-  T* w_in = static_cast<T*>(a.dst_in);
-  const int l16 = threadIdx.x & (kGroupLanes - 1);
-  const int64_t group = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
-  const int64_t s_mine = group * kGroupLanes + l16;
-  int32_t center_mine = -1;                   // >= 0: this lane's slot owns that centre
-  if (s_mine < a.num_pairs) {
-    const int32_t c = a.stage_center[s_mine];
-    if (c >= 0 && (int64_t)a.owner[c] == s_mine) center_mine = c;
-  }
-  for (int b = 0; b < kGroupLanes; ++b) {
-    const int32_t c = __shfl(center_mine, b, kGroupLanes);
-    if (c < 0) continue;
-    const float* src = a.stage_delta + (group * kGroupLanes + b) * (int64_t)a.dim;
-    T* dst = w_in + c * (int64_t)a.dim;
-    if (a.sq_in != nullptr) {
-      float* sq = a.sq_in + c * (int64_t)a.dim;
-      for (int e = l16; e < a.dim; e += kGroupLanes) {
-        const float d = -a.lr * src[e];
-        elem_store(dst, e, elem_load(dst, e) + a.c1 * d);
-        sq[e] += a.c2 * d * d;
-      }
-      continue;
-    }
-    for (int e = l16; e < a.dim; e += kGroupLanes)
-      elem_store(dst, e, elem_load(dst, e) - a.lr * src[e]);
-  }
+  for (int e = l16; e < a.dim; e += kGroupLanes)
+    elem_store(dst, e, (float)((double)elem_load(dst, e) + fix_value(src[e])));
 }
 
 // ---- host side -----------------------------------------------------------------------------
+// Work per 16-lane group: large batches fill the chip many times over, so long runs per
+// group amortise the row loads of a run of equal centres; small batches are cut finer so
+// that every compute unit gets work and the dependent loads of a group stay few.
+static int chunk_pairs_for(int64_t num_pairs) {
+  return num_pairs >= (1 << 20) ? 16 : (num_pairs >= (1 << 18) ? 8 : 4);
+}
+static int slice_terms_for(int64_t num_pairs) {
+  return num_pairs >= (1 << 20) ? 128 : (num_pairs >= (1 << 18) ? 64 : 32);
+}
 static int64_t forward_blocks_for(int64_t num_pairs) {
-  return ceil_div(ceil_div(num_pairs, kChunkPairs), kGroupsPerBlock);
+  return ceil_div(ceil_div(num_pairs, chunk_pairs_for(num_pairs)), kGroupsPerBlock);
 }
 
 struct SgnsPlan {
@@ -927,12 +1048,12 @@ struct SgnsPlan {
   float* g;
   uint32_t* rank;
   uint32_t* cnt;
-  uint32_t* owner;
   uint32_t* tile_sums;
   uint32_t* bad_ids;
   Term* sorted;
-  float* long_acc;
+  long long* long_acc;
   int32_t* stage_center;
+  uint32_t* stage_rank;
   float* stage_delta;
   int64_t long_slots;
   size_t bytes;
@@ -943,18 +1064,18 @@ static SgnsPlan plan_sgns(void* ws, int64_t num_pairs, int64_t num_nodes, int32_
   SgnsPlan p;
   const size_t b = (size_t)(num_pairs > 0 ? num_pairs : 1);
   const size_t terms = b * (size_t)(k + 1);
-  const size_t n1 = (size_t)(num_nodes > 0 ? num_nodes : 1) + 1;
-  p.long_slots = (int64_t)(terms >> kLongShift) + 1;
+  const size_t keys1 = 2 * (size_t)(num_nodes > 0 ? num_nodes : 1) + 1;
+  p.long_slots = (int64_t)((terms + b) >> kLongShift) + 1;
   p.loss_partials = cv.take<double>((size_t)forward_blocks_for((int64_t)b));
   p.g = cv.take<float>(terms);
   p.rank = cv.take<uint32_t>(terms);
-  p.cnt = cv.take<uint32_t>(n1);
-  p.owner = cv.take<uint32_t>(n1);
-  p.tile_sums = cv.take<uint32_t>((size_t)ceil_div((int64_t)n1, kScanTile));
+  p.cnt = cv.take<uint32_t>(keys1 + 3);                   // cleared 16 bytes at a time
+  p.tile_sums = cv.take<uint32_t>((size_t)ceil_div((int64_t)keys1, kScanTile));
   p.bad_ids = cv.take<uint32_t>(1);
-  p.sorted = cv.take<Term>(terms);
-  p.long_acc = cv.take<float>((size_t)p.long_slots * (size_t)dim);
+  p.sorted = cv.take<Term>(terms + b);
+  p.long_acc = cv.take<long long>((size_t)p.long_slots * (size_t)dim);
   p.stage_center = cv.take<int32_t>(b);
+  p.stage_rank = cv.take<uint32_t>(b);
   p.stage_delta = cv.take<float>(b * (size_t)dim);
   p.bytes = cv.used;
   return p;
@@ -962,51 +1083,49 @@ static SgnsPlan plan_sgns(void* ws, int64_t num_pairs, int64_t num_nodes, int32_
 
 template <typename T, int VPL, int RB, int UB>
 static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
-  const int64_t n1 = a.num_nodes + 1;
-  const int64_t tiles = ceil_div(n1, kScanTile);
-  const int64_t long4 = a.long_slots * (int64_t)(a.dim >> 2);
-  sgns_clear_kernel<<<(unsigned)ceil_div(max(n1, long4), 256), 256, 0, stream>>>(
-      a.cnt, a.owner, n1, (float4*)a.long_acc, long4, a.bad_ids);
+  const int64_t keys1 = 2 * a.num_nodes + 1;
+  const int64_t tiles = ceil_div(keys1, kScanTile);
+  const int64_t keys4 = ceil_div(keys1, 4);
+  sgns_clear_kernel<<<(unsigned)ceil_div(keys4, 256), 256, 0, stream>>>((uint4*)a.cnt, keys4, a.bad_ids);
   GS_LAUNCH_CHECK();
-  const size_t idx_lds = (size_t)kGroupsPerBlock * kChunkPairs * (a.k + 2) * sizeof(int32_t);
+  const size_t idx_lds = (size_t)kGroupsPerBlock * a.chunk_pairs * (a.k + 2) * sizeof(int32_t);
   sgns_forward_kernel<T, VPL, RB><<<(unsigned)(a.forward_blocks_per_xcd * 8), kSgnsThreads, idx_lds,
                                    stream>>>(a);
   GS_LAUNCH_CHECK();
-  scan_reduce_kernel<<<(unsigned)tiles, kScanThreads, 0, stream>>>(a.cnt, n1, a.tile_sums);
+  scan_reduce_kernel<<<(unsigned)tiles, kScanThreads, 0, stream>>>(a.cnt, keys1, a.tile_sums);
   GS_LAUNCH_CHECK();
   const int raw_sums = tiles <= kFewTiles ? 1 : 0;
   if (!raw_sums) {
     scan_tiles_kernel<<<1, 1024, 0, stream>>>(a.tile_sums, tiles);
     GS_LAUNCH_CHECK();
   }
-  scan_apply_kernel<<<(unsigned)tiles, kScanThreads, 0, stream>>>(a.cnt, n1, a.tile_sums, raw_sums);
+  scan_apply_kernel<<<(unsigned)tiles, kScanThreads, 0, stream>>>(a.cnt, keys1, a.tile_sums, raw_sums);
   GS_LAUNCH_CHECK();
-  sgns_place_kernel<<<(unsigned)ceil_div(a.num_terms, 256), 256, 0, stream>>>(a);
+  sgns_place_kernel<<<(unsigned)ceil_div(a.num_terms + a.num_pairs, 256), 256, 0, stream>>>(a);
   GS_LAUNCH_CHECK();
-  const int64_t update_groups = ceil_div(a.num_terms, kSlice);
-  const unsigned update_blocks = (unsigned)ceil_div(update_groups, kGroupsPerBlock);
+  // context-table keys: exactly num_terms positions; input-table keys: at most one per pair
+  const unsigned out_blocks = (unsigned)ceil_div(ceil_div(a.num_terms, a.slice_terms), kGroupsPerBlock);
+  const unsigned in_blocks = (unsigned)ceil_div(ceil_div(a.num_pairs, a.slice_terms), kGroupsPerBlock);
+  const size_t lds = (size_t)a.update_lds_bytes;
+  const unsigned finish_blocks = (unsigned)ceil_div(a.long_slots, kGroupsPerBlock) + 1;
+  const bool one_table = a.snap != nullptr;
   if constexpr (std::is_same<T, float>::value) {
-    if (a.sq_out != nullptr)
-      sgns_update_kernel<T, VPL, UB, true><<<update_blocks, kSgnsThreads, (size_t)a.update_lds_bytes,
-                                            stream>>>(a);
-    else
-      sgns_update_kernel<T, VPL, UB, false><<<update_blocks, kSgnsThreads, (size_t)a.update_lds_bytes,
-                                             stream>>>(a);
+    if (a.sq_out != nullptr) {
+      sgns_update_kernel<T, VPL, UB, true, false><<<out_blocks, kSgnsThreads, lds, stream>>>(a);
+      sgns_update_kernel<T, VPL, UB, true, true><<<in_blocks, kSgnsThreads, lds, stream>>>(a);
+    } else {
+      sgns_update_kernel<T, VPL, UB, false, false><<<out_blocks, kSgnsThreads, lds, stream>>>(a);
+      if (one_table) sgns_finish_kernel<T><<<finish_blocks, kSgnsThreads, 0, stream>>>(a, 1);
+      sgns_update_kernel<T, VPL, UB, false, true><<<in_blocks, kSgnsThreads, lds, stream>>>(a);
+    }
   } else {
-    sgns_update_kernel<T, VPL, UB, false><<<update_blocks, kSgnsThreads, (size_t)a.update_lds_bytes,
-                                           stream>>>(a);
+    sgns_update_kernel<T, VPL, UB, false, false><<<out_blocks, kSgnsThreads, lds, stream>>>(a);
+    if (one_table) sgns_finish_kernel<T><<<finish_blocks, kSgnsThreads, 0, stream>>>(a, 1);
+    sgns_update_kernel<T, VPL, UB, false, true><<<in_blocks, kSgnsThreads, lds, stream>>>(a);
   }
   GS_LAUNCH_CHECK();
-  sgns_long_rows_kernel<T><<<(unsigned)ceil_div(a.long_slots, kGroupsPerBlock), kSgnsThreads, 0,
-                            stream>>>(a);
-  GS_LAUNCH_CHECK();
-  // per centre, the lowest staging slot that holds it; one more block sums the loss
-  sgns_owner_kernel<<<(unsigned)ceil_div(a.num_pairs, 256) + 1, 256, 0, stream>>>(a);
-  GS_LAUNCH_CHECK();
-  const unsigned slot_blocks = (unsigned)ceil_div(a.num_pairs, kSgnsThreads);   // a slot per lane
-  sgns_merge_kernel<<<slot_blocks, kSgnsThreads, 0, stream>>>(a);
-  GS_LAUNCH_CHECK();
-  sgns_apply_kernel<T><<<slot_blocks, kSgnsThreads, 0, stream>>>(a);
+  // long rows (of both tables, unless the context-table ones are done); one more block sums the loss
+  sgns_finish_kernel<T><<<finish_blocks, kSgnsThreads, 0, stream>>>(a, one_table ? 2 : 0);
   GS_LAUNCH_CHECK();
   return GS_OK;
 }
@@ -1163,17 +1282,19 @@ static int32_t run_sgns(void* w_in, void* w_out, void* dst_in, void* dst_out, in
   a.g = p.g;
   a.rank = p.rank;
   a.cnt = p.cnt;
-  a.owner = p.owner;
   a.tile_sums = p.tile_sums;
   a.bad_ids = p.bad_ids;
   a.sorted = p.sorted;
   a.long_acc = p.long_acc;
   a.stage_center = p.stage_center;
+  a.stage_rank = p.stage_rank;
   a.stage_delta = p.stage_delta;
+  a.chunk_pairs = chunk_pairs_for(num_pairs);
+  a.slice_terms = slice_terms_for(num_pairs);
   a.loss_partials = p.loss_partials;
   a.forward_blocks = forward_blocks_for(num_pairs);
   a.forward_blocks_per_xcd = ceil_div(a.forward_blocks, 8);
-  a.update_lds_bytes = dim <= 512 ? kGroupsPerBlock * dim * (int)sizeof(float) + 64 : 0;
+  a.update_lds_bytes = dim <= 256 ? kGroupsPerBlock * dim * (int)sizeof(long long) + 64 : 0;
   a.loss_out = loss_sum_out;
   // float4 registers per lane for one row: 16 lanes x 4 floats = 64 elements each
   const int vpl = (dim + 63) / 64;

@@ -9,6 +9,8 @@ import numpy as np
 import pytest
 import torch
 
+from tolerances import assert_emb_close
+
 pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
@@ -234,7 +236,7 @@ def test_line_first_order_and_optimizer_steps_full_batch(gs, oracle, big):
     want = oracle.sgns_momentum_step(*host, hc, ho, hn, 0.025, 0.9)
     assert abs(float(loss.item()) - want) <= 1e-5 * abs(want)
     for t, h in zip(tabs, host):
-        assert (np.abs(t.cpu().numpy() - h) <= 1e-5 + 1e-6 * np.abs(h)).all()
+        assert_emb_close(t.cpu().numpy(), h)
 
     # Adam, first iteration (moments from zero), on the model the momentum step left (the
     # oracle's copy on both sides)

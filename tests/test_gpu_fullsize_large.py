@@ -17,6 +17,8 @@ import numpy as np
 import pytest
 import torch
 
+from tolerances import HALF_FLIP_FRACTION, emb_bound
+
 pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
@@ -45,13 +47,13 @@ def _rows(table, ids):
 
 
 def _check_rows(got, want, dtype, tally):
-    """fp32: 1e-5 max-abs.  bf16: every element within one bf16 step (or 1e-5 where the sum
-    cancels); the number of elements that are not bit-identical is tallied for the caller."""
+    """fp32: 1e-5 max-abs.  bf16: every element within one bf16 step (or the fp32 bound where
+    the sum cancels); the number of elements that are not bit-identical is tallied for the caller."""
     if dtype == "bf16":
         near = np.abs(got.astype(np.int32) - want.astype(np.int32)) <= 1
         gv = (got.astype(np.uint32) << 16).view(np.float32)
         wv = (want.astype(np.uint32) << 16).view(np.float32)
-        assert bool((near | (np.abs(gv - wv) <= 1e-5)).all())
+        assert bool((near | (np.abs(gv - wv) <= emb_bound(wv))).all())
         tally[0] += int((got != want).sum())
         tally[1] += got.size
     else:
@@ -214,10 +216,9 @@ def _run_workload(gs, oracle, index, num_walks):
             oracle.sgns_step(t_in, t_out, m_c, m_o, m_n, lr, dtype=odt)
             _check_rows(_rows(w_in, [node])[0], t_in[0], wl.dtype, tally)
 
-    # the sample is dominated by the busiest rows (thousands of fp32 terms each), where a
-    # sum is likeliest to land on a bf16 rounding boundary: allow 5 in 1000 to round the other way
+    # elements that rounded the other way (bf16 tables): the same fraction as everywhere
     if tally[1]:
-        assert tally[0] <= 5e-3 * tally[1], tally
+        assert tally[0] <= max(1.0, HALF_FLIP_FRACTION["bf16"] * tally[1]), tally
 
 
 def test_workload3_full_size(gs, oracle):

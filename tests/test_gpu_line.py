@@ -7,8 +7,7 @@ import torch
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-LOSS_RTOL = 1e-5
-EMB_ATOL = 1e-5
+from tolerances import EMB_ATOL, LOSS_RTOL, assert_half_close  # noqa: E402
 
 
 @pytest.fixture(scope="module")
@@ -168,12 +167,8 @@ def test_line1_step(gs, oracle, dim, k, b, dtype):
         torch.cuda.synchronize()
         assert abs(float(loss.item()) - want) <= LOSS_RTOL * abs(want)
         if dtype == "bf16":
-            f32 = lambda bits: (bits.astype(np.uint32) << 16).view(np.float32)  # noqa: E731
-            got = _bf16_bits(d_w)
             # two roundings per element: a flip in the first moves the second by one step
-            near = np.abs(got.astype(np.int32) - h_w.astype(np.int32)) <= 2
-            assert (near | (np.abs(f32(got) - f32(h_w)) <= EMB_ATOL)).all()
-            assert (got != h_w).mean() <= 2e-3
+            assert_half_close(_bf16_bits(d_w), h_w, "bf16", steps=2)
             d_w.copy_(torch.from_numpy(h_w.view(np.int16)).view(torch.bfloat16))
         else:
             assert np.abs(d_w.cpu().numpy() - h_w).max() <= EMB_ATOL
