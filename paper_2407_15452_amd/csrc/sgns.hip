@@ -57,6 +57,8 @@ namespace gs {
 constexpr int kSgnsThreads = 256;
 constexpr int kGroupLanes = 16;
 constexpr int kGroupsPerBlock = kSgnsThreads / kGroupLanes;
+constexpr int kStageSlice = 8;     // staged gradients per 16-lane group in the input-table pass: they are
+                                   // few (one per run of equal centres), so short slices keep the chip busy
 constexpr uint32_t kLongRow = 256; // rows with more terms than this go through the side buffer
 constexpr int kLongShift = 8;      // log2(kLongRow): side-buffer slot = first term position >> 8
 constexpr int kScanThreads = 256;
@@ -409,6 +411,16 @@ __device__ __forceinline__ void stage_flush(const SgnsArgs& a, int64_t slot, int
   }
 }
 
+// largest magnitude among the elements a lane holds of a row
+template <int VPL>
+__device__ __forceinline__ float row_peak(const float4 (&r)[VPL]) {
+  float m = 0.f;
+#pragma unroll
+  for (int v = 0; v < VPL; ++v)
+    m = fmaxf(fmaxf(m, fmaxf(fabsf(r[v].x), fabsf(r[v].y))), fmaxf(fabsf(r[v].z), fabsf(r[v].w)));
+  return m;
+}
+
 template <typename T, int VPL, int RB>
 __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) {
   extern __shared__ int32_t idx_s[];              // per group: centres[16], rows[16][K+1]
@@ -460,12 +472,20 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
   int32_t cur_c = -1;
   int flushes = 0;
   float loss = 0.f;
+  // The update kernels add products coef * element exactly while these stay below 32768:
+  // coef is -lr * g with |g| <= 1 times an element of an input row, or -lr times an element
+  // of a staged gradient.  Both kinds of rows pass through this kernel, which checks them.
+  float peak = 0.f;
 
   for (int p = 0; p < count; ++p) {
     const int32_t c = cen_s[p];
     if (c != cur_c) {
-      if (cur_c >= 0) stage_flush<T, VPL>(a, first + flushes++, cur_c, l16, du);
+      if (cur_c >= 0) {
+        peak = fmaxf(peak, row_peak<VPL>(du));
+        stage_flush<T, VPL>(a, first + flushes++, cur_c, l16, du);
+      }
       load_row<VPL>(w_in, c, a.dim, l16, u);
+      peak = fmaxf(peak, row_peak<VPL>(u));
       if (a.snap != nullptr) {              // one-table mode: keep the row as it is now
         RawRow<T, VPL> keep;
         load_raw<VPL>(w_in, c, a.dim, l16, keep);
@@ -512,8 +532,12 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
       if (mine) { a.g[e0 + my_j] = g_mine; a.rank[e0 + my_j] = rk; }
     }
   }
-  if (cur_c >= 0) stage_flush<T, VPL>(a, first + flushes++, cur_c, l16, du);
+  if (cur_c >= 0) {
+    peak = fmaxf(peak, row_peak<VPL>(du));
+    stage_flush<T, VPL>(a, first + flushes++, cur_c, l16, du);
+  }
   if (l16 >= flushes && l16 < count) a.stage_center[first + l16] = -1;
+  if (!(peak * fabsf(a.lr) < kFixPeak)) *a.bad_ids = 1u;   // (also taken for NaN)
 
   loss = row_sum16(loss);
   if (l16 == 0) loss_s[group_in_block] = loss;
@@ -701,50 +725,59 @@ __global__ __launch_bounds__(256) void sgns_place_kernel(SgnsArgs a) {
 }
 
 // ---- update: one pass over the key-major terms of one table ----------------------------
+// Here a whole wave works on one row at a time: the fields of a term are broadcast
+// from the lane that holds it into scalar registers, so every branch (row change,
+// long row, end of slice) is uniform and the per-row epilogue runs once per row.
+// Lane l holds, for p < PPL, piece p*64 + l of a row; a piece is WPP 32-bit words of the
+// table's storage type (4, 8 or 16 bytes: 256, 512 or 1024 contiguous bytes per load
+// instruction), i.e. EPP = WPP (fp32) or 2 * WPP (16-bit) consecutive elements.
+//
 // Exact row sums: acc holds the sum of the result bits of fma(element, coef * 2^36,
 // kFixMagic), i.e. terms * kFixMagicBits + the sum of the rounded products (mod 2^64).
 __device__ __forceinline__ void fix_add(unsigned long long& acc, double c, float x) {
   acc += (unsigned long long)__double_as_longlong(__builtin_fma((double)x, c, kFixMagic));
 }
 
-template <int VPL>
-__device__ __forceinline__ void fix_axpy(unsigned long long (&acc)[4 * VPL], double c, float& peak,
-                                         const RawRow<float, VPL>& x) {
+template <typename T>
+struct Words { static constexpr int kPerWord = 2; };     // elements in a 32-bit word of a table
+template <>
+struct Words<float> { static constexpr int kPerWord = 1; };
+
+// one piece of WORDS 32-bit words, in a single load / store instruction
+template <int WORDS>
+__device__ __forceinline__ void load_words(const uint32_t* __restrict__ p, uint32_t (&w)[WORDS]) {
+  if constexpr (WORDS == 1) {
+    w[0] = *p;
+  } else if constexpr (WORDS == 2) {
+    const uint2 x = *reinterpret_cast<const uint2*>(p);
+    w[0] = x.x; w[1] = x.y;
+  } else {
+    static_assert(WORDS % 4 == 0, "pieces are 4, 8 or a multiple of 16 bytes");
 #pragma unroll
-  for (int v = 0; v < VPL; ++v) {
-    const float4 f = x.r[v];
-    fix_add(acc[4 * v + 0], c, f.x); fix_add(acc[4 * v + 1], c, f.y);
-    fix_add(acc[4 * v + 2], c, f.z); fix_add(acc[4 * v + 3], c, f.w);
-    peak = fmaxf(peak, fmaxf(fmaxf(fabsf(f.x), fabsf(f.y)), fmaxf(fabsf(f.z), fabsf(f.w))));
-  }
-}
-template <int VPL, typename T, if_16bit<T> = 0>
-__device__ __forceinline__ void fix_axpy(unsigned long long (&acc)[4 * VPL], double c, float& peak,
-                                         const RawRow<T, VPL>& b) {
-#pragma unroll
-  for (int w = 0; w < VPL / 2; ++w) {
-    const uint4 x = b.r[w];
-    const float f[8] = {T::lo(x.x), T::hi(x.x), T::lo(x.y), T::hi(x.y),
-                        T::lo(x.z), T::hi(x.z), T::lo(x.w), T::hi(x.w)};
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      fix_add(acc[8 * w + i], c, f[i]);
-      peak = fmaxf(peak, fabsf(f[i]));
+    for (int i = 0; i < WORDS / 4; ++i) {
+      const uint4 x = reinterpret_cast<const uint4*>(p)[i];
+      w[4 * i] = x.x; w[4 * i + 1] = x.y; w[4 * i + 2] = x.z; w[4 * i + 3] = x.w;
     }
   }
 }
-
-// a staged gradient row (fp32, natural element order) in the register layout of table type T
-template <typename T, int VPL>
-__device__ __forceinline__ void load_stage(const float* __restrict__ stage, int64_t slot, int dim, int l16,
-                                           RawRow<float, VPL>& x) {
-  const float4* p = reinterpret_cast<const float4*>(stage + slot * (int64_t)dim);
-  const int dim4 = dim >> 2;
+template <int WORDS>
+__device__ __forceinline__ void store_words(uint32_t* __restrict__ p, const uint32_t (&w)[WORDS]) {
+  if constexpr (WORDS == 1) {
+    *p = w[0];
+  } else if constexpr (WORDS == 2) {
+    *reinterpret_cast<uint2*>(p) = make_uint2(w[0], w[1]);
+  } else {
 #pragma unroll
-  for (int v = 0; v < VPL; ++v) {
-    const int q = natural_q<T>(v, l16);
-    x.r[v] = (q < dim4) ? p[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i = 0; i < WORDS / 4; ++i)
+      reinterpret_cast<uint4*>(p)[i] = make_uint4(w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]);
   }
+}
+
+// element i of a piece held as words of storage type T, widened exactly
+template <typename T, int WORDS>
+__device__ __forceinline__ float piece_elem(const uint32_t (&w)[WORDS], int i) {
+  if constexpr (std::is_same<T, float>::value) return __uint_as_float(w[i]);
+  else return (i & 1) ? T::hi(w[i >> 1]) : T::lo(w[i >> 1]);
 }
 
 // the exact sum as a double: net integer (terms * magic bits taken off) times 2^-36
@@ -752,214 +785,226 @@ __device__ __forceinline__ double fix_value(unsigned long long acc) {
   return (double)(long long)acc * kFixInvScale;
 }
 
-// table[row] = round(old + d), d given in fp64 per register element: the fp64 sum is
-// rounded to fp32 once, and from there to the 16-bit storage type
-template <int VPL>
-__device__ __forceinline__ void store_row_delta(float* __restrict__ table, int64_t row, int dim, int l16,
-                                                const float4 (&old)[VPL], const double (&d)[4 * VPL]) {
-  float4* p = reinterpret_cast<float4*>(table + row * (int64_t)dim);
-  const int dim4 = dim >> 2;
-#pragma unroll
-  for (int v = 0; v < VPL; ++v) {
-    const int q = v * kGroupLanes + l16;
-    if (q < dim4)
-      p[q] = make_float4((float)((double)old[v].x + d[4 * v + 0]), (float)((double)old[v].y + d[4 * v + 1]),
-                         (float)((double)old[v].z + d[4 * v + 2]), (float)((double)old[v].w + d[4 * v + 3]));
-  }
-}
-template <int VPL, typename T, if_16bit<T> = 0>
-__device__ __forceinline__ void store_row_delta(T* __restrict__ table, int64_t row, int dim, int l16,
-                                                const float4 (&old)[VPL], const double (&d)[4 * VPL]) {
-  uint4* p = reinterpret_cast<uint4*>(table + row * (int64_t)dim);
-  const int chunks = dim >> 3;
-#pragma unroll
-  for (int w = 0; w < VPL / 2; ++w) {
-    const int c = w * kGroupLanes + l16;
-    if (c < chunks) {
-      const float4 a = old[2 * w], b = old[2 * w + 1];
-      const double* s = d + 8 * w;
-      uint4 x;
-      x.x = pack16<T>((float)((double)a.x + s[0]), (float)((double)a.y + s[1]));
-      x.y = pack16<T>((float)((double)a.z + s[2]), (float)((double)a.w + s[3]));
-      x.z = pack16<T>((float)((double)b.x + s[4]), (float)((double)b.y + s[5]));
-      x.w = pack16<T>((float)((double)b.z + s[6]), (float)((double)b.w + s[7]));
-      p[c] = x;
-    }
-  }
+__device__ __forceinline__ uint32_t uniform_u32(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_readfirstlane((int)x);
 }
 
-// Ownership: a row with at most kLongRow terms is handled whole by the group
+// Ownership: a row with at most kLongRow terms is handled whole by the wave
 // whose slice holds its first term, which writes it once.  Longer rows are
 // handled slice by slice; their partial sums meet in the side buffer at slot
 // (position of the row's first term) >> kLongShift, which no two long rows can
 // share because each of them spans more than 2^kLongShift positions.
 // kStage = false: context-table keys, positions [0, num_terms), source rows from the input
 // table; kStage = true: input-table keys, the positions after them, source rows = staged
-// gradients.
-template <typename T, int VPL, int UB, bool kSq, bool kStage>
+// gradients (fp32, natural element order).
+template <typename T, int WPP, int PPL, int UB, bool kSq, bool kStage>
 __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
   static_assert(!kSq || std::is_same<T, float>::value, "second-moment tables are fp32");
-  using SrcT = std::conditional_t<kStage, float, T>;
-  // source rows: the input table, or the copies the forward kernel kept (one-table mode)
-  const T* __restrict__ w_src = static_cast<const T*>(a.snap != nullptr ? a.snap : a.w_in);
-  T* w_dst = static_cast<T*>(kStage ? a.dst_in : a.dst_out);   // destination rows (old value and result)
-  float* sq_dst = kStage ? a.sq_in : a.sq_out;
+  constexpr int kWaves = kSgnsThreads / 64;
+  constexpr int EPP = WPP * Words<T>::kPerWord;          // elements per piece
+  constexpr int EPL = EPP * PPL;                         // elements per lane
+  constexpr int SW = kStage ? EPP : WPP;                 // 32-bit words of a source piece
+  // source rows: the input table, or the copies the forward kernel kept (one-table mode),
+  // or the staged gradients
+  const uint32_t* __restrict__ src_base = reinterpret_cast<const uint32_t*>(
+      kStage ? static_cast<const void*>(a.stage_delta) : (a.snap != nullptr ? a.snap : a.w_in));
+  uint32_t* dst_base = reinterpret_cast<uint32_t*>(kStage ? a.dst_in : a.dst_out);
+  uint32_t* sq_base = reinterpret_cast<uint32_t*>(kStage ? a.sq_in : a.sq_out);
   const uint32_t key_base = kStage ? (uint32_t)a.num_nodes : 0u;
   const int64_t pos_lo = kStage ? a.num_terms : 0;
-  const int64_t pos_hi = kStage ? (int64_t)a.cnt[2 * a.num_nodes] : a.num_terms;
-  const int l16 = threadIdx.x & (kGroupLanes - 1);
-  const int64_t group = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
-  const int group_in_block = threadIdx.x / kGroupLanes;
-  const int64_t slice_begin = pos_lo + group * a.slice_terms;
+  // (scalars that come out of memory are made wave-uniform explicitly: loop bounds and the
+  // lane numbers of the broadcasts below must live in scalar registers)
+  const int64_t pos_hi = kStage ? (int64_t)uniform_u32(a.cnt[2 * a.num_nodes]) : a.num_terms;
+  const int lane = threadIdx.x & 63;
+  const int wave_in_block = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int64_t wave = (int64_t)blockIdx.x * kWaves + wave_in_block;
+  const int slice = kStage ? kStageSlice : a.slice_terms;
+  const int64_t slice_begin = pos_lo + wave * slice;
   const bool active = slice_begin < pos_hi;
-  const int64_t slice_end = min(slice_begin + a.slice_terms, pos_hi);
+  const int64_t slice_end = min(slice_begin + slice, pos_hi);
   const Term* __restrict__ sorted = a.sorted;
+  const int64_t src_row_words = kStage ? (int64_t)a.dim : (int64_t)a.dim / Words<T>::kPerWord;
+  const int64_t dst_row_words = (int64_t)a.dim / Words<T>::kPerWord;
+  bool piece_ok[PPL];                                    // piece p of this lane lies inside the row
+#pragma unroll
+  for (int p = 0; p < PPL; ++p) piece_ok[p] = (p * 64 + lane) * EPP < a.dim;
 
   int64_t begin = slice_begin, end = active ? slice_end : slice_begin;
   if (active) {
-    const uint32_t w0 = sorted[slice_begin].where;
+    const uint32_t w0 = uniform_u32(sorted[slice_begin].where);
     const uint32_t len0 = w0 & 0xffffu, pos0 = w0 >> 16;
-    if (len0 <= kLongRow && pos0 > 0) begin = slice_begin - pos0 + len0;   // owned by an earlier group
-    const uint32_t w1 = sorted[slice_end - 1].where;
+    if (len0 <= kLongRow && pos0 > 0) begin = slice_begin - pos0 + len0;   // owned by an earlier wave
+    const uint32_t w1 = uniform_u32(sorted[slice_end - 1].where);
     const uint32_t len1 = w1 & 0xffffu, pos1 = w1 >> 16;
     if (len1 <= kLongRow) end = (slice_end - 1) - pos1 + len1;             // finish the row we started
   }
 
-  unsigned long long acc[4 * VPL];
-  float4 old[VPL];
+  unsigned long long acc[EPL];
+  uint32_t old[PPL][WPP];
 #pragma unroll
-  for (int x = 0; x < 4 * VPL; ++x) acc[x] = 0;
-  zero<VPL>(old);
+  for (int x = 0; x < EPL; ++x) acc[x] = 0;
+#pragma unroll
+  for (int p = 0; p < PPL; ++p)
+#pragma unroll
+    for (int w = 0; w < WPP; ++w) old[p][w] = 0u;
   uint32_t cur_row = kNoRow;       // key of the row being summed (table row: cur_row - key_base)
   bool cur_long = false;
   uint32_t cur_terms = 0;          // terms added into acc since it was cleared
-  float peak = 0.f, peak_c = 0.f;  // largest |element| and |coef| seen by this lane
-  const int dim4 = a.dim >> 2;
 
-  // takes the magic bits of the terms off: acc becomes the net integer sum
+  // takes the magic bits of the terms off (their low word is zero): acc becomes the net sum
   auto settle = [&]() {
-    const unsigned long long off = (unsigned long long)cur_terms * kFixMagicBits;
+    const unsigned long long off = (unsigned long long)(cur_terms * (uint32_t)(kFixMagicBits >> 32)) << 32;
 #pragma unroll
-    for (int x = 0; x < 4 * VPL; ++x) acc[x] -= off;
+    for (int x = 0; x < EPL; ++x) acc[x] -= off;
   };
   auto flush_long = [&]() {
     unsigned long long* dst = reinterpret_cast<unsigned long long*>(a.long_acc) +
                               (int64_t)(a.cnt[cur_row] >> kLongShift) * a.dim;
 #pragma unroll
-    for (int v = 0; v < VPL; ++v) {
-      const int q = natural_q<T>(v, l16);
-      if (q < dim4) {
+    for (int p = 0; p < PPL; ++p) {
+      if (piece_ok[p]) {
 #pragma unroll
-        for (int x = 0; x < 4; ++x) atomicAdd(dst + 4 * q + x, acc[4 * v + x]);
+        for (int i = 0; i < EPP; ++i) atomicAdd(dst + (p * 64 + lane) * EPP + i, acc[p * EPP + i]);
       }
     }
+  };
+  // new = round(old + d) for the elements of one piece, packed back into storage words
+  auto write_piece = [&](uint32_t* row_words, int p, const uint32_t (&was)[WPP], const double* d) {
+    uint32_t out[WPP];
+    if constexpr (std::is_same<T, float>::value) {
+#pragma unroll
+      for (int i = 0; i < WPP; ++i)
+        out[i] = __float_as_uint((float)((double)__uint_as_float(was[i]) + d[i]));
+    } else {
+#pragma unroll
+      for (int i = 0; i < WPP; ++i)
+        out[i] = pack16<T>((float)((double)T::lo(was[i]) + d[2 * i]),
+                           (float)((double)T::hi(was[i]) + d[2 * i + 1]));
+    }
+    store_words<WPP>(row_words + (int64_t)(p * 64 + lane) * WPP, out);
   };
   auto flush = [&]() {
     settle();
     if (cur_long) {
       flush_long();
-    } else {
-      const int64_t r = (int64_t)(cur_row - key_base);
-      double d[4 * VPL];
+      return;
+    }
+    const int64_t r = (int64_t)(cur_row - key_base);
+    uint32_t* row_words = dst_base + r * dst_row_words;
 #pragma unroll
-      for (int x = 0; x < 4 * VPL; ++x) d[x] = fix_value(acc[x]);
+    for (int p = 0; p < PPL; ++p) {
+      if (!piece_ok[p]) continue;
+      double d[EPP];
+#pragma unroll
+      for (int i = 0; i < EPP; ++i) d[i] = fix_value(acc[p * EPP + i]);
       if constexpr (kSq) {
-        float4 old2[VPL];
-        load_row<VPL>(sq_dst, r, a.dim, l16, old2);
-        double d2[4 * VPL];
+        uint32_t* sq_words = sq_base + r * dst_row_words;
+        uint32_t old2[WPP];
+        load_words<WPP>(sq_words + (int64_t)(p * 64 + lane) * WPP, old2);
+        double d2[EPP];
 #pragma unroll
-        for (int x = 0; x < 4 * VPL; ++x) {
-          d2[x] = (double)a.c2 * d[x] * d[x];
-          d[x] *= (double)a.c1;
+        for (int i = 0; i < EPP; ++i) {
+          d2[i] = (double)a.c2 * d[i] * d[i];
+          d[i] *= (double)a.c1;
         }
-        store_row_delta<VPL>(w_dst, r, a.dim, l16, old, d);
-        store_row_delta<VPL>(sq_dst, r, a.dim, l16, old2, d2);
+        write_piece(row_words, p, old[p], d);
+        write_piece(sq_words, p, old2, d2);
       } else {
-        store_row_delta<VPL>(w_dst, r, a.dim, l16, old, d);
+        write_piece(row_words, p, old[p], d);
       }
     }
   };
 
-  for (int64_t q = begin; q < end; q += kGroupLanes) {
+  for (int64_t q = begin; q < end; q += 64) {
     Term t;
     t.row = kNoRow; t.center = 0; t.coef = 0.f; t.where = 0;
-    if (q + l16 < end) t = sorted[q + l16];
-    const int n = (int)min((int64_t)kGroupLanes, end - q);
+    if (q + lane < end) t = sorted[q + lane];
+    const int n = (int)min((int64_t)64, end - q);
+#pragma unroll 1
+    for (int b0 = 0; b0 < n; b0 += UB) {
+      uint32_t u[UB][PPL][SW];
 #pragma unroll
-    for (int b0 = 0; b0 < kGroupLanes; b0 += UB) {
-      if (b0 < n) {
-        RawRow<SrcT, VPL> u[UB];
-        uint32_t rows[UB];
-        float coefs[UB];
-        uint32_t lens[UB];
+      for (int b = 0; b < UB; ++b) {
+        if (b0 + b < n) {
+          const int64_t src = (int64_t)__builtin_amdgcn_readlane(t.center, b0 + b);
+          const uint32_t* row_words = src_base + src * src_row_words;
 #pragma unroll
-        for (int b = 0; b < UB; ++b) {
-          rows[b] = (uint32_t)__shfl((int)t.row, b0 + b, kGroupLanes);
-          coefs[b] = __shfl(t.coef, b0 + b, kGroupLanes);
-          lens[b] = __shfl(t.where, b0 + b, kGroupLanes) & 0xffffu;
-          const int32_t src = __shfl(t.center, b0 + b, kGroupLanes);
-          if (b0 + b < n) {
-            if constexpr (kStage) load_stage<T, VPL>(a.stage_delta, src, a.dim, l16, u[b]);
-            else load_raw<VPL>(w_src, src, a.dim, l16, u[b]);
+          for (int p = 0; p < PPL; ++p) {
+            if (piece_ok[p]) {
+              load_words<SW>(row_words + (int64_t)(p * 64 + lane) * SW, u[b][p]);
+            } else {
+#pragma unroll
+              for (int w = 0; w < SW; ++w) u[b][p][w] = 0u;
+            }
           }
         }
+      }
 #pragma unroll
-        for (int b = 0; b < UB; ++b) {
-          if (b0 + b < n) {
-            if (rows[b] != cur_row) {
-              if (cur_row != kNoRow) flush();
-              cur_row = rows[b];
-              cur_long = lens[b] > kLongRow;
-              cur_terms = 0;
+      for (int b = 0; b < UB; ++b) {
+        if (b0 + b < n) {
+          const uint32_t row = (uint32_t)__builtin_amdgcn_readlane((int)t.row, b0 + b);
+          if (row != cur_row) {
+            if (cur_row != kNoRow) flush();
+            cur_row = row;
+            cur_long = ((uint32_t)__builtin_amdgcn_readlane((int)t.where, b0 + b) & 0xffffu) > kLongRow;
+            cur_terms = 0;
 #pragma unroll
-              for (int x = 0; x < 4 * VPL; ++x) acc[x] = 0;
-              if (!cur_long)
-                load_row<VPL>(static_cast<const T*>(w_dst), (int64_t)(cur_row - key_base), a.dim, l16, old);
+            for (int x = 0; x < EPL; ++x) acc[x] = 0;
+            if (!cur_long) {
+              const uint32_t* row_words = dst_base + (int64_t)(cur_row - key_base) * dst_row_words;
+#pragma unroll
+              for (int p = 0; p < PPL; ++p)
+                if (piece_ok[p]) load_words<WPP>(row_words + (int64_t)(p * 64 + lane) * WPP, old[p]);
             }
-            fix_axpy<VPL>(acc, (double)coefs[b] * kFixScale, peak, u[b]);
-            peak_c = fmaxf(peak_c, fabsf(coefs[b]));
-            ++cur_terms;
           }
+          const double c =
+              (double)__uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(t.coef), b0 + b)) *
+              kFixScale;
+#pragma unroll
+          for (int p = 0; p < PPL; ++p)
+#pragma unroll
+            for (int i = 0; i < EPP; ++i) {
+              const float x = kStage ? __uint_as_float(u[b][p][i]) : piece_elem<T, SW>(u[b][p], i);
+              fix_add(acc[p * EPP + i], c, x);
+            }
+          ++cur_terms;
         }
       }
     }
   }
-  if (!(peak * peak_c < kFixPeak)) *a.bad_ids = 1u;   // (also true for NaN)
-  // Last pending row of this group.  Groups of a block hold consecutive slices,
-  // so a row with very many terms is pending in many of them at once: their
+  // Last pending row of this wave.  Waves of a block hold consecutive slices,
+  // so a row with very many terms is pending in several of them at once: their
   // partial sums are added up in LDS first and leave the block as one update
-  // of the side buffer (16 times fewer atomics on the hottest rows).
+  // of the side buffer.
   const bool pending_long = cur_row != kNoRow && cur_long;
   if (cur_row != kNoRow && !cur_long) flush();
   if (a.update_lds_bytes == 0) {          // rows too wide for the LDS stage
     if (pending_long) flush();
     return;
   }
-  extern __shared__ unsigned long long comb_s[];   // [kGroupsPerBlock][dim] partial sums, then the row ids
-  uint32_t* comb_row = reinterpret_cast<uint32_t*>(comb_s + kGroupsPerBlock * a.dim);
-  if (l16 == 0) comb_row[group_in_block] = pending_long ? cur_row : kNoRow;
+  extern __shared__ unsigned long long comb_s[];   // [kWaves][dim] partial sums, then the row ids
+  uint32_t* comb_row = reinterpret_cast<uint32_t*>(comb_s + kWaves * a.dim);
+  if (lane == 0) comb_row[wave_in_block] = pending_long ? cur_row : kNoRow;
   if (pending_long) {
     settle();
-    unsigned long long* mine = comb_s + group_in_block * a.dim;
+    unsigned long long* mine = comb_s + wave_in_block * a.dim;
 #pragma unroll
-    for (int v = 0; v < VPL; ++v) {
-      const int q = natural_q<T>(v, l16);
-      if (q < dim4) {
+    for (int p = 0; p < PPL; ++p) {
+      if (piece_ok[p]) {
 #pragma unroll
-        for (int x = 0; x < 4; ++x) mine[4 * q + x] = acc[4 * v + x];
+        for (int i = 0; i < EPP; ++i) mine[(p * 64 + lane) * EPP + i] = acc[p * EPP + i];
       }
     }
   }
   __syncthreads();
-  if (pending_long && (group_in_block == 0 || comb_row[group_in_block - 1] != cur_row)) {
-    for (int g2 = group_in_block + 1; g2 < kGroupsPerBlock && comb_row[g2] == cur_row; ++g2) {
+  if (pending_long && (wave_in_block == 0 || comb_row[wave_in_block - 1] != cur_row)) {
+    for (int g2 = wave_in_block + 1; g2 < kWaves && comb_row[g2] == cur_row; ++g2) {
       const unsigned long long* other = comb_s + g2 * a.dim;
 #pragma unroll
-      for (int v = 0; v < VPL; ++v) {
-        const int q = natural_q<T>(v, l16);
-        if (q < dim4) {
+      for (int p = 0; p < PPL; ++p) {
+        if (piece_ok[p]) {
 #pragma unroll
-          for (int x = 0; x < 4; ++x) acc[4 * v + x] += other[4 * q + x];
+          for (int i = 0; i < EPP; ++i) acc[p * EPP + i] += other[(p * 64 + lane) * EPP + i];
         }
       }
     }
@@ -1081,7 +1126,33 @@ static SgnsPlan plan_sgns(void* ws, int64_t num_pairs, int64_t num_nodes, int32_
   return p;
 }
 
-template <typename T, int VPL, int RB, int UB>
+// the two update passes (context-table keys, then input-table keys) in the piece layout that
+// fits the row: 64 lanes x WPP words x PPL pieces cover the row, UB source rows in flight
+template <typename T, int WPP, int PPL, int UB>
+static int32_t launch_updates(const SgnsArgs& a, hipStream_t stream) {
+  constexpr int kWaves = kSgnsThreads / 64;
+  // context-table keys: exactly num_terms positions; input-table keys: at most one per pair
+  const unsigned out_blocks = (unsigned)ceil_div(ceil_div(a.num_terms, a.slice_terms), kWaves);
+  const unsigned in_blocks = (unsigned)ceil_div(ceil_div(a.num_pairs, kStageSlice), kWaves);
+  const size_t lds = (size_t)a.update_lds_bytes;
+  const unsigned finish_blocks = (unsigned)ceil_div(a.long_slots, kGroupsPerBlock) + 1;
+  const bool one_table = a.snap != nullptr;
+  if constexpr (std::is_same<T, float>::value) {
+    if (a.sq_out != nullptr) {
+      sgns_update_kernel<T, WPP, PPL, UB, true, false><<<out_blocks, kSgnsThreads, lds, stream>>>(a);
+      sgns_update_kernel<T, WPP, PPL, UB, true, true><<<in_blocks, kSgnsThreads, lds, stream>>>(a);
+      GS_LAUNCH_CHECK();
+      return GS_OK;
+    }
+  }
+  sgns_update_kernel<T, WPP, PPL, UB, false, false><<<out_blocks, kSgnsThreads, lds, stream>>>(a);
+  if (one_table) sgns_finish_kernel<T><<<finish_blocks, kSgnsThreads, 0, stream>>>(a, 1);
+  sgns_update_kernel<T, WPP, PPL, UB, false, true><<<in_blocks, kSgnsThreads, lds, stream>>>(a);
+  GS_LAUNCH_CHECK();
+  return GS_OK;
+}
+
+template <typename T, int VPL, int RB>
 static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
   const int64_t keys1 = 2 * a.num_nodes + 1;
   const int64_t tiles = ceil_div(keys1, kScanTile);
@@ -1103,29 +1174,17 @@ static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
   GS_LAUNCH_CHECK();
   sgns_place_kernel<<<(unsigned)ceil_div(a.num_terms + a.num_pairs, 256), 256, 0, stream>>>(a);
   GS_LAUNCH_CHECK();
-  // context-table keys: exactly num_terms positions; input-table keys: at most one per pair
-  const unsigned out_blocks = (unsigned)ceil_div(ceil_div(a.num_terms, a.slice_terms), kGroupsPerBlock);
-  const unsigned in_blocks = (unsigned)ceil_div(ceil_div(a.num_pairs, a.slice_terms), kGroupsPerBlock);
-  const size_t lds = (size_t)a.update_lds_bytes;
-  const unsigned finish_blocks = (unsigned)ceil_div(a.long_slots, kGroupsPerBlock) + 1;
-  const bool one_table = a.snap != nullptr;
-  if constexpr (std::is_same<T, float>::value) {
-    if (a.sq_out != nullptr) {
-      sgns_update_kernel<T, VPL, UB, true, false><<<out_blocks, kSgnsThreads, lds, stream>>>(a);
-      sgns_update_kernel<T, VPL, UB, true, true><<<in_blocks, kSgnsThreads, lds, stream>>>(a);
-    } else {
-      sgns_update_kernel<T, VPL, UB, false, false><<<out_blocks, kSgnsThreads, lds, stream>>>(a);
-      if (one_table) sgns_finish_kernel<T><<<finish_blocks, kSgnsThreads, 0, stream>>>(a, 1);
-      sgns_update_kernel<T, VPL, UB, false, true><<<in_blocks, kSgnsThreads, lds, stream>>>(a);
-    }
-  } else {
-    sgns_update_kernel<T, VPL, UB, false, false><<<out_blocks, kSgnsThreads, lds, stream>>>(a);
-    if (one_table) sgns_finish_kernel<T><<<finish_blocks, kSgnsThreads, 0, stream>>>(a, 1);
-    sgns_update_kernel<T, VPL, UB, false, true><<<in_blocks, kSgnsThreads, lds, stream>>>(a);
-  }
-  GS_LAUNCH_CHECK();
+  const int row_bytes = a.dim * (int)sizeof(T);
+  int32_t rc;
+  if (row_bytes <= 256) rc = launch_updates<T, 1, 1, 16>(a, stream);
+  else if (row_bytes <= 512) rc = launch_updates<T, 2, 1, 16>(a, stream);
+  else if (row_bytes <= 1024) rc = launch_updates<T, 4, 1, 8>(a, stream);
+  else if (row_bytes <= 2048) rc = launch_updates<T, 4, 2, 4>(a, stream);
+  else rc = launch_updates<T, 4, 4, 2>(a, stream);
+  if (rc != GS_OK) return rc;
   // long rows (of both tables, unless the context-table ones are done); one more block sums the loss
-  sgns_finish_kernel<T><<<finish_blocks, kSgnsThreads, 0, stream>>>(a, one_table ? 2 : 0);
+  const unsigned finish_blocks = (unsigned)ceil_div(a.long_slots, kGroupsPerBlock) + 1;
+  sgns_finish_kernel<T><<<finish_blocks, kSgnsThreads, 0, stream>>>(a, a.snap != nullptr ? 2 : 0);
   GS_LAUNCH_CHECK();
   return GS_OK;
 }
@@ -1294,28 +1353,28 @@ static int32_t run_sgns(void* w_in, void* w_out, void* dst_in, void* dst_out, in
   a.loss_partials = p.loss_partials;
   a.forward_blocks = forward_blocks_for(num_pairs);
   a.forward_blocks_per_xcd = ceil_div(a.forward_blocks, 8);
-  a.update_lds_bytes = dim <= 256 ? kGroupsPerBlock * dim * (int)sizeof(long long) + 64 : 0;
+  a.update_lds_bytes = (kSgnsThreads / 64) * dim * (int)sizeof(long long) + 64;
   a.loss_out = loss_sum_out;
   // float4 registers per lane for one row: 16 lanes x 4 floats = 64 elements each
   const int vpl = (dim + 63) / 64;
   if (dtype == GS_F32) {
-    if (vpl <= 1) return launch_sgns<float, 1, 6, 8>(a, stream);
-    if (vpl <= 2) return launch_sgns<float, 2, 6, 8>(a, stream);
-    if (vpl <= 4) return launch_sgns<float, 4, 3, 4>(a, stream);
-    if (vpl <= 8) return launch_sgns<float, 8, 2, 2>(a, stream);
-    return launch_sgns<float, 16, 1, 1>(a, stream);
+    if (vpl <= 1) return launch_sgns<float, 1, 6>(a, stream);
+    if (vpl <= 2) return launch_sgns<float, 2, 6>(a, stream);
+    if (vpl <= 4) return launch_sgns<float, 4, 3>(a, stream);
+    if (vpl <= 8) return launch_sgns<float, 8, 2>(a, stream);
+    return launch_sgns<float, 16, 1>(a, stream);
   }
   // 16-bit rows: a 16-byte piece is 8 elements = two float4, so the register count is even
   if (dtype == GS_BF16) {
-    if (vpl <= 2) return launch_sgns<bf16_t, 2, 6, 16>(a, stream);
-    if (vpl <= 4) return launch_sgns<bf16_t, 4, 6, 8>(a, stream);
-    if (vpl <= 8) return launch_sgns<bf16_t, 8, 4, 4>(a, stream);
-    return launch_sgns<bf16_t, 16, 2, 2>(a, stream);
+    if (vpl <= 2) return launch_sgns<bf16_t, 2, 6>(a, stream);
+    if (vpl <= 4) return launch_sgns<bf16_t, 4, 6>(a, stream);
+    if (vpl <= 8) return launch_sgns<bf16_t, 8, 4>(a, stream);
+    return launch_sgns<bf16_t, 16, 2>(a, stream);
   }
-  if (vpl <= 2) return launch_sgns<f16_t, 2, 6, 16>(a, stream);
-  if (vpl <= 4) return launch_sgns<f16_t, 4, 6, 8>(a, stream);
-  if (vpl <= 8) return launch_sgns<f16_t, 8, 4, 4>(a, stream);
-  return launch_sgns<f16_t, 16, 2, 2>(a, stream);
+  if (vpl <= 2) return launch_sgns<f16_t, 2, 6>(a, stream);
+  if (vpl <= 4) return launch_sgns<f16_t, 4, 6>(a, stream);
+  if (vpl <= 8) return launch_sgns<f16_t, 8, 4>(a, stream);
+  return launch_sgns<f16_t, 16, 2>(a, stream);
 }
 
 }  // namespace gs
