@@ -57,6 +57,7 @@ namespace gs {
 constexpr int kSgnsThreads = 256;
 constexpr int kGroupLanes = 16;
 constexpr int kGroupsPerBlock = kSgnsThreads / kGroupLanes;
+constexpr size_t kCompactFactor = 16;  // keys per batch entry beyond which the key space is compacted
 constexpr int kStageSlice = 8;     // staged gradients per 16-lane group in the input-table pass: they are
                                    // few (one per run of equal centres), so short slices keep the chip busy
 constexpr uint32_t kLongRow = 256; // rows with more terms than this go through the side buffer
@@ -84,8 +85,7 @@ struct Term {      // one contribution to a destination row
   int32_t center;  // source row: row of the input table (one-table mode: slot of its copy in
                    // `snap`), or the staging slot for an input-table key
   float coef;      // -lr * g, or -lr for a staged gradient
-  uint32_t where;  // low 16 bits: number of terms of this row, high 16: position of this
-                   // term among them; both saturate at 65535 (exact for rows <= kLongRow)
+  uint32_t pos;    // position of this term among the terms of its key
 };
 
 struct SgnsArgs {
@@ -127,7 +127,16 @@ struct SgnsArgs {
   float lr;
   float* g;                 // [num_terms]
   uint32_t* rank;           // [num_terms]
-  uint32_t* cnt;            // [2 * num_nodes + 1], indexed by key; after scan: offsets
+  uint32_t* cnt;            // [cnt_last + 1] counters, indexed by the slot of a key; after scan: offsets,
+                            // and entry cnt_last holds the number of positions in use
+  int64_t cnt_last;
+  // Compacted key space, for graphs much larger than the batch (else null: slot = key): an
+  // open-addressing table of the keys the batch holds; the slot of a key is where it sits.
+  // The context-table keys have the first 1 << out_bits places to themselves and the
+  // input-table keys the 1 << in_bits places after them, so that in `sorted` every
+  // context-table key still comes before every input-table key.
+  uint32_t* key_table;      // [(1 << out_bits) + (1 << in_bits)], kNoRow = free
+  int32_t out_bits, in_bits;
   uint32_t* tile_sums;      // scan scratch
   Term* sorted;             // [num_terms + num_pairs]
   long long* long_acc;      // [long_slots][dim] exact sums of the long rows
@@ -137,7 +146,6 @@ struct SgnsArgs {
   double* loss_partials;    // [forward blocks]
   int64_t forward_blocks;
   int64_t forward_blocks_per_xcd;
-  int32_t update_lds_bytes; // LDS for the block-level sum of long-row partials (0: not used)
   double* loss_out;
   uint32_t* bad_ids;        // set when a centre / context / negative id is not a row of the tables,
                             // or a product left the range of the exact accumulation
@@ -381,13 +389,50 @@ __device__ __forceinline__ int64_t xcd_contiguous_block(int64_t bid, int64_t per
   return (bid & 7) * per_xcd + (bid >> 3);
 }
 
+// Counter slot of a key.  With the compacted key space the forward kernel enters the keys
+// (claim_slot: first come, first served, linear probing; the table has at least twice as
+// many places as the batch can hold keys) and the place kernel looks them up (find_slot).
+// Which slot a key gets depends on the order of arrival, and with it the order of the rows in
+// `sorted`; the results do not (exact sums).
+struct KeyRegion { uint32_t base, mask, first; };   // places [base, base + mask], probing from first
+__device__ __forceinline__ KeyRegion key_region(const SgnsArgs& a, uint32_t key) {
+  const bool input_key = key >= (uint32_t)a.num_nodes;
+  const int bits = input_key ? a.in_bits : a.out_bits;
+  KeyRegion r;
+  r.base = input_key ? (1u << a.out_bits) : 0u;
+  r.mask = (1u << bits) - 1u;
+  r.first = (key * 2654435761u) >> (32 - bits);
+  return r;
+}
+__device__ __forceinline__ uint32_t claim_slot(const SgnsArgs& a, uint32_t key) {
+  if (a.key_table == nullptr) return key;
+  const KeyRegion r = key_region(a, key);
+  uint32_t h = r.first;
+  while (true) {
+    uint32_t* place = a.key_table + r.base + h;
+    uint32_t seen = __hip_atomic_load(place, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (seen == kNoRow) seen = atomicCAS(place, kNoRow, key);
+    if (seen == kNoRow || seen == key) return r.base + h;
+    h = (h + 1u) & r.mask;
+  }
+}
+__device__ __forceinline__ uint32_t find_slot(const SgnsArgs& a, uint32_t key) {
+  if (a.key_table == nullptr) return key;
+  const KeyRegion r = key_region(a, key);
+  uint32_t h = r.first;
+  while (a.key_table[r.base + h] != key) h = (h + 1u) & r.mask;   // every key of the batch is in the table
+  return r.base + h;
+}
+
 // ---- clear / fill ---------------------------------------------------------------------
 // everything a call starts from: counters 0, no bad id seen (16 bytes per lane; the counter
 // array is padded to a multiple of four entries)
-__global__ void sgns_clear_kernel(uint4* __restrict__ cnt4, int64_t n4, uint32_t* __restrict__ flag) {
+__global__ void sgns_clear_kernel(uint4* __restrict__ cnt4, int64_t n4, uint4* __restrict__ table4,
+                                  int64_t m4, uint32_t* __restrict__ flag) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i == 0) *flag = 0u;
   if (i < n4) cnt4[i] = make_uint4(0u, 0u, 0u, 0u);
+  if (i < m4) table4[i] = make_uint4(kNoRow, kNoRow, kNoRow, kNoRow);
 }
 
 // ---- forward ------------------------------------------------------------------------------
@@ -400,7 +445,7 @@ __device__ __forceinline__ void stage_flush(const SgnsArgs& a, int64_t slot, int
                                             const float4 (&du)[VPL]) {
   if (l16 == 0) {
     a.stage_center[slot] = center;
-    a.stage_rank[slot] = atomicAdd(a.cnt + a.num_nodes + center, 1u);
+    a.stage_rank[slot] = atomicAdd(a.cnt + claim_slot(a, (uint32_t)a.num_nodes + (uint32_t)center), 1u);
   }
   float4* out = reinterpret_cast<float4*>(a.stage_delta + slot * (int64_t)a.dim);
   const int dim4 = a.dim >> 2;
@@ -507,7 +552,7 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
         const uint32_t h = ((uint32_t)row * 2654435761u) >> (32 - kHotBits);
         const int32_t seen = atomicCAS(&hot_key[h], -1, row);
         if (seen == -1 || seen == row) rk = kRankPending | (atomicAdd(&hot_cnt[h], 1u) << kHotBits) | h;
-        else rk = atomicAdd(a.cnt + row, 1u);
+        else rk = atomicAdd(a.cnt + claim_slot(a, (uint32_t)row), 1u);
       }
       RawRow<T, VPL> vv[RB];
 #pragma unroll
@@ -544,7 +589,7 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
   __syncthreads();
   // one global update per locally counted row, then complete the pending ranks
   for (int h = threadIdx.x; h < kHotSlots; h += kSgnsThreads)
-    if (hot_key[h] >= 0) hot_base[h] = atomicAdd(a.cnt + hot_key[h], hot_cnt[h]);
+    if (hot_key[h] >= 0) hot_base[h] = atomicAdd(a.cnt + claim_slot(a, (uint32_t)hot_key[h]), hot_cnt[h]);
   __syncthreads();
   for (int t = l16; t < count * K1; t += kGroupLanes) {
     const int64_t e = first * (int64_t)K1 + t;
@@ -650,7 +695,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(uint32_t* __re
 #pragma unroll
     for (int k4 = 0; k4 < kScanPerThread / 4; ++k4) {
       const uint4 x = p4[k4];
-      v[4 * k4] = x.x; v[4 * k4 + 1] = x.y; v[4 * k4 + 2] = x.z; v[4 * k4 + 3] = x.w;
+      v[4 * k4] = x.x; v[4 * k4 + 1] = x.y;
+      v[4 * k4 + 2] = x.z; v[4 * k4 + 3] = x.w;
     }
   } else {
 #pragma unroll
@@ -692,7 +738,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(uint32_t* __re
 
 // ---- place: scatter the terms into key-major order ------------------------------
 // Entries [0, num_terms) are the (pair, j) terms, entries num_terms + s the staging slots.
-// The entry that lands first in a long row also clears the row's slot of the side buffer.
+// The entry with position kLongRow (it exists exactly in the long rows) also clears the
+// row's slot of the side buffer.
 __global__ __launch_bounds__(256) void sgns_place_kernel(SgnsArgs a) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= a.num_terms + a.num_pairs) return;
@@ -715,10 +762,10 @@ __global__ __launch_bounds__(256) void sgns_place_kernel(SgnsArgs a) {
     t.coef = -a.lr;
     rk = a.stage_rank[slot];
   }
-  const uint32_t begin = a.cnt[t.row], len = a.cnt[(int64_t)t.row + 1] - begin;
-  t.where = min(len, 65535u) | (min(rk, 65535u) << 16);
+  const uint32_t begin = a.cnt[find_slot(a, t.row)];
+  t.pos = rk;
   a.sorted[begin + rk] = t;
-  if (rk == 0 && len > kLongRow) {
+  if (rk == kLongRow) {
     long long* acc = a.long_acc + (int64_t)(begin >> kLongShift) * a.dim;
     for (int x = 0; x < a.dim; ++x) acc[x] = 0;
   }
@@ -789,11 +836,25 @@ __device__ __forceinline__ uint32_t uniform_u32(uint32_t x) {
   return (uint32_t)__builtin_amdgcn_readfirstlane((int)x);
 }
 
-// Ownership: a row with at most kLongRow terms is handled whole by the wave
-// whose slice holds its first term, which writes it once.  Longer rows are
-// handled slice by slice; their partial sums meet in the side buffer at slot
-// (position of the row's first term) >> kLongShift, which no two long rows can
-// share because each of them spans more than 2^kLongShift positions.
+// first position >= p (and < limit) whose term starts a segment, else limit; wave-uniform
+__device__ __forceinline__ int64_t next_segment_start(const Term* __restrict__ sorted, int64_t p,
+                                                      int64_t limit, int lane) {
+  while (p < limit) {
+    const bool start = p + lane >= limit || (sorted[p + lane].pos & (kLongRow - 1u)) == 0u;
+    const unsigned long long mask = __builtin_amdgcn_ballot_w64(start);
+    if (mask != 0ull) return min(limit, p + (int64_t)__builtin_ctzll(mask));
+    p += 64;
+  }
+  return limit;
+}
+
+// Ownership: the terms of a key are cut into segments of kLongRow consecutive positions
+// (pos = 0..255, 256..511, ...); a wave handles the segments whose first term lies in its
+// slice, reading on past the slice's end to finish the last one.  A row of at most kLongRow
+// terms is one segment: it is written once, as round(old + sum).  The partial sums of a row
+// with more segments meet in the side buffer at slot (position of the row's first term) >>
+// kLongShift, which no two such rows can share because each spans more than 2^kLongShift
+// positions.
 // kStage = false: context-table keys, positions [0, num_terms), source rows from the input
 // table; kStage = true: input-table keys, the positions after them, source rows = staged
 // gradients (fp32, natural element order).
@@ -814,10 +875,9 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
   const int64_t pos_lo = kStage ? a.num_terms : 0;
   // (scalars that come out of memory are made wave-uniform explicitly: loop bounds and the
   // lane numbers of the broadcasts below must live in scalar registers)
-  const int64_t pos_hi = kStage ? (int64_t)uniform_u32(a.cnt[2 * a.num_nodes]) : a.num_terms;
+  const int64_t pos_hi = kStage ? (int64_t)uniform_u32(a.cnt[a.cnt_last]) : a.num_terms;
   const int lane = threadIdx.x & 63;
-  const int wave_in_block = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-  const int64_t wave = (int64_t)blockIdx.x * kWaves + wave_in_block;
+  const int64_t wave = (int64_t)blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int slice = kStage ? kStageSlice : a.slice_terms;
   const int64_t slice_begin = pos_lo + wave * slice;
   const bool active = slice_begin < pos_hi;
@@ -829,14 +889,10 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
 #pragma unroll
   for (int p = 0; p < PPL; ++p) piece_ok[p] = (p * 64 + lane) * EPP < a.dim;
 
-  int64_t begin = slice_begin, end = active ? slice_end : slice_begin;
+  int64_t begin = slice_begin, end = slice_begin;
   if (active) {
-    const uint32_t w0 = uniform_u32(sorted[slice_begin].where);
-    const uint32_t len0 = w0 & 0xffffu, pos0 = w0 >> 16;
-    if (len0 <= kLongRow && pos0 > 0) begin = slice_begin - pos0 + len0;   // owned by an earlier wave
-    const uint32_t w1 = uniform_u32(sorted[slice_end - 1].where);
-    const uint32_t len1 = w1 & 0xffffu, pos1 = w1 >> 16;
-    if (len1 <= kLongRow) end = (slice_end - 1) - pos1 + len1;             // finish the row we started
+    begin = next_segment_start(sorted, slice_begin, pos_hi, lane);   // what lies before is an earlier wave's
+    end = next_segment_start(sorted, slice_end, pos_hi, lane);       // finish the segment we started
   }
 
   unsigned long long acc[EPL];
@@ -847,8 +903,9 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
   for (int p = 0; p < PPL; ++p)
 #pragma unroll
     for (int w = 0; w < WPP; ++w) old[p][w] = 0u;
-  uint32_t cur_row = kNoRow;       // key of the row being summed (table row: cur_row - key_base)
-  bool cur_long = false;
+  uint32_t cur_row = kNoRow;       // key of the segment being summed (table row: cur_row - key_base)
+  uint32_t cur_seg = 0;            // its number within the key (pos >> kLongShift of its terms)
+  int64_t seg_first = 0;           // position of its first term
   uint32_t cur_terms = 0;          // terms added into acc since it was cleared
 
   // takes the magic bits of the terms off (their low word is zero): acc becomes the net sum
@@ -858,8 +915,9 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
     for (int x = 0; x < EPL; ++x) acc[x] -= off;
   };
   auto flush_long = [&]() {
+    const int64_t row_first = seg_first - ((int64_t)cur_seg << kLongShift);
     unsigned long long* dst = reinterpret_cast<unsigned long long*>(a.long_acc) +
-                              (int64_t)(a.cnt[cur_row] >> kLongShift) * a.dim;
+                              (row_first >> kLongShift) * a.dim;
 #pragma unroll
     for (int p = 0; p < PPL; ++p) {
       if (piece_ok[p]) {
@@ -883,9 +941,10 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
     }
     store_words<WPP>(row_words + (int64_t)(p * 64 + lane) * WPP, out);
   };
-  auto flush = [&]() {
+  // continues: the next term belongs to the same key (the row has a further segment)
+  auto flush = [&](bool continues) {
     settle();
-    if (cur_long) {
+    if (cur_seg > 0 || continues) {
       flush_long();
       return;
     }
@@ -917,7 +976,7 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
 
   for (int64_t q = begin; q < end; q += 64) {
     Term t;
-    t.row = kNoRow; t.center = 0; t.coef = 0.f; t.where = 0;
+    t.row = kNoRow; t.center = 0; t.coef = 0.f; t.pos = 0;
     if (q + lane < end) t = sorted[q + lane];
     const int n = (int)min((int64_t)64, end - q);
 #pragma unroll 1
@@ -942,15 +1001,17 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
 #pragma unroll
       for (int b = 0; b < UB; ++b) {
         if (b0 + b < n) {
-          const uint32_t row = (uint32_t)__builtin_amdgcn_readlane((int)t.row, b0 + b);
-          if (row != cur_row) {
-            if (cur_row != kNoRow) flush();
+          const uint32_t pos = (uint32_t)__builtin_amdgcn_readlane((int)t.pos, b0 + b);
+          if ((pos & (kLongRow - 1u)) == 0u) {           // a segment starts here
+            const uint32_t row = (uint32_t)__builtin_amdgcn_readlane((int)t.row, b0 + b);
+            if (cur_row != kNoRow) flush(row == cur_row);
             cur_row = row;
-            cur_long = ((uint32_t)__builtin_amdgcn_readlane((int)t.where, b0 + b) & 0xffffu) > kLongRow;
+            cur_seg = pos >> kLongShift;
+            seg_first = q + b0 + b;
             cur_terms = 0;
 #pragma unroll
             for (int x = 0; x < EPL; ++x) acc[x] = 0;
-            if (!cur_long) {
+            if (pos == 0u) {
               const uint32_t* row_words = dst_base + (int64_t)(cur_row - key_base) * dst_row_words;
 #pragma unroll
               for (int p = 0; p < PPL; ++p)
@@ -972,44 +1033,8 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
       }
     }
   }
-  // Last pending row of this wave.  Waves of a block hold consecutive slices,
-  // so a row with very many terms is pending in several of them at once: their
-  // partial sums are added up in LDS first and leave the block as one update
-  // of the side buffer.
-  const bool pending_long = cur_row != kNoRow && cur_long;
-  if (cur_row != kNoRow && !cur_long) flush();
-  if (a.update_lds_bytes == 0) {          // rows too wide for the LDS stage
-    if (pending_long) flush();
-    return;
-  }
-  extern __shared__ unsigned long long comb_s[];   // [kWaves][dim] partial sums, then the row ids
-  uint32_t* comb_row = reinterpret_cast<uint32_t*>(comb_s + kWaves * a.dim);
-  if (lane == 0) comb_row[wave_in_block] = pending_long ? cur_row : kNoRow;
-  if (pending_long) {
-    settle();
-    unsigned long long* mine = comb_s + wave_in_block * a.dim;
-#pragma unroll
-    for (int p = 0; p < PPL; ++p) {
-      if (piece_ok[p]) {
-#pragma unroll
-        for (int i = 0; i < EPP; ++i) mine[(p * 64 + lane) * EPP + i] = acc[p * EPP + i];
-      }
-    }
-  }
-  __syncthreads();
-  if (pending_long && (wave_in_block == 0 || comb_row[wave_in_block - 1] != cur_row)) {
-    for (int g2 = wave_in_block + 1; g2 < kWaves && comb_row[g2] == cur_row; ++g2) {
-      const unsigned long long* other = comb_s + g2 * a.dim;
-#pragma unroll
-      for (int p = 0; p < PPL; ++p) {
-        if (piece_ok[p]) {
-#pragma unroll
-          for (int i = 0; i < EPP; ++i) acc[p * EPP + i] += other[(p * 64 + lane) * EPP + i];
-        }
-      }
-    }
-    flush_long();
-  }
+  // last pending segment: the row goes on if the term after the range has the same key
+  if (cur_row != kNoRow) flush(end < pos_hi && uniform_u32(sorted[end].row) == cur_row);
 }
 
 // element-wise row helpers for the finishing kernel (natural order)
@@ -1021,9 +1046,9 @@ template <typename T, if_16bit<T> = 0>
 __device__ __forceinline__ void elem_store(T* row, int e, float v) { row[e].bits = (uint16_t)T::round(v); }
 
 // ---- finish: table[row] = round(old + side buffer) for the long rows ------------------------
-// Side-buffer slot s belongs to the long row whose first term lies in
-// [s << kLongShift, (s+1) << kLongShift): that row then also owns the last
-// position of the window.  The last block of the launch adds up the per-block
+// Side-buffer slot s belongs to the long row (more than kLongRow terms) whose first term
+// lies in [s << kLongShift, (s+1) << kLongShift): that row then also owns the last position
+// of the window.  The last block of the launch adds up the per-block
 // loss partials instead (in a fixed order, so the loss is reproducible); a bad id
 // or an out-of-range product seen by an earlier kernel turns it into NaN.
 // which: 0 = long rows of both tables and the loss; 1 = context-table keys only, no loss;
@@ -1050,11 +1075,13 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_finish_kernel(SgnsArgs a, i
   const int l16 = threadIdx.x & (kGroupLanes - 1);
   const int64_t s = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
   const int64_t last_pos = ((s + 1) << kLongShift) - 1;
-  if (last_pos >= (int64_t)a.cnt[2 * a.num_nodes]) return;
+  const int64_t total = (int64_t)a.cnt[a.cnt_last];
+  if (last_pos >= total) return;
   const Term t = a.sorted[last_pos];
-  if ((t.where & 0xffffu) <= kLongRow) return;
-  const int64_t first_pos = (int64_t)a.cnt[t.row];
+  const int64_t first_pos = last_pos - (int64_t)t.pos;
   if ((first_pos >> kLongShift) != s) return;
+  // long: the row has a term at position kLongRow
+  if (first_pos + (int64_t)kLongRow >= total || a.sorted[first_pos + kLongRow].row != t.row) return;
   const bool input_row = (int64_t)t.row >= a.num_nodes;
   if (which != 0 && input_row != (which == 2)) return;
   const int64_t row = input_row ? (int64_t)t.row - a.num_nodes : (int64_t)t.row;
@@ -1093,6 +1120,9 @@ struct SgnsPlan {
   float* g;
   uint32_t* rank;
   uint32_t* cnt;
+  int64_t cnt_last;         // counters are cnt[0 .. cnt_last]
+  uint32_t* key_table;      // compacted key space (null: slot = key)
+  int32_t out_bits, in_bits;
   uint32_t* tile_sums;
   uint32_t* bad_ids;
   Term* sorted;
@@ -1109,13 +1139,29 @@ static SgnsPlan plan_sgns(void* ws, int64_t num_pairs, int64_t num_nodes, int32_
   SgnsPlan p;
   const size_t b = (size_t)(num_pairs > 0 ? num_pairs : 1);
   const size_t terms = b * (size_t)(k + 1);
-  const size_t keys1 = 2 * (size_t)(num_nodes > 0 ? num_nodes : 1) + 1;
+  const size_t keys = 2 * (size_t)(num_nodes > 0 ? num_nodes : 1);
+  // A counter per key while the keys are few.  For graphs much larger than the batch (the
+  // paper's own batches of 512 to 2048 source nodes on graphs of 10^8 and more vertices) the
+  // counters go over the places of a table of the keys the batch holds (at most one per term
+  // and per pair): everything that is cleared, scanned or hit at random in a call then has
+  // the size of the batch, not of the graph.
+  const bool compact = keys > kCompactFactor * (terms + b);
+  p.out_bits = p.in_bits = 0;
+  size_t places = 0;
+  if (compact) {                 // at least twice as many places as there can be keys of a kind
+    p.out_bits = p.in_bits = 8;
+    while (((size_t)1 << p.out_bits) < 2 * terms) ++p.out_bits;
+    while (((size_t)1 << p.in_bits) < 2 * b) ++p.in_bits;
+    places = ((size_t)1 << p.out_bits) + ((size_t)1 << p.in_bits);
+  }
+  p.cnt_last = (int64_t)(compact ? places : keys);
   p.long_slots = (int64_t)((terms + b) >> kLongShift) + 1;
   p.loss_partials = cv.take<double>((size_t)forward_blocks_for((int64_t)b));
   p.g = cv.take<float>(terms);
   p.rank = cv.take<uint32_t>(terms);
-  p.cnt = cv.take<uint32_t>(keys1 + 3);                   // cleared 16 bytes at a time
-  p.tile_sums = cv.take<uint32_t>((size_t)ceil_div((int64_t)keys1, kScanTile));
+  p.cnt = cv.take<uint32_t>((size_t)p.cnt_last + 1 + 3);                   // cleared 16 bytes at a time
+  p.key_table = compact ? cv.take<uint32_t>(places) : nullptr;
+  p.tile_sums = cv.take<uint32_t>((size_t)ceil_div(p.cnt_last + 1, kScanTile));
   p.bad_ids = cv.take<uint32_t>(1);
   p.sorted = cv.take<Term>(terms + b);
   p.long_acc = cv.take<long long>((size_t)p.long_slots * (size_t)dim);
@@ -1134,7 +1180,7 @@ static int32_t launch_updates(const SgnsArgs& a, hipStream_t stream) {
   // context-table keys: exactly num_terms positions; input-table keys: at most one per pair
   const unsigned out_blocks = (unsigned)ceil_div(ceil_div(a.num_terms, a.slice_terms), kWaves);
   const unsigned in_blocks = (unsigned)ceil_div(ceil_div(a.num_pairs, kStageSlice), kWaves);
-  const size_t lds = (size_t)a.update_lds_bytes;
+  const size_t lds = 0;
   const unsigned finish_blocks = (unsigned)ceil_div(a.long_slots, kGroupsPerBlock) + 1;
   const bool one_table = a.snap != nullptr;
   if constexpr (std::is_same<T, float>::value) {
@@ -1154,10 +1200,12 @@ static int32_t launch_updates(const SgnsArgs& a, hipStream_t stream) {
 
 template <typename T, int VPL, int RB>
 static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
-  const int64_t keys1 = 2 * a.num_nodes + 1;
+  const int64_t keys1 = a.cnt_last + 1;
   const int64_t tiles = ceil_div(keys1, kScanTile);
   const int64_t keys4 = ceil_div(keys1, 4);
-  sgns_clear_kernel<<<(unsigned)ceil_div(keys4, 256), 256, 0, stream>>>((uint4*)a.cnt, keys4, a.bad_ids);
+  const int64_t table4 = a.key_table != nullptr ? a.cnt_last / 4 : 0;   // (a multiple of four places)
+  sgns_clear_kernel<<<(unsigned)ceil_div(max(keys4, table4), 256), 256, 0, stream>>>(
+      (uint4*)a.cnt, keys4, (uint4*)a.key_table, table4, a.bad_ids);
   GS_LAUNCH_CHECK();
   const size_t idx_lds = (size_t)kGroupsPerBlock * a.chunk_pairs * (a.k + 2) * sizeof(int32_t);
   sgns_forward_kernel<T, VPL, RB><<<(unsigned)(a.forward_blocks_per_xcd * 8), kSgnsThreads, idx_lds,
@@ -1341,6 +1389,10 @@ static int32_t run_sgns(void* w_in, void* w_out, void* dst_in, void* dst_out, in
   a.g = p.g;
   a.rank = p.rank;
   a.cnt = p.cnt;
+  a.cnt_last = p.cnt_last;
+  a.key_table = p.key_table;
+  a.out_bits = p.out_bits;
+  a.in_bits = p.in_bits;
   a.tile_sums = p.tile_sums;
   a.bad_ids = p.bad_ids;
   a.sorted = p.sorted;
@@ -1353,7 +1405,6 @@ static int32_t run_sgns(void* w_in, void* w_out, void* dst_in, void* dst_out, in
   a.loss_partials = p.loss_partials;
   a.forward_blocks = forward_blocks_for(num_pairs);
   a.forward_blocks_per_xcd = ceil_div(a.forward_blocks, 8);
-  a.update_lds_bytes = (kSgnsThreads / 64) * dim * (int)sizeof(long long) + 64;
   a.loss_out = loss_sum_out;
   // float4 registers per lane for one row: 16 lanes x 4 floats = 64 elements each
   const int vpl = (dim + 63) / 64;
@@ -1437,11 +1488,12 @@ extern "C" int32_t gs_sgns_step_fused(void* w_in, void* w_out, int64_t num_nodes
     GS_LAUNCH_CHECK();
     return GS_OK;
   }
+  int32_t* negs_ws = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + p.bytes);
   SgnsExtras x;
   x.noise = noise;
   x.neg_seed = neg_seed;
   x.neg_pair_base = pair_index_base;
-  x.negs_draw = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + p.bytes);
+  x.negs_draw = negs_ws;
   return run_sgns(w_in, w_out, w_in, w_out, num_nodes, dim, dtype, centers, contexts, nullptr,
                   num_pairs, k, lr, loss_sum_out, p, stream, x);
 }

@@ -894,3 +894,38 @@ def test_sgns_step_same_bits_every_run(gs, fmt):
     for r in results[1:]:
         for x, y in zip(results[0], r):
             assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("fmt", ["f32", "bf16"])
+@pytest.mark.parametrize("b,k", [(1, 5), (37, 0), (2_048, 5), (9_000, 2)])
+def test_sgns_step_small_batch_on_large_graph(gs, oracle, b, k, fmt):
+    """The paper's own regime (Sec. 4: batches of 512 to 2048 source nodes on graphs of 10^8
+    vertices): the batch names a tiny part of the rows, so the step counts over a table of the
+    batch's keys instead of over all vertices.  Hub rows with thousands of terms, runs of equal
+    centres, centres that are also contexts; rows the batch does not name keep their bits."""
+    from paper_2407_15452_amd import inputs
+    n, dim = 400_000, 64
+    f_in, f_out = inputs.random_tables(n, dim, seed=b + k, scale=0.25)
+    rng = np.random.default_rng(b * 31 + k)
+    c = np.repeat((n * rng.random(b // 5 + 1) ** 2).astype(np.int32), 5)[:b]
+    o = rng.integers(0, n, b).astype(np.int32)
+    o[::3] = c[::3]
+    neg = (n * rng.random((b, k)) ** 6).astype(np.int32)          # a few rows take most draws
+    if fmt == "f32":
+        g_in, g_out = _sgns_case(gs, oracle, f_in, f_out, c, o, neg, 0.025)
+        named = np.zeros(n, bool)
+        named[c] = named[o] = True
+        named[neg.ravel()] = True
+        np.testing.assert_array_equal(g_in[~named], f_in.numpy()[~named])
+        np.testing.assert_array_equal(g_out[~named], f_out.numpy()[~named])
+    else:
+        b_in, b_out = f_in.to(torch.bfloat16), f_out.to(torch.bfloat16)
+        h_in, h_out = _bf16_bits(b_in), _bf16_bits(b_out)
+        want = oracle.sgns_step(h_in, h_out, c, o, neg, 0.025, dtype=oracle.BF16)
+        d_in, d_out = b_in.to(DEV), b_out.to(DEV)
+        loss = gs.gs_sgns_step(d_in, d_out, _t(c), _t(o), _t(neg).reshape(b, k), 0.025)
+        torch.cuda.synchronize()
+        assert abs(float(loss.item()) - want) <= LOSS_RTOL * abs(want)
+        # few elements are touched at all: one that rounds the other way is a large fraction
+        assert_half_close(_bf16_bits(d_in), h_in, "bf16", flip_fraction=1e-3)
+        assert_half_close(_bf16_bits(d_out), h_out, "bf16", flip_fraction=1e-3)
