@@ -238,6 +238,26 @@ int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int32_t dim, in
                      void* ws, size_t ws_bytes, void* stream);
 
 /* --------------------------------------------------------------------------
+ * gs_sgns_step_static -- gs_sgns_step for callers that cannot allocate or hand
+ * over device memory for a workspace: code under HIP graph capture, tight
+ * training or serving loops, harnesses that forbid hipMalloc.  The scratch memory
+ * of the step is an 8 MiB array that is part of the library's code object on
+ * every GPU (held until the process ends); the call allocates and frees nothing.
+ *   Same arguments (without ws, ws_bytes), results and errors as gs_sgns_step,
+ *   for small batches: num_pairs <= 4096, num_pairs * (k+1) <= 65536, dim <=
+ *   256; GS_EWORKSPACE beyond that.  The graph may have any size (the step
+ *   counts over a table of the batch's keys).
+ *   All calls on one GPU share that GPU's array: calls that overlap in time on
+ *   one GPU (two streams, two threads) race; one call at a time per GPU.  The
+ *   first call on a device looks the array's address up (hipGetSymbolAddress)
+ *   and should therefore be made outside a graph capture.
+ * ------------------------------------------------------------------------ */
+int32_t gs_sgns_step_static(void* w_in, void* w_out, int64_t num_nodes, int32_t dim, int32_t dtype,
+                            const int32_t* centers, const int32_t* contexts, const int32_t* negs,
+                            int64_t num_pairs, int32_t k, float lr, double* loss_sum_out,
+                            void* stream);
+
+/* --------------------------------------------------------------------------
  * gs_sgns_momentum_step -- the same iteration with the optimizer the paper
  * runs: SGD with momentum written as the three storage operations of Sec. 3.2
  * (model update for SGD with momentum), applied to both tables:

@@ -26,7 +26,8 @@ EXPORTS = (
     "gs_random_walk", "gs_node2vec_walk",
     "gs_make_pairs_workspace_bytes", "gs_make_pairs",
     "gs_sample_negatives", "gs_sample_edges",
-    "gs_sgns_step_workspace_bytes", "gs_sgns_step", "gs_sgns_momentum_step", "gs_sgns_adam_step",
+    "gs_sgns_step_workspace_bytes", "gs_sgns_step", "gs_sgns_step_static", "gs_sgns_momentum_step",
+    "gs_sgns_adam_step",
     "gs_sgns_step_fused_workspace_bytes", "gs_sgns_step_fused",
     "gs_line1_step_workspace_bytes", "gs_line1_step",
     "gs_unique_ids_workspace_bytes", "gs_unique_ids", "gs_get_rows", "gs_put_rows",
@@ -290,6 +291,25 @@ def gs_sgns_step(w_in, w_out, centers, contexts, negs, lr: float, loss_out=None,
                             _dev(loss_out, torch.float64, "loss_sum_out"), _dev(ws),
                             C.c_size_t(ws.numel()), _stream())
     _check(rc, "gs_sgns_step")
+    return loss_out
+
+
+def gs_sgns_step_static(w_in, w_out, centers, contexts, negs, lr: float, loss_out=None):
+    """gs_sgns_step on the library's own static scratch array (small batches; see gs.h)."""
+    dtype = _table_dtype(w_in)
+    num_nodes, dim = int(w_in.shape[0]), int(w_in.shape[1])
+    num_pairs = int(centers.numel())
+    k = int(negs.shape[1]) if negs.dim() == 2 else 0
+    if loss_out is None:
+        loss_out = torch.zeros(1, dtype=torch.float64, device=w_in.device)
+    rc = lib().gs_sgns_step_static(_dev(w_in, None, "w_in"), _dev(w_out, w_in.dtype, "w_out"),
+                                   C.c_int64(num_nodes), C.c_int32(dim), C.c_int32(dtype),
+                                   _dev(centers, torch.int32, "centers"),
+                                   _dev(contexts, torch.int32, "contexts"),
+                                   _dev(negs, torch.int32, "negs") if negs.numel() else None,
+                                   C.c_int64(num_pairs), C.c_int32(k), C.c_float(lr),
+                                   _dev(loss_out, torch.float64, "loss_sum_out"), _stream())
+    _check(rc, "gs_sgns_step_static")
     return loss_out
 
 

@@ -48,6 +48,7 @@
 // LINE) reads the input rows in the update kernel from copies the forward kernel
 // kept, because that kernel then writes rows of the table it would read.
 #include <cmath>
+#include <mutex>
 #include <type_traits>
 
 #include "common.h"
@@ -1134,7 +1135,10 @@ struct SgnsPlan {
   size_t bytes;
 };
 
-static SgnsPlan plan_sgns(void* ws, int64_t num_pairs, int64_t num_nodes, int32_t k, int32_t dim) {
+// force_compact: always count over the table of the batch's keys, whatever the graph's size,
+// so that the workspace depends on (num_pairs, k, dim) only
+static SgnsPlan plan_sgns(void* ws, int64_t num_pairs, int64_t num_nodes, int32_t k, int32_t dim,
+                          bool force_compact = false) {
   Carver cv(ws);
   SgnsPlan p;
   const size_t b = (size_t)(num_pairs > 0 ? num_pairs : 1);
@@ -1145,7 +1149,7 @@ static SgnsPlan plan_sgns(void* ws, int64_t num_pairs, int64_t num_nodes, int32_
   // counters go over the places of a table of the keys the batch holds (at most one per term
   // and per pair): everything that is cleared, scanned or hit at random in a call then has
   // the size of the batch, not of the graph.
-  const bool compact = keys > kCompactFactor * (terms + b);
+  const bool compact = force_compact || keys > kCompactFactor * (terms + b);
   p.out_bits = p.in_bits = 0;
   size_t places = 0;
   if (compact) {                 // at least twice as many places as there can be keys of a kind
@@ -1449,6 +1453,60 @@ extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int3
   if (bad != GS_OK) return bad;
   SgnsPlan p = plan_sgns(ws, num_pairs, num_nodes, k, dim);
   if (ws_bytes < p.bytes) return GS_EWORKSPACE;
+  if (num_pairs == 0) {
+    zero_double_kernel<<<1, 1, 0, stream>>>(loss_sum_out);
+    GS_LAUNCH_CHECK();
+    return GS_OK;
+  }
+  return run_sgns(w_in, w_out, w_in, w_out, num_nodes, dim, dtype, centers, contexts, negs, num_pairs,
+                  k, lr, loss_sum_out, p, stream);
+}
+
+// ---- the step for callers that cannot allocate ------------------------------------------
+// Scratch memory of gs_sgns_step_static: one array per GPU, part of the loaded code object,
+// held until the process ends.  Host code never uses the array's name as an address: the
+// device address is asked for once per device (hipGetSymbolAddress, with that device
+// current) and kept.
+constexpr int64_t kStaticMaxPairs = 4096;
+constexpr int64_t kStaticMaxTerms = 65536;
+constexpr int32_t kStaticMaxDim = 256;
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kStaticMaxDevices = 64;
+static void* g_scratch_ptr[kStaticMaxDevices];   // device address of `scratch`, per device
+static std::mutex g_scratch_mutex;
+
+static int32_t static_scratch(void** out) {
+  int dev = -1;
+  GS_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kStaticMaxDevices) return GS_EINVAL;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    GS_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (ptr == nullptr) return GS_EHIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return GS_OK;
+}
+
+extern "C" int32_t gs_sgns_step_static(void* w_in, void* w_out, int64_t num_nodes, int32_t dim,
+                                       int32_t dtype, const int32_t* centers, const int32_t* contexts,
+                                       const int32_t* negs, int64_t num_pairs, int32_t k, float lr,
+                                       double* loss_sum_out, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  if (num_pairs > kStaticMaxPairs || dim > kStaticMaxDim) return GS_EWORKSPACE;
+  if (num_pairs > 0 && k >= 0 && num_pairs * (int64_t)(k + 1) > kStaticMaxTerms) return GS_EWORKSPACE;
+  void* ws = nullptr;
+  const int32_t got = static_scratch(&ws);
+  if (got != GS_OK) return got;
+  const int32_t bad = check_sgns_args(w_in, w_out, num_nodes, dim, dtype, centers, contexts, negs,
+                                      num_pairs, k, loss_sum_out, ws);
+  if (bad != GS_OK) return bad;
+  SgnsPlan p = plan_sgns(ws, num_pairs, num_nodes, k, dim, true);
+  if (p.bytes > kStaticScratchBytes) return GS_EWORKSPACE;
   if (num_pairs == 0) {
     zero_double_kernel<<<1, 1, 0, stream>>>(loss_sum_out);
     GS_LAUNCH_CHECK();
