@@ -297,6 +297,42 @@ int32_t gs_sgns_step_fused(void* w_in, void* w_out, int64_t num_nodes, int32_t d
                            void* stream);
 
 /* --------------------------------------------------------------------------
+ * gs_pair_offsets, gs_sgns_step_from_walks -- sampling and update in one call
+ * (Sec. 2.2: walks -> skip-gram pairs -> negative sampling; Sec. 3.2: the
+ * sampled nodes of a batch are fetched and trained on): the iteration derives
+ * its (centre, context) pairs from the walk buffer and draws its negatives
+ * inside the forward kernel, so no centers / contexts / negs arrays exist at
+ * the boundary (the derived ids are kept in the workspace for the later kernels
+ * of the step).
+ *
+ * gs_pair_offsets: offsets_out int64[num_walks+1]; offsets_out[w] = number of
+ *   pairs gs_make_pairs emits for the walks before w, offsets_out[num_walks] =
+ *   for all of them.  Once per walk buffer.
+ *
+ * gs_sgns_step_from_walks: the batch is pairs first_pair .. first_pair +
+ *   num_pairs - 1 of the sequence gs_make_pairs would emit for walks[0 ..
+ *   num_walks) (any slice: batch boundaries need not fall on walks); negative j
+ *   of pair i is the draw of gs_sample_negatives for pair index pair_index_base
+ *   + i.  The result is that of gs_make_pairs + gs_sample_negatives +
+ *   gs_sgns_step on that slice.  If the walks hold fewer than first_pair +
+ *   num_pairs pairs, loss_sum_out is NaN (as for an id that is no row).
+ *   walks int32[num_walks][walk_len]; pair_offsets as written by gs_pair_offsets;
+ *   other arguments, limits and errors as for gs_sgns_step_fused; workspace
+ *   gs_sgns_step_from_walks_workspace_bytes.
+ * ------------------------------------------------------------------------ */
+size_t gs_pair_offsets_workspace_bytes(int64_t num_walks);
+int32_t gs_pair_offsets(const int32_t* walks, int64_t num_walks, int32_t walk_len, int32_t window,
+                        int64_t* offsets_out, void* ws, size_t ws_bytes, void* stream);
+size_t gs_sgns_step_from_walks_workspace_bytes(int64_t num_pairs, int64_t num_nodes, int32_t k,
+                                               int32_t dim, int32_t dtype);
+int32_t gs_sgns_step_from_walks(void* w_in, void* w_out, int64_t num_nodes, int32_t dim, int32_t dtype,
+                                const int32_t* walks, int64_t num_walks, int32_t walk_len,
+                                int32_t window, const int64_t* pair_offsets, int64_t first_pair,
+                                int64_t num_pairs, const gs_alias* noise, uint64_t pair_index_base,
+                                uint64_t neg_seed, int32_t k, float lr, double* loss_sum_out, void* ws,
+                                size_t ws_bytes, void* stream);
+
+/* --------------------------------------------------------------------------
  * gs_line1_step -- LINE iteration with first-order proximity (the LINE variant
  * with one embedding per node; Sec. 2.2 / Sec. 4 cite LINE, Sec. 3.2 gives the
  * batch shape): one table w on both sides.  For pair i: u = w[sources[i]],

@@ -29,6 +29,8 @@ EXPORTS = (
     "gs_sgns_step_workspace_bytes", "gs_sgns_step", "gs_sgns_step_static", "gs_sgns_momentum_step",
     "gs_sgns_adam_step",
     "gs_sgns_step_fused_workspace_bytes", "gs_sgns_step_fused",
+    "gs_pair_offsets_workspace_bytes", "gs_pair_offsets",
+    "gs_sgns_step_from_walks_workspace_bytes", "gs_sgns_step_from_walks",
     "gs_line1_step_workspace_bytes", "gs_line1_step",
     "gs_unique_ids_workspace_bytes", "gs_unique_ids", "gs_get_rows", "gs_put_rows",
     "gs_table_mult", "gs_table_mult_add", "gs_sort_pairs_workspace_bytes", "gs_sort_pairs",
@@ -440,6 +442,49 @@ def gs_sgns_step_fused(w_in, w_out, centers, contexts, noise, k: int, neg_seed: 
         C.c_int32(k), C.c_float(lr), _dev(loss_out, torch.float64), _dev(ws), C.c_size_t(ws.numel()),
         _stream())
     _check(rc, "gs_sgns_step_fused")
+    return loss_out
+
+
+def gs_pair_offsets(walks, window: int, out=None, ws=None):
+    """int64[num_walks + 1]: pairs emitted for the walks before each walk, and for all of them."""
+    num_walks, walk_len = int(walks.shape[0]), int(walks.shape[1])
+    dev = walks.device
+    if out is None:
+        out = torch.empty(num_walks + 1, dtype=torch.int64, device=dev)
+    if ws is None:
+        ws = _workspace(int(lib().gs_pair_offsets_workspace_bytes(C.c_int64(num_walks))), dev)
+    rc = lib().gs_pair_offsets(_dev(walks, torch.int32, "walks"), C.c_int64(num_walks), C.c_int32(walk_len),
+                               C.c_int32(window), _dev(out, torch.int64, "offsets_out"), _dev(ws),
+                               C.c_size_t(ws.numel()), _stream())
+    _check(rc, "gs_pair_offsets")
+    return out
+
+
+def gs_sgns_step_from_walks_workspace_bytes(num_pairs: int, num_nodes: int, k: int, dim: int,
+                                            dtype: int = GS_F32) -> int:
+    return int(lib().gs_sgns_step_from_walks_workspace_bytes(
+        C.c_int64(num_pairs), C.c_int64(num_nodes), C.c_int32(k), C.c_int32(dim), C.c_int32(dtype)))
+
+
+def gs_sgns_step_from_walks(w_in, w_out, walks, window: int, pair_offsets, first_pair: int,
+                            num_pairs: int, noise, k: int, neg_seed: int, lr: float,
+                            pair_index_base: int = 0, loss_out=None, ws=None):
+    """Pairs from the walk buffer, negatives from the counters, and the iteration, in one call."""
+    dtype = _table_dtype(w_in)
+    num_nodes, dim = int(w_in.shape[0]), int(w_in.shape[1])
+    num_walks, walk_len = int(walks.shape[0]), int(walks.shape[1])
+    dev = w_in.device
+    if loss_out is None:
+        loss_out = torch.zeros(1, dtype=torch.float64, device=dev)
+    if ws is None:
+        ws = _workspace(gs_sgns_step_from_walks_workspace_bytes(num_pairs, num_nodes, k, dim, dtype), dev)
+    rc = lib().gs_sgns_step_from_walks(
+        _dev(w_in), _dev(w_out), C.c_int64(num_nodes), C.c_int32(dim), C.c_int32(dtype),
+        _dev(walks, torch.int32, "walks"), C.c_int64(num_walks), C.c_int32(walk_len), C.c_int32(window),
+        _dev(pair_offsets, torch.int64, "pair_offsets"), C.c_int64(first_pair), C.c_int64(num_pairs),
+        _alias_ref(noise), C.c_uint64(pair_index_base), C.c_uint64(neg_seed), C.c_int32(k),
+        C.c_float(lr), _dev(loss_out, torch.float64), _dev(ws), C.c_size_t(ws.numel()), _stream())
+    _check(rc, "gs_sgns_step_from_walks")
     return loss_out
 
 

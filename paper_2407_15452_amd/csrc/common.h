@@ -139,6 +139,39 @@ __device__ __forceinline__ uint32_t pack16(float lo, float hi) {
   return T::round(lo) | (T::round(hi) << 16);
 }
 
+// ---- skip-gram pair numbering inside one walk (Sec. 2.2; order: position, then offset) ----
+// f(x) = sum_{m=0}^{x-1} min(m, W).  A walk prefix of `len` nodes has
+// C(a) = f(a) + f(len) - f(len - a) pairs before position a, 2 f(len) in all.
+__device__ __forceinline__ int64_t window_prefix(int64_t x, int64_t w) {
+  return (x <= w + 1) ? x * (x - 1) / 2 : w * (w + 1) / 2 + (x - w - 1) * w;
+}
+__device__ __forceinline__ int64_t pairs_before(int64_t a, int64_t len, int64_t w) {
+  return window_prefix(a, w) + window_prefix(len, w) - window_prefix(len - a, w);
+}
+
+// length of the non-negative prefix of a row (-1 only ever forms a suffix)
+__device__ __forceinline__ int32_t valid_prefix(const int32_t* row, int32_t walk_len) {
+  int32_t lo = 0, hi = walk_len;
+  while (lo < hi) {
+    const int32_t mid = (lo + hi) >> 1;
+    if (row[mid] >= 0) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+// pair number q (0-based) of a walk prefix of `len` nodes: centre position a, context position
+__device__ __forceinline__ void pair_positions(int64_t q, int64_t len, int64_t window, int64_t& a,
+                                               int64_t& other) {
+  int64_t alo = 0, ahi = len - 1;                 // last a with pairs_before(a) <= q
+  while (alo < ahi) {
+    const int64_t mid = (alo + ahi + 1) >> 1;
+    if (pairs_before(mid, len, window) <= q) alo = mid; else ahi = mid - 1;
+  }
+  a = alo;
+  other = max((int64_t)0, a - window) + (q - pairs_before(a, len, window));
+  if (other >= a) ++other;
+}
+
 template <typename OffT>
 __device__ __forceinline__ int64_t load_off(const void* offsets, int64_t i) {
   return (int64_t) static_cast<const OffT*>(offsets)[i];

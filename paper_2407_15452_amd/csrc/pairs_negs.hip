@@ -5,25 +5,6 @@
 
 namespace gs {
 
-// f(x) = sum_{m=0}^{x-1} min(m, W).  A walk prefix of `len` nodes has
-// C(a) = f(a) + f(len) - f(len - a) pairs before position a, 2 f(len) in all.
-__device__ __forceinline__ int64_t window_prefix(int64_t x, int64_t w) {
-  return (x <= w + 1) ? x * (x - 1) / 2 : w * (w + 1) / 2 + (x - w - 1) * w;
-}
-__device__ __forceinline__ int64_t pairs_before(int64_t a, int64_t len, int64_t w) {
-  return window_prefix(a, w) + window_prefix(len, w) - window_prefix(len - a, w);
-}
-
-// length of the non-negative prefix of a row (-1 only ever forms a suffix)
-__device__ __forceinline__ int32_t valid_prefix(const int32_t* row, int32_t walk_len) {
-  int32_t lo = 0, hi = walk_len;
-  while (lo < hi) {
-    const int32_t mid = (lo + hi) >> 1;
-    if (row[mid] >= 0) lo = mid + 1; else hi = mid;
-  }
-  return lo;
-}
-
 __global__ void pairs_count_kernel(const int32_t* __restrict__ walks, int64_t num_walks,
                                    int32_t walk_len, int32_t window, int64_t* __restrict__ counts) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -65,15 +46,8 @@ __global__ __launch_bounds__(kEmitThreads) void pairs_emit_kernel(
     const int g = lo;
     const int64_t q = p - base_s[g];
     const int64_t len = len_s[g];
-    // centre position: last a with pairs_before(a) <= q
-    int64_t alo = 0, ahi = len - 1;
-    while (alo < ahi) {
-      const int64_t mid = (alo + ahi + 1) >> 1;
-      if (pairs_before(mid, len, window) <= q) alo = mid; else ahi = mid - 1;
-    }
-    const int64_t a = alo;
-    int64_t other = max((int64_t)0, a - window) + (q - pairs_before(a, len, window));
-    if (other >= a) ++other;
+    int64_t a, other;
+    pair_positions(q, len, window, a, other);
     const int32_t* row = rows + g * walk_len;
     centers[p] = row[a];
     contexts[p] = row[other];
@@ -168,6 +142,31 @@ extern "C" int32_t gs_make_pairs(const int32_t* walks, int64_t num_walks, int32_
     GS_LAUNCH_CHECK();
   }
   return GS_OK;
+}
+
+extern "C" size_t gs_pair_offsets_workspace_bytes(int64_t num_walks) {
+  if (num_walks < 0) return 0;
+  Carver cv(nullptr);
+  cv.take<int64_t>(scan_scratch_elems(num_walks > 0 ? num_walks : 1));
+  return cv.used;
+}
+
+extern "C" int32_t gs_pair_offsets(const int32_t* walks, int64_t num_walks, int32_t walk_len,
+                                   int32_t window, int64_t* offsets_out, void* ws, size_t ws_bytes,
+                                   void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  if (num_walks < 0 || walk_len < 1 || walk_len > 4096 || window < 1 || !offsets_out) return GS_EINVAL;
+  if (num_walks > 0 && !walks) return GS_EINVAL;
+  if (!ws || !aligned(ws, 256)) return GS_EINVAL;
+  if (ws_bytes < gs_pair_offsets_workspace_bytes(num_walks)) return GS_EWORKSPACE;
+  if (num_walks > 0) {
+    pairs_count_kernel<<<(unsigned)ceil_div(num_walks, 256), 256, 0, stream>>>(walks, num_walks, walk_len,
+                                                                             window, offsets_out);
+    GS_LAUNCH_CHECK();
+  }
+  // exclusive sums in place; the total goes to the entry after the last walk
+  return exclusive_scan_i64(offsets_out, num_walks, static_cast<int64_t*>(ws), offsets_out + num_walks,
+                            stream);
 }
 
 extern "C" int32_t gs_sample_negatives(const gs_alias* noise, int64_t num_nodes, int64_t num_pairs,

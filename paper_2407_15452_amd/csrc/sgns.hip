@@ -107,6 +107,18 @@ struct SgnsArgs {
   uint64_t neg_seed;
   uint64_t neg_pair_base;
   int32_t* negs_draw;
+  // pairs made inside the step (walks != null): pair i of the batch is pair first_pair + i of
+  // the canonical pair sequence of walks[0 .. num_walks) (walk, then centre position, then
+  // offset: the order of gs_make_pairs); pair_offsets[w] = number of pairs of the walks before
+  // w, pair_offsets[num_walks] = all of them.  The forward kernel writes the ids it derives to
+  // gen_centers / gen_contexts (which `centers` / `contexts` then point to) for the later kernels
+  const int32_t* walks;
+  const int64_t* pair_offsets;
+  int64_t num_walks;
+  int64_t first_pair;
+  int32_t walk_len, window;
+  int32_t* gen_centers;
+  int32_t* gen_contexts;
   // one table on both sides (first-order LINE; else null): the update kernel writes rows of
   // the table while input rows are still needed, so the forward kernel keeps a copy of every
   // input row it loads (one per run of equal centres, at the run's staging slot) and notes
@@ -494,11 +506,38 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
   int32_t* cen_s = idx_s + group_in_block * (a.chunk_pairs * (K1 + 1));
   int32_t* rows_s = cen_s + a.chunk_pairs;
   for (int h = threadIdx.x; h < kHotSlots; h += kSgnsThreads) { hot_key[h] = -1; hot_cnt[h] = 0u; }
-  if (l16 < count) cen_s[l16] = checked_row(a, a.centers[first + l16]);
+  if (a.walks != nullptr) {
+    if (l16 < count) {                      // lane p derives pair p of the chunk from its walk
+      int32_t c = 0, o = 0;
+      const int64_t gp = a.first_pair + first + l16;
+      if (gp < a.pair_offsets[a.num_walks]) {
+        int64_t lo = 0, hi = a.num_walks - 1;     // last walk w with pair_offsets[w] <= gp
+        while (lo < hi) {
+          const int64_t mid = (lo + hi + 1) >> 1;
+          if (a.pair_offsets[mid] <= gp) lo = mid; else hi = mid - 1;
+        }
+        const int32_t* row = a.walks + lo * (int64_t)a.walk_len;
+        const int64_t len = valid_prefix(row, a.walk_len);
+        int64_t at, other;
+        pair_positions(gp - a.pair_offsets[lo], len, a.window, at, other);
+        c = row[at];
+        o = row[other];
+      } else {
+        *a.bad_ids = 1u;                    // the walks do not hold that many pairs
+      }
+      a.gen_centers[first + l16] = c;
+      a.gen_contexts[first + l16] = o;
+      cen_s[l16] = checked_row(a, c);
+      rows_s[l16 * K1] = checked_row(a, o);
+    }
+  } else if (l16 < count) {
+    cen_s[l16] = checked_row(a, a.centers[first + l16]);
+  }
   for (int t = l16; t < count * K1; t += kGroupLanes) {
     const int p = t / K1, j = t - p * K1;
     int32_t row;
     if (j == 0) {
+      if (a.walks != nullptr) continue;     // set above
       row = checked_row(a, a.contexts[first + p]);
     } else if (a.draw_negs) {
       const Block4 b = philox_at(a.neg_seed, a.neg_pair_base + (uint64_t)(first + p), (uint32_t)(j - 1),
@@ -1351,6 +1390,12 @@ struct SgnsExtras {
   int32_t* negs_draw = nullptr;
   void* snap = nullptr;            // one table on both sides: copies of the input rows, pair slots
   int32_t* pair_slot = nullptr;
+  const int32_t* walks = nullptr;  // pairs made inside the step
+  const int64_t* pair_offsets = nullptr;
+  int64_t num_walks = 0, first_pair = 0;
+  int32_t walk_len = 0, window = 0;
+  int32_t* gen_centers = nullptr;
+  int32_t* gen_contexts = nullptr;
 };
 
 // Logits from (w_in, w_out); every touched row r of the destination tables becomes
@@ -1376,6 +1421,18 @@ static int32_t run_sgns(void* w_in, void* w_out, void* dst_in, void* dst_out, in
   if (a.draw_negs) negs = x.negs_draw;
   a.snap = x.snap;
   a.pair_slot = x.pair_slot;
+  a.walks = x.walks;
+  a.pair_offsets = x.pair_offsets;
+  a.num_walks = x.num_walks;
+  a.first_pair = x.first_pair;
+  a.walk_len = x.walk_len;
+  a.window = x.window;
+  a.gen_centers = x.gen_centers;
+  a.gen_contexts = x.gen_contexts;
+  if (a.walks != nullptr) {
+    centers = x.gen_centers;
+    contexts = x.gen_contexts;
+  }
   a.w_in = w_in;
   a.w_out = w_out;
   a.dst_in = dst_in;
@@ -1554,6 +1611,62 @@ extern "C" int32_t gs_sgns_step_fused(void* w_in, void* w_out, int64_t num_nodes
   x.negs_draw = negs_ws;
   return run_sgns(w_in, w_out, w_in, w_out, num_nodes, dim, dtype, centers, contexts, nullptr,
                   num_pairs, k, lr, loss_sum_out, p, stream, x);
+}
+
+// workspace of the call that makes its pairs: the step's own, the drawn negatives, the derived ids
+static size_t walk_ids_bytes(int64_t num_pairs) {
+  return align_up((size_t)(num_pairs > 0 ? num_pairs : 1) * sizeof(int32_t));
+}
+
+extern "C" size_t gs_sgns_step_from_walks_workspace_bytes(int64_t num_pairs, int64_t num_nodes, int32_t k,
+                                                          int32_t dim, int32_t dtype) {
+  (void)dtype;
+  if (num_pairs < 0 || num_nodes < 0 || k < 0 || dim < 1) return 0;
+  return plan_sgns(nullptr, num_pairs, num_nodes, k, dim).bytes + fused_negs_bytes(num_pairs, k) +
+         2 * walk_ids_bytes(num_pairs);
+}
+
+extern "C" int32_t gs_sgns_step_from_walks(void* w_in, void* w_out, int64_t num_nodes, int32_t dim,
+                                           int32_t dtype, const int32_t* walks, int64_t num_walks,
+                                           int32_t walk_len, int32_t window, const int64_t* pair_offsets,
+                                           int64_t first_pair, int64_t num_pairs, const gs_alias* noise,
+                                           uint64_t pair_index_base, uint64_t neg_seed, int32_t k,
+                                           float lr, double* loss_sum_out, void* ws, size_t ws_bytes,
+                                           void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  if (!walks || !pair_offsets || num_walks < 1 || walk_len < 1 || walk_len > 4096 || window < 1 ||
+      first_pair < 0)
+    return GS_EINVAL;
+  // the ids live in the workspace: hand the checker non-null stand-ins
+  const int32_t* stand_in = static_cast<const int32_t*>(ws);
+  const int32_t bad = check_sgns_args(w_in, w_out, num_nodes, dim, dtype, stand_in, stand_in, stand_in,
+                                      num_pairs, k, loss_sum_out, ws);
+  if (bad != GS_OK) return bad;
+  if (noise != nullptr && noise->prob != nullptr && !noise->alias) return GS_EINVAL;
+  SgnsPlan p = plan_sgns(ws, num_pairs, num_nodes, k, dim);
+  const size_t negs_bytes = fused_negs_bytes(num_pairs, k), ids_bytes = walk_ids_bytes(num_pairs);
+  if (ws_bytes < p.bytes + negs_bytes + 2 * ids_bytes) return GS_EWORKSPACE;
+  if (num_pairs == 0) {
+    zero_double_kernel<<<1, 1, 0, stream>>>(loss_sum_out);
+    GS_LAUNCH_CHECK();
+    return GS_OK;
+  }
+  char* extra = static_cast<char*>(ws) + p.bytes;
+  SgnsExtras x;
+  x.noise = noise;
+  x.neg_seed = neg_seed;
+  x.neg_pair_base = pair_index_base;
+  x.negs_draw = reinterpret_cast<int32_t*>(extra);
+  x.gen_centers = reinterpret_cast<int32_t*>(extra + negs_bytes);
+  x.gen_contexts = reinterpret_cast<int32_t*>(extra + negs_bytes + ids_bytes);
+  x.walks = walks;
+  x.pair_offsets = pair_offsets;
+  x.num_walks = num_walks;
+  x.first_pair = first_pair;
+  x.walk_len = walk_len;
+  x.window = window;
+  return run_sgns(w_in, w_out, w_in, w_out, num_nodes, dim, dtype, nullptr, nullptr, nullptr, num_pairs,
+                  k, lr, loss_sum_out, p, stream, x);
 }
 
 // workspace of the one-table step: the step's own, the copies of the input rows, the pair slots

@@ -929,3 +929,70 @@ def test_sgns_step_small_batch_on_large_graph(gs, oracle, b, k, fmt):
         # few elements are touched at all: one that rounds the other way is a large fraction
         assert_half_close(_bf16_bits(d_in), h_in, "bf16", flip_fraction=1e-3)
         assert_half_close(_bf16_bits(d_out), h_out, "bf16", flip_fraction=1e-3)
+
+
+# ----------------------------------------------------------------------------- pairs made inside the step
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("walk_len,window,k", [(20, 5, 5), (7, 9, 3), (33, 2, 0)])
+def test_sgns_step_from_walks(gs, oracle, walk_len, window, k, dtype):
+    """gs_pair_offsets + gs_sgns_step_from_walks against the oracle's make_pairs +
+    sample_negatives + sgns_step on the same walks: a directed graph with sinks (walks of every
+    length, some without any pair), batches cut at arbitrary pair indices (inside walks, across
+    several walks, the ragged last one), pair numbering continued over the batches."""
+    from paper_2407_15452_amd import inputs
+    n, dim = 3000, 64
+    rng = np.random.default_rng(walk_len * 100 + window)
+    src = rng.integers(0, n, 9000).astype(np.int32)
+    dst = rng.integers(0, n, 9000).astype(np.int32)
+    src[dst % 5 == 0] = dst[dst % 5 == 0]                # a fifth of the nodes only receive edges
+    flags = oracle.DROP_SELF_LOOPS | oracle.DEDUPE
+    off, nb, _ = oracle.csr_build(src, dst, None, n, flags)
+    g = gs.gs_csr_build(_t(src), _t(dst), None, n, flags)
+    starts = rng.integers(0, n, 1500).astype(np.int32)
+    h_walks = oracle.random_walk(off, nb, starts, walk_len, seed=21)
+    walks = gs.gs_random_walk(g, None, _t(starts), walk_len, 21)
+    np.testing.assert_array_equal(walks.cpu().numpy(), h_walks)
+    assert (h_walks[:, 1] < 0).any() and (h_walks[:, -1] >= 0).any()
+    hc, ho = oracle.make_pairs(h_walks, window)
+    total = hc.size
+    offsets = gs.gs_pair_offsets(walks, window)
+    per_walk = np.array([oracle.make_pairs(h_walks[i:i + 1], window)[0].size for i in range(len(starts))])
+    np.testing.assert_array_equal(offsets.cpu().numpy(), np.concatenate([[0], np.cumsum(per_walk)]))
+    nw = inputs.noise_weights(torch.as_tensor(off)).numpy()
+    seg = np.array([0, n], dtype=np.int32)
+    noise_h = oracle.alias_build(seg, nw)
+    noise_d = gs.gs_alias_build(_t(seg), _t(nw), pack=True)
+    f_in, f_out = inputs.random_tables(n, dim, seed=window, scale=0.2)
+    if dtype == "bf16":
+        d_in, d_out = f_in.to(torch.bfloat16).to(DEV), f_out.to(torch.bfloat16).to(DEV)
+        h_in, h_out = _bf16_bits(d_in).copy(), _bf16_bits(d_out).copy()
+        code = oracle.BF16
+    else:
+        d_in, d_out = f_in.to(DEV), f_out.to(DEV)
+        h_in, h_out = f_in.numpy().copy(), f_out.numpy().copy()
+        code = oracle.F32
+    cuts = sorted({0, 1, 7, total // 3 + 1, total // 3 + 2, 2 * total // 3 + 5, total})
+    base = (1 << 33) + 5
+    for lo, hi in zip(cuts[:-1], cuts[1:]):
+        m = hi - lo
+        neg = oracle.sample_negatives(noise_h, n, m, k, seed=77, pair_index_base=base + lo)
+        if k == 0:
+            neg = np.zeros((m, 0), dtype=np.int32)
+        want = oracle.sgns_step(h_in, h_out, hc[lo:hi], ho[lo:hi], neg, 0.02, dtype=code)
+        loss = gs.gs_sgns_step_from_walks(d_in, d_out, walks, window, offsets, lo, m, noise_d, k, 77,
+                                          0.02, pair_index_base=base + lo)
+        torch.cuda.synchronize()
+        assert abs(float(loss.item()) - want) <= LOSS_RTOL * abs(want)
+        if dtype == "bf16":
+            for d_t, h_t in ((d_in, h_in), (d_out, h_out)):
+                # small batches touch few elements: one that rounds the other way weighs more
+                assert_half_close(_bf16_bits(d_t), h_t, "bf16", flip_fraction=1e-3)
+                d_t.copy_(torch.from_numpy(h_t.view(np.int16)).view(torch.bfloat16))
+        else:
+            assert np.abs(d_in.cpu().numpy() - h_in).max() <= EMB_ATOL
+            assert np.abs(d_out.cpu().numpy() - h_out).max() <= EMB_ATOL
+            d_in.copy_(torch.from_numpy(h_in))
+            d_out.copy_(torch.from_numpy(h_out))
+    # a slice that reaches past the last pair is reported through the loss
+    loss = gs.gs_sgns_step_from_walks(d_in, d_out, walks, window, offsets, total - 3, 10, noise_d, k, 77, 0.02)
+    assert np.isnan(float(loss.item()))
