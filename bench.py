@@ -25,58 +25,51 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "sgns_step_hbm_traffic.json")
-SGNS_SOURCE = os.path.join(ROOT, "paper_2407_15452_amd", "csrc", "sgns.hip")
-WALK_SOURCE = os.path.join(ROOT, "paper_2407_15452_amd", "csrc", "walk.hip")
+CSRC = os.path.join(ROOT, "paper_2407_15452_amd", "csrc")
 
 
 def sgns_bytes_per_pair(k: int, dim: int, elem_bytes: int, window: int) -> float:
-    """Algorithmic HBM bytes per positive pair of one batch-synchronous SGNS
-    iteration without any cache reuse: every context/negative row is read once
-    for the logits and read-modified-written once for the update; the centre
-    row is read, staged and updated once per run of 2*window equal centres;
-    plus the index and gradient-coefficient arrays both passes read."""
+    """Algorithmic bytes per positive pair of one batch-synchronous SGNS iteration
+    without any reuse: K+2 rows read for the logits, K+1 context-table rows read
+    again and written for the update, the centre row read and written once per
+    run of 2*window equal centres ((3(K+1) + 2/(2W)) rows in all), the 8 + 4K
+    index bytes of the pair and 4 bytes of gradient coefficient per term."""
     rb = dim * elem_bytes
-    rows = 3 * (k + 1) * rb
-    centre = 4 * rb / (2 * window)
-    idx = 2 * 4 * (k + 2) + 2 * 4 * (k + 1)
-    return rows + centre + idx
+    return (3 * (k + 1) + 2.0 / (2 * window)) * rb + (8 + 4 * k) + 4 * (k + 1)
 
 
-def measured_traffic(workload_name: str):
-    """HBM bytes per gs_sgns_step call from the committed rocprofv3 counter runs,
-    or None when there is none for this workload or the kernels have changed
-    since the counters were taken."""
-    rec = traffic_record(workload_name)
-    return rec["hbm_bytes_per_call"] if rec else None
-
-
-def code_hash(path: str) -> str:
-    """sha256 of a C++ source with comments and white space removed: edits to comments do
-    not change it, edits to the code do."""
+def code_hash(*names: str) -> str:
+    """sha256 over C++ sources (comments and white space removed: edits to comments do not
+    change it, edits to the code do) and the compiler flags the library is built with."""
     import re
-    text = open(path, encoding="utf-8").read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    text = re.sub(r"//[^\n]*", "", text)
-    return hashlib.sha256(re.sub(r"\s+", "", text).encode()).hexdigest()
+    from paper_2407_15452_amd import build as gs_build
+    h = hashlib.sha256()
+    for name in names:
+        text = open(os.path.join(CSRC, name), encoding="utf-8").read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        text = re.sub(r"//[^\n]*", "", text)
+        h.update(re.sub(r"\s+", "", text).encode())
+    h.update(" ".join(gs_build.HIPCC_FLAGS).encode())
+    return h.hexdigest()
 
 
-def walk_record(workload_name: str):
-    """Counter record of the walker (bytes fetched per transition), or None when there is none
-    for this workload or walk.hip has changed since."""
+def stored_record(workload_name: str, hash_field: str, *sources: str):
+    """Counter record of a committed rocprofv3 run for this workload, or None when there is
+    none or the kernels it was taken on have changed since."""
     try:
         rec = json.load(open(TRAFFIC_FILE))[workload_name]
-        ok = rec["walk_hip_code_sha256"] == code_hash(WALK_SOURCE)
-        return rec if ok and "walk_fetch_bytes_per_transition" in rec else None
+        return rec if rec.get(hash_field) == code_hash(*sources) else None
     except (OSError, KeyError, ValueError):
         return None
 
 
 def traffic_record(workload_name: str):
-    try:
-        rec = json.load(open(TRAFFIC_FILE))[workload_name]
-        return rec if rec["sgns_hip_code_sha256"] == code_hash(SGNS_SOURCE) else None
-    except (OSError, KeyError, ValueError):
-        return None
+    return stored_record(workload_name, "sgns_code_sha256", "sgns.hip", "common.h")
+
+
+def walk_record(workload_name: str):
+    rec = stored_record(workload_name, "walk_code_sha256", "walk.hip", "common.h")
+    return rec if rec and "walk_fetch_bytes_per_transition" in rec else None
 
 
 def parse():
@@ -90,7 +83,8 @@ def parse():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the momentum / Adam / LINE / fused-negatives / get-put measurements")
     ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy (reference for HBM byte counters)")
+                    help="also run one plain 1 GiB device copy and one gather of 2^21 distinct random "
+                         "rows (kernels of known traffic: references for the byte counters)")
     ap.add_argument("--walk-sample", type=int, default=4_000_000,
                     help="walks in the stand-alone walk-throughput launch")
     return ap.parse_args()
@@ -221,6 +215,15 @@ def main():
         b_.copy_(a_)
         torch.cuda.synchronize()
         del a_, b_
+        # 2^21 distinct random rows of the input table into a dense block (gs_get_rows): reads
+        # 2^21 * row bytes at random, writes 2^21 * dim * 4 bytes in a stream
+        n_cal = min(1 << 21, wl.num_nodes)
+        ids_cal = torch.randperm(wl.num_nodes, device=dev, generator=torch.Generator(dev).manual_seed(1))
+        ids_cal = ids_cal[:n_cal].to(torch.int32).contiguous()
+        blk_cal = torch.empty((n_cal, wl.dim), dtype=torch.float32, device=dev)
+        gs.gs_get_rows(w_in, ids_cal, out=blk_cal)
+        torch.cuda.synchronize()
+        del ids_cal, blk_cal
 
     # ------------------------------------------------------------------ warm-up + timed region
     if W > 0:
@@ -262,7 +265,7 @@ def main():
     # ------------------------------------------------------------------ extra measurements
     # (other entry points on the same tables and batches; --no-extras leaves them out, e.g. for
     # a kernel profile of the timed path alone)
-    momentum_ms = adam_ms = fused = line = storage = None
+    momentum_ms = adam_ms = fused = line = storage = from_walks_ms = None
     if not args.no_extras:
         # ------------------------------------------------------------------ momentum variant (extra)
         # the paper's optimizer (dense mult / sparse put / dense mult_add); timed on the last batch
@@ -331,6 +334,40 @@ def main():
             torch.cuda.synchronize()
             fused[name] = e0.elapsed_time(e1) / K
         del fused_ws
+
+        # ------------------------------------------------------------------ pairs made in the step (extra)
+        # gs_make_pairs + gs_sample_negatives + gs_sgns_step per batch against one
+        # gs_sgns_step_from_walks per batch (gs_pair_offsets once per walk chunk), same batches
+        nw_t = starts_timed.numel()
+        wk_t = walks_buf[:nw_t]
+        fw_ws = torch.empty(gs.gs_sgns_step_from_walks_workspace_bytes(B, wl.num_nodes, k, wl.dim, sgns_dtype),
+                            dtype=torch.uint8, device=dev)
+        offs = gs.gs_pair_offsets(wk_t, win)
+
+        def from_walks(j):
+            gs.gs_sgns_step_from_walks(w_in, w_out, wk_t, win, offs, j * B, B, noise, k, wl.neg_seed, lr,
+                                       pair_index_base=j * B, loss_out=losses[:1], ws=fw_ws)
+
+        def three_calls(j):
+            if j == 0:
+                gs.gs_make_pairs(wk_t, win, centers, contexts, n_pairs_dev, pairs_ws, sync=False)
+            two_calls(j)
+
+        from_walks_ms = {}
+        for name, fn in (("make_pairs_negatives_step_ms", three_calls), ("from_walks_step_ms", from_walks)):
+            for j in range(min(2, K)):
+                fn(j)
+            torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            if name == "from_walks_step_ms":
+                gs.gs_pair_offsets(wk_t, win, out=offs)
+            for j in range(K):
+                fn(j)
+            e1.record()
+            torch.cuda.synchronize()
+            from_walks_ms[name] = e0.elapsed_time(e1) / K
+        del fw_ws, offs
 
         # ------------------------------------------------------------------ LINE batches (extra)
         # B sampled edges (uniform over the CSR entries) + negatives + the same step
@@ -447,12 +484,15 @@ def main():
         "momentum_step_ms": momentum_ms,
         "adam_step_ms": adam_ms,
         "fused_negatives": fused,
+        "pairs_made_in_step": from_walks_ms,
         "line": line,
         "storage_ops": storage,
         "roofline": {"bound": "hbm", "kernel": "gs_sgns_step (all kernels of one call)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "bytes_per_pair": bpp,
-                     "traffic": measured_traffic(wl.name)},
+                     "what": "algorithmic (no-reuse) bytes of the batch-synchronous iteration over the "
+                             "measured time of one call",
+                     "traffic": None},
     }
     wrec = walk_record(wl.name)
     if wrec:
@@ -462,15 +502,24 @@ def main():
                                    "achieved": rate, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                    "frac": rate / HBM_PEAK_GBS,
                                    "fetch_bytes_per_transition": wrec["walk_fetch_bytes_per_transition"],
+                                   "fetch_source": wrec.get("source", "profiles/") + " (stored; code hash matched)",
+                                   "fetch_measured_in_this_run": False,
+                                   "algorithmic_bytes_per_transition": 132,
+                                   "algorithmic_frac": 132 * walk_steps_per_s / 1e9 / HBM_PEAK_GBS,
                                    "l2_hit_rate": wrec.get("walk_l2_hit_rate")}
     rec = traffic_record(wl.name)
     if rec:
-        # counter-measured bytes of one call over the step time measured here: the HBM rate the
-        # step actually sustains, as a fraction of the peak, and the L2 hit rate of its kernels
+        # Bytes per call that crossed the L2 -> fabric boundary (FETCH_SIZE + WRITE_SIZE of a
+        # committed rocprofv3 counter run on the same kernels: stored, not measured in this run),
+        # over the step time measured here.  Reads served by the Infinity Cache count in it: it
+        # bounds the HBM traffic from above.
         rate = rec["hbm_bytes_per_call"] / (sgns_ms * 1e-3) / 1e9
-        result["roofline"]["traffic_GBps"] = rate
-        result["roofline"]["traffic_frac"] = rate / HBM_PEAK_GBS
-        result["roofline"]["l2_hit_rate"] = rec.get("l2_hit_rate")
+        result["roofline"].update({
+            "traffic": rec["hbm_bytes_per_call"], "traffic_GBps": rate, "traffic_frac": rate / HBM_PEAK_GBS,
+            "traffic_what": "L2-miss traffic (L2 <-> fabric bytes; Infinity Cache hits included)",
+            "traffic_source": rec.get("source", "profiles/") + " (stored; code hash matched)",
+            "traffic_measured_in_this_run": False,
+            "l2_hit_rate": rec.get("l2_hit_rate")})
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, g, row_alias, noise, w_in, w_out, lr)

@@ -241,7 +241,7 @@ int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int32_t dim, in
  * gs_sgns_step_static -- gs_sgns_step for callers that cannot allocate or hand
  * over device memory for a workspace: code under HIP graph capture, tight
  * training or serving loops, harnesses that forbid hipMalloc.  The scratch memory
- * of the step is an 8 MiB array that is part of the library's code object on
+ * of the step is a 12 MiB array that is part of the library's code object on
  * every GPU (held until the process ends); the call allocates and frees nothing.
  *   Same arguments (without ws, ws_bytes), results and errors as gs_sgns_step,
  *   for small batches: num_pairs <= 4096, num_pairs * (k+1) <= 65536, dim <=

@@ -24,7 +24,7 @@
 //   update     once over the context-table keys (source rows: the input table,
 //              still unmodified), then once over the input-table keys (source
 //              rows: the staged gradients): delta = sum coef * source row.
-//              Rows with at most kLongRow terms are handled whole by one
+//              Rows of one segment (256 terms, 64 in small batches) are handled whole by one
 //              16-lane group and written once; longer rows are summed slice by
 //              slice into a side buffer
 //   finish     table[row] = round(old + side buffer) for the long rows; one
@@ -61,8 +61,11 @@ constexpr int kGroupsPerBlock = kSgnsThreads / kGroupLanes;
 constexpr size_t kCompactFactor = 16;  // keys per batch entry beyond which the key space is compacted
 constexpr int kStageSlice = 8;     // staged gradients per 16-lane group in the input-table pass: they are
                                    // few (one per run of equal centres), so short slices keep the chip busy
-constexpr uint32_t kLongRow = 256; // rows with more terms than this go through the side buffer
-constexpr int kLongShift = 8;      // log2(kLongRow): side-buffer slot = first term position >> 8
+// Terms of one key are cut into segments of 2^seg_shift positions, each summed by one wave;
+// rows with more than one segment go through the side buffer (slot = position of the row's
+// first term >> seg_shift).  Long segments keep the side-buffer traffic low; small batches take
+// short ones, so that the few waves of a launch do not wait for one that sums a long segment.
+constexpr int kSegShiftLarge = 8, kSegShiftSmall = 6;
 constexpr int kScanThreads = 256;
 constexpr int kScanPerThread = 16;
 constexpr int kScanTile = kScanThreads * kScanPerThread;
@@ -132,7 +135,8 @@ struct SgnsArgs {
   int64_t num_nodes;
   int64_t num_terms;        // num_pairs * (k + 1): positions [0, num_terms) of `sorted` hold the
                             // context-table keys, the positions after them the input-table keys
-  int64_t long_slots;       // ((num_terms + num_pairs) >> kLongShift) + 1
+  int64_t long_slots;       // ((num_terms + num_pairs) >> seg_shift) + 1
+  int32_t seg_shift;        // log2 of the segment length
   int32_t chunk_pairs;      // consecutive pairs per 16-lane group in forward (<= 16)
   int32_t slice_terms;      // sorted terms per 16-lane group in update
   int32_t k;
@@ -778,8 +782,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(uint32_t* __re
 
 // ---- place: scatter the terms into key-major order ------------------------------
 // Entries [0, num_terms) are the (pair, j) terms, entries num_terms + s the staging slots.
-// The entry with position kLongRow (it exists exactly in the long rows) also clears the
-// row's slot of the side buffer.
+// The entry with position 2^seg_shift (it exists exactly in the rows of more than one
+// segment) also clears the row's slot of the side buffer.
 __global__ __launch_bounds__(256) void sgns_place_kernel(SgnsArgs a) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= a.num_terms + a.num_pairs) return;
@@ -805,8 +809,8 @@ __global__ __launch_bounds__(256) void sgns_place_kernel(SgnsArgs a) {
   const uint32_t begin = a.cnt[find_slot(a, t.row)];
   t.pos = rk;
   a.sorted[begin + rk] = t;
-  if (rk == kLongRow) {
-    long long* acc = a.long_acc + (int64_t)(begin >> kLongShift) * a.dim;
+  if (rk == (1u << a.seg_shift)) {
+    long long* acc = a.long_acc + (int64_t)(begin >> a.seg_shift) * a.dim;
     for (int x = 0; x < a.dim; ++x) acc[x] = 0;
   }
 }
@@ -878,9 +882,9 @@ __device__ __forceinline__ uint32_t uniform_u32(uint32_t x) {
 
 // first position >= p (and < limit) whose term starts a segment, else limit; wave-uniform
 __device__ __forceinline__ int64_t next_segment_start(const Term* __restrict__ sorted, int64_t p,
-                                                      int64_t limit, int lane) {
+                                                      int64_t limit, int lane, uint32_t seg_mask) {
   while (p < limit) {
-    const bool start = p + lane >= limit || (sorted[p + lane].pos & (kLongRow - 1u)) == 0u;
+    const bool start = p + lane >= limit || (sorted[p + lane].pos & seg_mask) == 0u;
     const unsigned long long mask = __builtin_amdgcn_ballot_w64(start);
     if (mask != 0ull) return min(limit, p + (int64_t)__builtin_ctzll(mask));
     p += 64;
@@ -888,13 +892,12 @@ __device__ __forceinline__ int64_t next_segment_start(const Term* __restrict__ s
   return limit;
 }
 
-// Ownership: the terms of a key are cut into segments of kLongRow consecutive positions
-// (pos = 0..255, 256..511, ...); a wave handles the segments whose first term lies in its
-// slice, reading on past the slice's end to finish the last one.  A row of at most kLongRow
+// Ownership: the terms of a key are cut into segments of S = 2^seg_shift consecutive
+// positions (pos = 0..S-1, S..2S-1, ...); a wave handles the segments whose first term lies
+// in its slice, reading on past the slice's end to finish the last one.  A row of at most S
 // terms is one segment: it is written once, as round(old + sum).  The partial sums of a row
 // with more segments meet in the side buffer at slot (position of the row's first term) >>
-// kLongShift, which no two such rows can share because each spans more than 2^kLongShift
-// positions.
+// seg_shift, which no two such rows can share because each spans more than S positions.
 // kStage = false: context-table keys, positions [0, num_terms), source rows from the input
 // table; kStage = true: input-table keys, the positions after them, source rows = staged
 // gradients (fp32, natural element order).
@@ -929,10 +932,11 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
 #pragma unroll
   for (int p = 0; p < PPL; ++p) piece_ok[p] = (p * 64 + lane) * EPP < a.dim;
 
+  const uint32_t seg_mask = (1u << a.seg_shift) - 1u;
   int64_t begin = slice_begin, end = slice_begin;
   if (active) {
-    begin = next_segment_start(sorted, slice_begin, pos_hi, lane);   // what lies before is an earlier wave's
-    end = next_segment_start(sorted, slice_end, pos_hi, lane);       // finish the segment we started
+    begin = next_segment_start(sorted, slice_begin, pos_hi, lane, seg_mask);   // what lies before is an earlier wave's
+    end = next_segment_start(sorted, slice_end, pos_hi, lane, seg_mask);       // finish the segment we started
   }
 
   unsigned long long acc[EPL];
@@ -944,7 +948,7 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
 #pragma unroll
     for (int w = 0; w < WPP; ++w) old[p][w] = 0u;
   uint32_t cur_row = kNoRow;       // key of the segment being summed (table row: cur_row - key_base)
-  uint32_t cur_seg = 0;            // its number within the key (pos >> kLongShift of its terms)
+  uint32_t cur_seg = 0;            // its number within the key (pos >> seg_shift of its terms)
   int64_t seg_first = 0;           // position of its first term
   uint32_t cur_terms = 0;          // terms added into acc since it was cleared
 
@@ -955,9 +959,9 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
     for (int x = 0; x < EPL; ++x) acc[x] -= off;
   };
   auto flush_long = [&]() {
-    const int64_t row_first = seg_first - ((int64_t)cur_seg << kLongShift);
+    const int64_t row_first = seg_first - ((int64_t)cur_seg << a.seg_shift);
     unsigned long long* dst = reinterpret_cast<unsigned long long*>(a.long_acc) +
-                              (row_first >> kLongShift) * a.dim;
+                              (row_first >> a.seg_shift) * a.dim;
 #pragma unroll
     for (int p = 0; p < PPL; ++p) {
       if (piece_ok[p]) {
@@ -1042,11 +1046,11 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
       for (int b = 0; b < UB; ++b) {
         if (b0 + b < n) {
           const uint32_t pos = (uint32_t)__builtin_amdgcn_readlane((int)t.pos, b0 + b);
-          if ((pos & (kLongRow - 1u)) == 0u) {           // a segment starts here
+          if ((pos & seg_mask) == 0u) {                  // a segment starts here
             const uint32_t row = (uint32_t)__builtin_amdgcn_readlane((int)t.row, b0 + b);
             if (cur_row != kNoRow) flush(row == cur_row);
             cur_row = row;
-            cur_seg = pos >> kLongShift;
+            cur_seg = pos >> a.seg_shift;
             seg_first = q + b0 + b;
             cur_terms = 0;
 #pragma unroll
@@ -1086,9 +1090,9 @@ template <typename T, if_16bit<T> = 0>
 __device__ __forceinline__ void elem_store(T* row, int e, float v) { row[e].bits = (uint16_t)T::round(v); }
 
 // ---- finish: table[row] = round(old + side buffer) for the long rows ------------------------
-// Side-buffer slot s belongs to the long row (more than kLongRow terms) whose first term
-// lies in [s << kLongShift, (s+1) << kLongShift): that row then also owns the last position
-// of the window.  The last block of the launch adds up the per-block
+// Side-buffer slot s belongs to the long row (more than one segment of S = 2^seg_shift terms)
+// whose first term lies in [s * S, (s+1) * S): that row then also owns the last position of
+// the window.  The last block of the launch adds up the per-block
 // loss partials instead (in a fixed order, so the loss is reproducible); a bad id
 // or an out-of-range product seen by an earlier kernel turns it into NaN.
 // which: 0 = long rows of both tables and the loss; 1 = context-table keys only, no loss;
@@ -1114,14 +1118,15 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_finish_kernel(SgnsArgs a, i
   }
   const int l16 = threadIdx.x & (kGroupLanes - 1);
   const int64_t s = ((int64_t)blockIdx.x * kSgnsThreads + threadIdx.x) / kGroupLanes;
-  const int64_t last_pos = ((s + 1) << kLongShift) - 1;
+  const int64_t last_pos = ((s + 1) << a.seg_shift) - 1;
   const int64_t total = (int64_t)a.cnt[a.cnt_last];
   if (last_pos >= total) return;
   const Term t = a.sorted[last_pos];
   const int64_t first_pos = last_pos - (int64_t)t.pos;
-  if ((first_pos >> kLongShift) != s) return;
-  // long: the row has a term at position kLongRow
-  if (first_pos + (int64_t)kLongRow >= total || a.sorted[first_pos + kLongRow].row != t.row) return;
+  if ((first_pos >> a.seg_shift) != s) return;
+  // long: the row has a term at position S
+  const int64_t second = first_pos + ((int64_t)1 << a.seg_shift);
+  if (second >= total || a.sorted[second].row != t.row) return;
   const bool input_row = (int64_t)t.row >= a.num_nodes;
   if (which != 0 && input_row != (which == 2)) return;
   const int64_t row = input_row ? (int64_t)t.row - a.num_nodes : (int64_t)t.row;
@@ -1151,6 +1156,9 @@ static int chunk_pairs_for(int64_t num_pairs) {
 static int slice_terms_for(int64_t num_pairs) {
   return num_pairs >= (1 << 20) ? 128 : (num_pairs >= (1 << 18) ? 64 : 32);
 }
+static int seg_shift_for(int64_t num_pairs) {
+  return num_pairs >= (1 << 18) ? kSegShiftLarge : kSegShiftSmall;
+}
 static int64_t forward_blocks_for(int64_t num_pairs) {
   return ceil_div(ceil_div(num_pairs, chunk_pairs_for(num_pairs)), kGroupsPerBlock);
 }
@@ -1171,6 +1179,7 @@ struct SgnsPlan {
   uint32_t* stage_rank;
   float* stage_delta;
   int64_t long_slots;
+  int32_t seg_shift;
   size_t bytes;
 };
 
@@ -1198,7 +1207,8 @@ static SgnsPlan plan_sgns(void* ws, int64_t num_pairs, int64_t num_nodes, int32_
     places = ((size_t)1 << p.out_bits) + ((size_t)1 << p.in_bits);
   }
   p.cnt_last = (int64_t)(compact ? places : keys);
-  p.long_slots = (int64_t)((terms + b) >> kLongShift) + 1;
+  p.seg_shift = seg_shift_for((int64_t)b);
+  p.long_slots = (int64_t)((terms + b) >> p.seg_shift) + 1;
   p.loss_partials = cv.take<double>((size_t)forward_blocks_for((int64_t)b));
   p.g = cv.take<float>(terms);
   p.rank = cv.take<uint32_t>(terms);
@@ -1444,6 +1454,7 @@ static int32_t run_sgns(void* w_in, void* w_out, void* dst_in, void* dst_out, in
   a.num_nodes = num_nodes;
   a.num_terms = num_pairs * (int64_t)(k + 1);
   a.long_slots = p.long_slots;
+  a.seg_shift = p.seg_shift;
   a.k = k;
   a.dim = dim;
   a.lr = lr;
@@ -1527,7 +1538,7 @@ extern "C" int32_t gs_sgns_step(void* w_in, void* w_out, int64_t num_nodes, int3
 constexpr int64_t kStaticMaxPairs = 4096;
 constexpr int64_t kStaticMaxTerms = 65536;
 constexpr int32_t kStaticMaxDim = 256;
-constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+constexpr size_t kStaticScratchBytes = (size_t)12 << 20;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 constexpr int kStaticMaxDevices = 64;
