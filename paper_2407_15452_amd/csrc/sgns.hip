@@ -59,6 +59,7 @@ constexpr int kSgnsThreads = 256;
 constexpr int kGroupLanes = 16;
 constexpr int kGroupsPerBlock = kSgnsThreads / kGroupLanes;
 constexpr size_t kCompactFactor = 16;  // keys per batch entry beyond which the key space is compacted
+constexpr int64_t kStageMaxBlocks = 8192;   // launch of the input-table pass (its waves stride over the slices)
 constexpr int kStageSlice = 8;     // staged gradients per 16-lane group in the input-table pass: they are
                                    // few (one per run of equal centres), so short slices keep the chip busy
 // Terms of one key are cut into segments of 2^seg_shift positions, each summed by one wave;
@@ -147,13 +148,17 @@ struct SgnsArgs {
   uint32_t* cnt;            // [cnt_last + 1] counters, indexed by the slot of a key; after scan: offsets,
                             // and entry cnt_last holds the number of positions in use
   int64_t cnt_last;
-  // Compacted key space, for graphs much larger than the batch (else null: slot = key): an
-  // open-addressing table of the keys the batch holds; the slot of a key is where it sits.
-  // The context-table keys have the first 1 << out_bits places to themselves and the
-  // input-table keys the 1 << in_bits places after them, so that in `sorted` every
-  // context-table key still comes before every input-table key.
-  uint32_t* key_table;      // [(1 << out_bits) + (1 << in_bits)], kNoRow = free
+  // Counter slots.  The context-table keys take the slots [0, in_base), the input-table keys
+  // the slots from in_base on, so that in `sorted` every context-table key comes before every
+  // input-table key.  A kind of key is either counted per vertex (bits == 0: slot = vertex) or,
+  // when the graph is much larger than the batch, through an open-addressing table of
+  // 1 << bits places holding the keys of the batch (slot = the key's place).  The batch has
+  // few input-table keys (one per run of equal centres), so those go through a table sooner.
+  uint32_t* key_table;      // [table_places = (out_bits ? 1 << out_bits : 0) + (in_bits ? 1 << in_bits : 0)],
+                            // kNoRow = free
+  int64_t table_places;
   int32_t out_bits, in_bits;
+  uint32_t in_base;
   uint32_t* tile_sums;      // scan scratch
   Term* sorted;             // [num_terms + num_pairs]
   long long* long_acc;      // [long_slots][dim] exact sums of the long rows
@@ -411,34 +416,40 @@ __device__ __forceinline__ int64_t xcd_contiguous_block(int64_t bid, int64_t per
 // many places as the batch can hold keys) and the place kernel looks them up (find_slot).
 // Which slot a key gets depends on the order of arrival, and with it the order of the rows in
 // `sorted`; the results do not (exact sums).
-struct KeyRegion { uint32_t base, mask, first; };   // places [base, base + mask], probing from first
+struct KeyRegion {
+  uint32_t slot_base;   // first counter slot of this kind of key
+  uint32_t vertex;      // the key's vertex
+  uint32_t* table;      // the kind's table (bits != 0)
+  int bits;
+};
 __device__ __forceinline__ KeyRegion key_region(const SgnsArgs& a, uint32_t key) {
   const bool input_key = key >= (uint32_t)a.num_nodes;
-  const int bits = input_key ? a.in_bits : a.out_bits;
   KeyRegion r;
-  r.base = input_key ? (1u << a.out_bits) : 0u;
-  r.mask = (1u << bits) - 1u;
-  r.first = (key * 2654435761u) >> (32 - bits);
+  r.slot_base = input_key ? a.in_base : 0u;
+  r.vertex = input_key ? key - (uint32_t)a.num_nodes : key;
+  r.bits = input_key ? a.in_bits : a.out_bits;
+  r.table = a.key_table + ((input_key && a.out_bits != 0) ? (1u << a.out_bits) : 0u);
   return r;
 }
 __device__ __forceinline__ uint32_t claim_slot(const SgnsArgs& a, uint32_t key) {
-  if (a.key_table == nullptr) return key;
   const KeyRegion r = key_region(a, key);
-  uint32_t h = r.first;
+  if (r.bits == 0) return r.slot_base + r.vertex;
+  const uint32_t mask = (1u << r.bits) - 1u;
+  uint32_t h = (key * 2654435761u) >> (32 - r.bits);
   while (true) {
-    uint32_t* place = a.key_table + r.base + h;
-    uint32_t seen = __hip_atomic_load(place, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (seen == kNoRow) seen = atomicCAS(place, kNoRow, key);
-    if (seen == kNoRow || seen == key) return r.base + h;
-    h = (h + 1u) & r.mask;
+    uint32_t seen = __hip_atomic_load(r.table + h, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (seen == kNoRow) seen = atomicCAS(r.table + h, kNoRow, key);
+    if (seen == kNoRow || seen == key) return r.slot_base + h;
+    h = (h + 1u) & mask;
   }
 }
 __device__ __forceinline__ uint32_t find_slot(const SgnsArgs& a, uint32_t key) {
-  if (a.key_table == nullptr) return key;
   const KeyRegion r = key_region(a, key);
-  uint32_t h = r.first;
-  while (a.key_table[r.base + h] != key) h = (h + 1u) & r.mask;   // every key of the batch is in the table
-  return r.base + h;
+  if (r.bits == 0) return r.slot_base + r.vertex;
+  const uint32_t mask = (1u << r.bits) - 1u;
+  uint32_t h = (key * 2654435761u) >> (32 - r.bits);
+  while (r.table[h] != key) h = (h + 1u) & mask;   // every key of the batch is in the table
+  return r.slot_base + h;
 }
 
 // ---- clear / fill ---------------------------------------------------------------------
@@ -920,11 +931,8 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
   // lane numbers of the broadcasts below must live in scalar registers)
   const int64_t pos_hi = kStage ? (int64_t)uniform_u32(a.cnt[a.cnt_last]) : a.num_terms;
   const int lane = threadIdx.x & 63;
-  const int64_t wave = (int64_t)blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int64_t first_wave = (int64_t)blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int slice = kStage ? kStageSlice : a.slice_terms;
-  const int64_t slice_begin = pos_lo + wave * slice;
-  const bool active = slice_begin < pos_hi;
-  const int64_t slice_end = min(slice_begin + slice, pos_hi);
   const Term* __restrict__ sorted = a.sorted;
   const int64_t src_row_words = kStage ? (int64_t)a.dim : (int64_t)a.dim / Words<T>::kPerWord;
   const int64_t dst_row_words = (int64_t)a.dim / Words<T>::kPerWord;
@@ -933,11 +941,14 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
   for (int p = 0; p < PPL; ++p) piece_ok[p] = (p * 64 + lane) * EPP < a.dim;
 
   const uint32_t seg_mask = (1u << a.seg_shift) - 1u;
-  int64_t begin = slice_begin, end = slice_begin;
-  if (active) {
-    begin = next_segment_start(sorted, slice_begin, pos_hi, lane, seg_mask);   // what lies before is an earlier wave's
-    end = next_segment_start(sorted, slice_end, pos_hi, lane, seg_mask);       // finish the segment we started
-  }
+  // a wave takes the slices first_wave, first_wave + (waves of the launch), ...: the launch of
+  // the input-table pass is sized for the few slots a batch normally uses, not for one per pair
+  for (int64_t wave = first_wave;; wave += (int64_t)gridDim.x * kWaves) {
+  const int64_t slice_begin = pos_lo + wave * slice;
+  if (slice_begin >= pos_hi) break;
+  const int64_t slice_end = min(slice_begin + slice, pos_hi);
+  const int64_t begin = next_segment_start(sorted, slice_begin, pos_hi, lane, seg_mask);   // what lies before is an earlier wave's
+  const int64_t end = next_segment_start(sorted, slice_end, pos_hi, lane, seg_mask);       // finish the segment we started
 
   unsigned long long acc[EPL];
   uint32_t old[PPL][WPP];
@@ -1079,6 +1090,7 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_update_kernel(SgnsArgs a) {
   }
   // last pending segment: the row goes on if the term after the range has the same key
   if (cur_row != kNoRow) flush(end < pos_hi && uniform_u32(sorted[end].row) == cur_row);
+  }
 }
 
 // element-wise row helpers for the finishing kernel (natural order)
@@ -1169,8 +1181,10 @@ struct SgnsPlan {
   uint32_t* rank;
   uint32_t* cnt;
   int64_t cnt_last;         // counters are cnt[0 .. cnt_last]
-  uint32_t* key_table;      // compacted key space (null: slot = key)
+  uint32_t* key_table;      // tables of the batch's keys (null: none)
+  int64_t table_places;
   int32_t out_bits, in_bits;
+  uint32_t in_base;
   uint32_t* tile_sums;
   uint32_t* bad_ids;
   Term* sorted;
@@ -1197,23 +1211,26 @@ static SgnsPlan plan_sgns(void* ws, int64_t num_pairs, int64_t num_nodes, int32_
   // counters go over the places of a table of the keys the batch holds (at most one per term
   // and per pair): everything that is cleared, scanned or hit at random in a call then has
   // the size of the batch, not of the graph.
+  // (a table has at least twice as many places as there can be keys of its kind)
+  const size_t nodes = keys / 2;
   const bool compact = force_compact || keys > kCompactFactor * (terms + b);
-  p.out_bits = p.in_bits = 0;
-  size_t places = 0;
-  if (compact) {                 // at least twice as many places as there can be keys of a kind
-    p.out_bits = p.in_bits = 8;
-    while (((size_t)1 << p.out_bits) < 2 * terms) ++p.out_bits;
-    while (((size_t)1 << p.in_bits) < 2 * b) ++p.in_bits;
-    places = ((size_t)1 << p.out_bits) + ((size_t)1 << p.in_bits);
-  }
-  p.cnt_last = (int64_t)(compact ? places : keys);
+  int in_bits = 8, out_bits = 8;
+  while (((size_t)1 << out_bits) < 2 * terms) ++out_bits;
+  while (((size_t)1 << in_bits) < 2 * b) ++in_bits;
+  p.out_bits = compact ? out_bits : 0;
+  p.in_bits = (compact || ((size_t)1 << in_bits) < nodes) ? in_bits : 0;
+  const size_t out_slots = p.out_bits ? (size_t)1 << p.out_bits : nodes;
+  const size_t in_slots = p.in_bits ? (size_t)1 << p.in_bits : nodes;
+  p.in_base = (uint32_t)out_slots;
+  p.table_places = (int64_t)((p.out_bits ? (size_t)1 << p.out_bits : 0) + (p.in_bits ? (size_t)1 << p.in_bits : 0));
+  p.cnt_last = (int64_t)(out_slots + in_slots);
   p.seg_shift = seg_shift_for((int64_t)b);
   p.long_slots = (int64_t)((terms + b) >> p.seg_shift) + 1;
   p.loss_partials = cv.take<double>((size_t)forward_blocks_for((int64_t)b));
   p.g = cv.take<float>(terms);
   p.rank = cv.take<uint32_t>(terms);
   p.cnt = cv.take<uint32_t>((size_t)p.cnt_last + 1 + 3);                   // cleared 16 bytes at a time
-  p.key_table = compact ? cv.take<uint32_t>(places) : nullptr;
+  p.key_table = p.table_places > 0 ? cv.take<uint32_t>((size_t)p.table_places) : nullptr;
   p.tile_sums = cv.take<uint32_t>((size_t)ceil_div(p.cnt_last + 1, kScanTile));
   p.bad_ids = cv.take<uint32_t>(1);
   p.sorted = cv.take<Term>(terms + b);
@@ -1232,7 +1249,7 @@ static int32_t launch_updates(const SgnsArgs& a, hipStream_t stream) {
   constexpr int kWaves = kSgnsThreads / 64;
   // context-table keys: exactly num_terms positions; input-table keys: at most one per pair
   const unsigned out_blocks = (unsigned)ceil_div(ceil_div(a.num_terms, a.slice_terms), kWaves);
-  const unsigned in_blocks = (unsigned)ceil_div(ceil_div(a.num_pairs, kStageSlice), kWaves);
+  const unsigned in_blocks = (unsigned)min((int64_t)kStageMaxBlocks, ceil_div(ceil_div(a.num_pairs, kStageSlice), kWaves));
   const size_t lds = 0;
   const unsigned finish_blocks = (unsigned)ceil_div(a.long_slots, kGroupsPerBlock) + 1;
   const bool one_table = a.snap != nullptr;
@@ -1256,7 +1273,7 @@ static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
   const int64_t keys1 = a.cnt_last + 1;
   const int64_t tiles = ceil_div(keys1, kScanTile);
   const int64_t keys4 = ceil_div(keys1, 4);
-  const int64_t table4 = a.key_table != nullptr ? a.cnt_last / 4 : 0;   // (a multiple of four places)
+  const int64_t table4 = a.table_places / 4;   // (tables have at least 256 places each)
   sgns_clear_kernel<<<(unsigned)ceil_div(max(keys4, table4), 256), 256, 0, stream>>>(
       (uint4*)a.cnt, keys4, (uint4*)a.key_table, table4, a.bad_ids);
   GS_LAUNCH_CHECK();
@@ -1463,8 +1480,10 @@ static int32_t run_sgns(void* w_in, void* w_out, void* dst_in, void* dst_out, in
   a.cnt = p.cnt;
   a.cnt_last = p.cnt_last;
   a.key_table = p.key_table;
+  a.table_places = p.table_places;
   a.out_bits = p.out_bits;
   a.in_bits = p.in_bits;
+  a.in_base = p.in_base;
   a.tile_sums = p.tile_sums;
   a.bad_ids = p.bad_ids;
   a.sorted = p.sorted;
