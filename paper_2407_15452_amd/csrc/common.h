@@ -67,8 +67,11 @@ __device__ __forceinline__ Block4 philox4x32_10(uint32_t c0, uint32_t c1, uint32
                                                 uint32_t k0, uint32_t k1) {
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
-    const uint32_t hi_a = __umulhi(0xD2511F53u, c0), lo_a = 0xD2511F53u * c0;
-    const uint32_t hi_b = __umulhi(0xCD9E8D57u, c2), lo_b = 0xCD9E8D57u * c2;
+    // one 32 x 32 -> 64 bit multiply per product (both halves from one instruction)
+    const uint64_t pa = (uint64_t)0xD2511F53u * (uint64_t)c0;
+    const uint64_t pb = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+    const uint32_t hi_a = (uint32_t)(pa >> 32), lo_a = (uint32_t)pa;
+    const uint32_t hi_b = (uint32_t)(pb >> 32), lo_b = (uint32_t)pb;
     c0 = hi_b ^ c1 ^ k0;
     c1 = lo_b;
     c2 = hi_a ^ c3 ^ k1;
