@@ -31,7 +31,6 @@ struct WalkArgs {
   uint64_t seed;
   int32_t walk_len;
   float inv_p, inv_q, max_bias;
-  float inv_num_nodes;
 };
 
 // Alias step of a weighted draw: keep slot j, or move to the slot's alias.
@@ -110,11 +109,12 @@ __global__ __launch_bounds__(kWalkThreads) void walk_kernel(WalkArgs a) {
 // carries its own state (which read it needs next), each iteration issues that
 // one read for all 64 lanes together, and the lane then moves to its next state;
 // lanes never wait for each other except at the one load per iteration.
-// The membership search in the previous node's row reads four neighbouring entries per
-// probe (one 16-byte access, the same cache line as a 4-byte one): first an interpolated
-// guess (the ids of a row are spread over [0, num_nodes)), then a second guess from the
-// entries just read, then bisection; a probe whose entries lie on both sides of x ends
-// the search at once.  About half as many probes as a one-entry binary search.
+// The membership search in the previous node's row is an interpolation search (the ids of
+// a row are spread evenly over [0, num_nodes), so x is expected where a straight line
+// between the entries that bound the remaining range puts it; every third probe bisects
+// instead, which bounds the search on rows that are not spread evenly).  A probe reads four
+// neighbouring entries (one 16-byte access, the same cache line as a 4-byte one), and a
+// probe whose entries lie on both sides of x ends the search at once.
 // Each lane stages its own last kWin positions in LDS and writes them out as one
 // 64-byte row segment when the window is full (or the walk is over).
 struct __attribute__((packed, aligned(4))) Quad { int32_t v[4]; };   // four entries, 4-byte aligned
@@ -152,11 +152,11 @@ __global__ __launch_bounds__(kWalkThreads) void node2vec_kernel(WalkArgs a) {
   uint32_t word2 = 0;                       // alias uniform (weighted)
   float s = 0.f;                            // acceptance uniform * max_bias
   int32_t x = 0;                            // candidate
-  // the membership search in flight: entries before L are < x, entries from H on are > x
-  int64_t L = 0, H = 0, p = 0;
-  float slope = 0.f;
+  // the membership search in flight: entries before L are < x, entries from H on are > x;
+  // v_lo < x is the entry before L (or -1), v_hi > x the entry at H (or num_nodes)
+  int64_t L = 0, H = 0;
+  int32_t v_lo = 0, v_hi = 0;
   int probes = 0;                           // probes made in this search
-  int32_t vnear = 0;                        // entry next to the remaining range, from the last probe
   int64_t pos = 0;                          // what this iteration reads: nbrs[pos] (or the alias entry at pos)
 
   // position t + 1 of the walk is `node`: into the lane's window, and out when it is full
@@ -202,9 +202,13 @@ __global__ __launch_bounds__(kWalkThreads) void node2vec_kernel(WalkArgs a) {
       pos = lo + j;
       state = (kWeighted ? kAlias : kDraw);
     } else if (state == kSearch) {           // (the range [L, H) is never empty here)
-      if (probes == 0) p = L + (int64_t)((float)x * slope);
-      else if (probes == 1) p = p + (int64_t)((float)(x - vnear) * slope);
-      else p = L + ((H - L) >> 1);
+      int64_t p;
+      if (probes % 3 == 2) {
+        p = L + ((H - L) >> 1);
+      } else {
+        const float part = (float)((int64_t)x - v_lo) / (float)((int64_t)v_hi - v_lo);
+        p = L + (int64_t)(part * (float)(H - L));
+      }
       p = min(max(p, L), H - 1);
       // the four entries around p: an aligned group, or the array's last four
       pos = wide ? min(p & ~(int64_t)3, a.num_entries - 4) : p;
@@ -254,9 +258,9 @@ __global__ __launch_bounds__(kWalkThreads) void node2vec_kernel(WalkArgs a) {
         if (!(s < bias_hi)) { decision = kReject; break; }
         L = prev_lo; H = prev_hi;
         if (L >= H) { known = true; break; }                       // (prev has no row: cannot happen after a step)
-        // ids of a row are spread over [0, num_nodes): x is expected near L + x * n / num_nodes
-        slope = (float)(H - L) * a.inv_num_nodes;
-        probes = (H - L > 16) ? 0 : 2;      // short rows: bisection from the start
+        v_lo = -1;
+        v_hi = (int32_t)a.num_nodes;
+        probes = 0;
         state = kSearch;
         break;
       case kSearch: {
@@ -273,8 +277,8 @@ __global__ __launch_bounds__(kWalkThreads) void node2vec_kernel(WalkArgs a) {
         }
         ++probes;
         if (found) { known = true; member = true; break; }
-        if (x < first_v) { H = pos + i0; vnear = first_v; }
-        else if (x > last_v) { L = pos + i1 + 1; vnear = last_v; }
+        if (x < first_v) { H = pos + i0; v_hi = first_v; }
+        else if (x > last_v) { L = pos + i1 + 1; v_lo = last_v; }
         else known = true;                  // x lies between two neighbouring entries
         if (L >= H) known = true;
         break;
@@ -328,7 +332,6 @@ static int32_t walk_common(const gs_csr* g, const gs_alias* al, const int32_t* s
   a.inv_p = 1.0f / p;
   a.inv_q = 1.0f / q;
   a.max_bias = fmaxf(a.inv_p, fmaxf(1.0f, a.inv_q));
-  a.inv_num_nodes = g->num_nodes > 0 ? 1.0f / (float)g->num_nodes : 0.0f;
   if (g->offset_bits == 64) launch_walk<int64_t>(weighted, second, a, stream);
   else launch_walk<int32_t>(weighted, second, a, stream);
   GS_LAUNCH_CHECK();
