@@ -219,16 +219,22 @@ int32_t gs_sample_edges(const gs_csr* g, const gs_alias* edge_alias, int64_t num
  *   occurrences in the batch.  loss_sum_out double[1] on the device receives
  *   the sum of loss_i (overwritten).
  *   Every touched element is written once, as round(old + delta) with delta
- *   summed in fp32 (bf16: round to nearest even).
+ *   the exact sum of the fp32 products (16-bit formats: round to nearest even
+ *   through fp32).
  *   dim must be a multiple of 4 (fp32) or 8 (16-bit) and at most 1024; k <= 60;
  *   num_pairs * (k+1) < 2^31.  Rows that the batch does not name are not
  *   touched.  w_in and w_out must be two tables (GS_EINVAL if they are the
  *   same address).  The ids live on the device and are checked there: an id
  *   outside [0, num_nodes) is treated as row 0, so no access leaves the
  *   tables, and loss_sum_out is set to NaN to report it (the tables are then
- *   not meaningful).  The workspace holds the per-term coefficients, the terms
- *   regrouped by destination row, a counter per node, an fp32 side buffer for
- *   rows with many terms and the staged centre-row gradients.
+ *   not meaningful).  The same report is made when a product lr * element
+ *   reaches 16384 in magnitude (the exact accumulation of the row sums covers
+ *   products below 32768).  The row sums are exact (64-bit fixed point, multiples
+ *   of 2^-36), so the same call on the same inputs gives the same bits every
+ *   time.  The workspace holds the per-term coefficients, the terms regrouped by
+ *   destination row, a counter per key (two per node, or per key of the batch
+ *   when the graph is much larger than the batch), a side buffer for rows with
+ *   many terms and the staged centre-row gradients.
  * ------------------------------------------------------------------------ */
 size_t gs_sgns_step_workspace_bytes(int64_t num_pairs, int64_t num_nodes, int32_t k, int32_t dim,
                                     int32_t dtype);

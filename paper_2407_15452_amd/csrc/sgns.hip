@@ -12,34 +12,40 @@
 // Destination rows of both tables share one key space: key r < N is row r of
 // the context table (its terms are the (pair, j) logits that name it), key N + c
 // is row c of the input table (its terms are the staged gradients of the runs
-// of equal centres).
+// of equal centres).  A key has a counter slot: the key itself, or, when the
+// graph is much larger than the batch, its place in a table of the batch's keys
+// (so that nothing cleared, scanned or hit at random has the size of the graph).
 //
-//   clear      cnt[0..2N] = 0
+//   clear      counters 0, key tables empty
 //   forward    read-only on both tables: logits, g = dLoss/dx, loss, the
 //              centre-row gradient of every run of equal centres staged in a
-//              slot, and rank = cnt[key]++ for every term and every used slot
+//              slot, and rank = cnt[slot of key]++ for every term and every
+//              used staging slot (optionally the pairs themselves from the walk
+//              buffer and the negatives from their counters)
 //   scan       off = exclusive prefix sum of cnt
-//   place      sorted[off[key] + rank] = (key, source row, coefficient):
+//   place      sorted[off[key] + rank] = (key, source row, coefficient, rank):
 //              (context row, centre, -lr * g) or (N + centre, slot, -lr)
 //   update     once over the context-table keys (source rows: the input table,
 //              still unmodified), then once over the input-table keys (source
-//              rows: the staged gradients): delta = sum coef * source row.
-//              Rows of one segment (256 terms, 64 in small batches) are handled whole by one
-//              16-lane group and written once; longer rows are summed slice by
-//              slice into a side buffer
-//   finish     table[row] = round(old + side buffer) for the long rows; one
+//              rows: the staged gradients): delta = sum coef * source row.  A
+//              whole wave works on one row at a time.  The terms of a key are cut
+//              into segments of 256 positions (64 in small batches); a row of one
+//              segment is written once, as round(old + delta); the segments of a
+//              longer row are added into a side buffer
+//   finish     table[row] = round(old + side buffer) for the longer rows; one
 //              extra block sums the per-block loss partials in a fixed order
 //
 // delta is accumulated exactly: every product coef * element is rounded once to
 // a multiple of 2^-36 (one fp64 fused multiply-add against 1.5 * 2^52, whose
 // result bits hold the integer) and the 64-bit integers are added.  Integer
 // addition is associative, so the result does not depend on the order in which
-// the terms of a row arrive (ranks come from atomics) or on how a long row is
-// split: the same call gives the same bits every time.
+// the terms of a row arrive (ranks come from atomics), on the places the keys
+// get in their table, or on how a long row is split: the same call gives the
+// same bits every time.
 //
-// A row is handled by 16 lanes holding 16-byte pieces (256 contiguous bytes per
-// load instruction); a wave works on four rows at once and a dot product is a
-// 16-lane DPP reduction.  No matrix cores: 0.3 flop per byte moved.
+// Forward: a row is handled by 16 lanes holding 16-byte pieces (256 contiguous
+// bytes per load instruction); a wave works on four rows at once and a dot
+// product is a 16-lane DPP reduction.  No matrix cores: 0.3 flop per byte moved.
 //
 // The other entry points of this file run the same kernels with a few switches
 // (SgnsArgs / SgnsExtras): the momentum and Adam steps write the row sums into
