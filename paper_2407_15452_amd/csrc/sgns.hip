@@ -797,6 +797,36 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(uint32_t* __re
   }
 }
 
+// The whole scan in one block, for the few counters of a small batch (one kernel instead of
+// two on a path that is bound by its number of dependent kernels): a thread sums its stretch
+// of consecutive entries, the block scans the sums, the thread writes its stretch.
+constexpr int64_t kScanSmallMax = 1 << 17;
+__global__ __launch_bounds__(1024) void scan_small_kernel(uint32_t* __restrict__ data, int64_t n) {
+  __shared__ uint32_t wave_tot[16];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t per = (n + 1023) / 1024;
+  const int64_t lo = min(n, (int64_t)threadIdx.x * per), hi = min(n, lo + per);
+  uint32_t local = 0;
+  for (int64_t i = lo; i < hi; ++i) local += data[i];
+  uint32_t incl = local;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t up = __shfl_up(incl, d, 64);
+    if (lane >= d) incl += up;
+  }
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  uint32_t run = incl - local;
+#pragma unroll
+  for (int w = 0; w < 16; ++w)
+    if (w < wave) run += wave_tot[w];
+  for (int64_t i = lo; i < hi; ++i) {
+    const uint32_t v = data[i];
+    data[i] = run;
+    run += v;
+  }
+}
+
 // ---- place: scatter the terms into key-major order ------------------------------
 // Entries [0, num_terms) are the (pair, j) terms, entries num_terms + s the staging slots.
 // The entry with position 2^seg_shift (it exists exactly in the rows of more than one
@@ -1287,15 +1317,20 @@ static int32_t launch_sgns(const SgnsArgs& a, hipStream_t stream) {
   sgns_forward_kernel<T, VPL, RB><<<(unsigned)(a.forward_blocks_per_xcd * 8), kSgnsThreads, idx_lds,
                                    stream>>>(a);
   GS_LAUNCH_CHECK();
-  scan_reduce_kernel<<<(unsigned)tiles, kScanThreads, 0, stream>>>(a.cnt, keys1, a.tile_sums);
-  GS_LAUNCH_CHECK();
-  const int raw_sums = tiles <= kFewTiles ? 1 : 0;
-  if (!raw_sums) {
-    scan_tiles_kernel<<<1, 1024, 0, stream>>>(a.tile_sums, tiles);
+  if (keys1 <= kScanSmallMax) {
+    scan_small_kernel<<<1, 1024, 0, stream>>>(a.cnt, keys1);
+    GS_LAUNCH_CHECK();
+  } else {
+    scan_reduce_kernel<<<(unsigned)tiles, kScanThreads, 0, stream>>>(a.cnt, keys1, a.tile_sums);
+    GS_LAUNCH_CHECK();
+    const int raw_sums = tiles <= kFewTiles ? 1 : 0;
+    if (!raw_sums) {
+      scan_tiles_kernel<<<1, 1024, 0, stream>>>(a.tile_sums, tiles);
+      GS_LAUNCH_CHECK();
+    }
+    scan_apply_kernel<<<(unsigned)tiles, kScanThreads, 0, stream>>>(a.cnt, keys1, a.tile_sums, raw_sums);
     GS_LAUNCH_CHECK();
   }
-  scan_apply_kernel<<<(unsigned)tiles, kScanThreads, 0, stream>>>(a.cnt, keys1, a.tile_sums, raw_sums);
-  GS_LAUNCH_CHECK();
   sgns_place_kernel<<<(unsigned)ceil_div(a.num_terms + a.num_pairs, 256), 256, 0, stream>>>(a);
   GS_LAUNCH_CHECK();
   const int row_bytes = a.dim * (int)sizeof(T);
