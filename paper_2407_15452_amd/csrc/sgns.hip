@@ -799,15 +799,28 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(uint32_t* __re
 
 // The whole scan in one block, for the few counters of a small batch (one kernel instead of
 // two on a path that is bound by its number of dependent kernels): a thread sums its stretch
-// of consecutive entries, the block scans the sums, the thread writes its stretch.
+// of consecutive entries, the block scans the sums, the thread writes its stretch.  Entries
+// move 16 bytes at a time, eight independent loads in flight per thread: `data` is 16-byte
+// aligned and allocated up to a multiple of four entries; the padding is read (it holds
+// zeros) and written.
 constexpr int64_t kScanSmallMax = 1 << 17;
 __global__ __launch_bounds__(1024) void scan_small_kernel(uint32_t* __restrict__ data, int64_t n) {
   __shared__ uint32_t wave_tot[16];
+  constexpr int kBurst = 8;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t per = (n + 1023) / 1024;
-  const int64_t lo = min(n, (int64_t)threadIdx.x * per), hi = min(n, lo + per);
+  uint4* __restrict__ d4 = (uint4*)data;
+  const int64_t n4 = (n + 3) / 4;
+  const int per = (int)((n4 + 1023) / 1024);
+  const int64_t lo = min(n4, (int64_t)threadIdx.x * per);
+  const int mine = (int)(min(n4, lo + per) - lo);
   uint32_t local = 0;
-  for (int64_t i = lo; i < hi; ++i) local += data[i];
+  for (int c = 0; c < mine; c += kBurst) {
+    uint4 v[kBurst];
+#pragma unroll
+    for (int u = 0; u < kBurst; ++u) v[u] = (c + u < mine) ? d4[lo + c + u] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int u = 0; u < kBurst; ++u) local += v[u].x + v[u].y + v[u].z + v[u].w;
+  }
   uint32_t incl = local;
 #pragma unroll
   for (int d = 1; d < 64; d <<= 1) {
@@ -820,10 +833,20 @@ __global__ __launch_bounds__(1024) void scan_small_kernel(uint32_t* __restrict__
 #pragma unroll
   for (int w = 0; w < 16; ++w)
     if (w < wave) run += wave_tot[w];
-  for (int64_t i = lo; i < hi; ++i) {
-    const uint32_t v = data[i];
-    data[i] = run;
-    run += v;
+  for (int c = 0; c < mine; c += kBurst) {
+    uint4 v[kBurst];
+#pragma unroll
+    for (int u = 0; u < kBurst; ++u) v[u] = (c + u < mine) ? d4[lo + c + u] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int u = 0; u < kBurst; ++u) {
+      uint4 o;
+      o.x = run;
+      o.y = o.x + v[u].x;
+      o.z = o.y + v[u].y;
+      o.w = o.z + v[u].z;
+      run = o.w + v[u].w;
+      if (c + u < mine) d4[lo + c + u] = o;
+    }
   }
 }
 
