@@ -90,3 +90,14 @@ def test_argument_checks_that_need_no_gpu(lib):
         lib.gs_unique_ids_workspace_bytes(C.c_int64(1000), C.c_int64(10**9))
     assert lib.gs_sgns_step_fused_workspace_bytes(C.c_int64(1000), C.c_int64(10), C.c_int32(5), C.c_int32(128), C.c_int32(0)) > \
         lib.gs_sgns_step_workspace_bytes(C.c_int64(1000), C.c_int64(10), C.c_int32(5), C.c_int32(128), C.c_int32(0))
+
+
+def test_static_step_rejects_oversized_batches_on_the_host(lib):
+    """gs_sgns_step_static checks its limits before it asks for the scratch array's address."""
+    fake, other = C.c_void_p(256), C.c_void_p(512)
+    call = lambda pairs, k, dim: lib.gs_sgns_step_static(  # noqa: E731
+        fake, other, C.c_int64(10), C.c_int32(dim), C.c_int32(0), fake, fake, fake, C.c_int64(pairs),
+        C.c_int32(k), C.c_float(0.1), fake, None)
+    assert call(4097, 5, 128) == -2
+    assert call(4096, 16, 128) == -2            # 4096 * 17 terms > 65536
+    assert call(1024, 5, 260) == -2
