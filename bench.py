@@ -265,7 +265,7 @@ def main():
     # ------------------------------------------------------------------ extra measurements
     # (other entry points on the same tables and batches; --no-extras leaves them out, e.g. for
     # a kernel profile of the timed path alone)
-    momentum_ms = adam_ms = fused = line = storage = from_walks_ms = None
+    momentum_ms = adam_ms = fused = line = storage = from_walks_ms = small = None
     if not args.no_extras:
         # ------------------------------------------------------------------ momentum variant (extra)
         # the paper's optimizer (dense mult / sparse put / dense mult_add); timed on the last batch
@@ -462,6 +462,22 @@ def main():
                    "put_ms": put_ms, "put_GBps": n_uniq * (2 * row_bytes + rb_blk) / put_ms / 1e6}
         del block, uniq_ws, batch_ids
 
+        # ------------------------------------------------------------------ small batches (extra)
+        # 2048 pairs on the same graph: the regime where a step is a chain of short dependent
+        # kernels; with a caller workspace and on the library's static scratch array
+        small = None
+        if wl.dim <= 256:
+            sb = min(2048, B)
+            sc, so_, sn = centers[lo:lo + sb], contexts[lo:lo + sb], negs[:sb]
+            small_ws = torch.empty(gs.gs_sgns_step_workspace_bytes(sb, wl.num_nodes, k, wl.dim), dtype=torch.uint8,
+                                   device=dev)
+            small = {"pairs": sb,
+                     "step_ms": timed(lambda: gs.gs_sgns_step(w_in, w_out, sc, so_, sn, lr, loss_out=losses[:1],
+                                                              ws=small_ws), reps=50),
+                     "static_step_ms": timed(lambda: gs.gs_sgns_step_static(w_in, w_out, sc, so_, sn, lr,
+                                                                            loss_out=losses[:1]), reps=50)}
+            del small_ws
+
     walk_kind = ("node2vec p=%g q=%g" % (wl.p, wl.q)) if wl.node2vec else "first-order"
     walk_kind += ", alias-weighted" if wl.weighted else ", uniform"
     result = {
@@ -487,6 +503,7 @@ def main():
         "pairs_made_in_step": from_walks_ms,
         "line": line,
         "storage_ops": storage,
+        "small_batch": small,
         "roofline": {"bound": "hbm", "kernel": "gs_sgns_step (all kernels of one call)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "bytes_per_pair": bpp,
