@@ -251,40 +251,6 @@ __device__ __forceinline__ void load_row(const T* __restrict__ table, int64_t ro
   }
 }
 
-// table[row] = round(old + delta), both given as register images
-template <int VPL>
-__device__ __forceinline__ void store_row_sum(float* __restrict__ table, int64_t row, int dim, int l16,
-                                              const float4 (&old)[VPL], const float4 (&d)[VPL]) {
-  float4* p = reinterpret_cast<float4*>(table + row * (int64_t)dim);
-  const int dim4 = dim >> 2;
-#pragma unroll
-  for (int v = 0; v < VPL; ++v) {
-    const int q = v * kGroupLanes + l16;
-    if (q < dim4)
-      p[q] = make_float4(old[v].x + d[v].x, old[v].y + d[v].y, old[v].z + d[v].z, old[v].w + d[v].w);
-  }
-}
-
-template <int VPL, typename T, if_16bit<T> = 0>
-__device__ __forceinline__ void store_row_sum(T* __restrict__ table, int64_t row, int dim, int l16,
-                                              const float4 (&old)[VPL], const float4 (&d)[VPL]) {
-  uint4* p = reinterpret_cast<uint4*>(table + row * (int64_t)dim);
-  const int chunks = dim >> 3;
-#pragma unroll
-  for (int w = 0; w < VPL / 2; ++w) {
-    const int c = w * kGroupLanes + l16;
-    if (c < chunks) {
-      const float4 a = old[2 * w], b = old[2 * w + 1], da = d[2 * w], db = d[2 * w + 1];
-      uint4 x;
-      x.x = pack16<T>(a.x + da.x, a.y + da.y);
-      x.y = pack16<T>(a.z + da.z, a.w + da.w);
-      x.z = pack16<T>(b.x + db.x, b.y + db.y);
-      x.w = pack16<T>(b.z + db.z, b.w + db.w);
-      p[c] = x;
-    }
-  }
-}
-
 template <int VPL>
 __device__ __forceinline__ float dot_partial(const float4 (&a)[VPL], const float4 (&b)[VPL]) {
   float s = 0.f;
@@ -441,21 +407,32 @@ __device__ __forceinline__ uint32_t claim_slot(const SgnsArgs& a, uint32_t key) 
   const KeyRegion r = key_region(a, key);
   if (r.bits == 0) return r.slot_base + r.vertex;
   const uint32_t mask = (1u << r.bits) - 1u;
-  uint32_t h = (key * 2654435761u) >> (32 - r.bits);
-  while (true) {
+  const uint32_t home = (key * 2654435761u) >> (32 - r.bits);
+  uint32_t h = home;
+  // (the probe count is bounded so that the loop ends whatever the memory holds; a table
+  // without a free place cannot arise from a batch the plan was made for, and is reported)
+  for (uint32_t probes = 0; probes <= mask; ++probes) {
     uint32_t seen = __hip_atomic_load(r.table + h, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (seen == kNoRow) seen = atomicCAS(r.table + h, kNoRow, key);
     if (seen == kNoRow || seen == key) return r.slot_base + h;
     h = (h + 1u) & mask;
   }
+  *a.bad_ids = 1u;
+  return r.slot_base + home;
 }
 __device__ __forceinline__ uint32_t find_slot(const SgnsArgs& a, uint32_t key) {
   const KeyRegion r = key_region(a, key);
   if (r.bits == 0) return r.slot_base + r.vertex;
   const uint32_t mask = (1u << r.bits) - 1u;
-  uint32_t h = (key * 2654435761u) >> (32 - r.bits);
-  while (r.table[h] != key) h = (h + 1u) & mask;   // every key of the batch is in the table
-  return r.slot_base + h;
+  const uint32_t home = (key * 2654435761u) >> (32 - r.bits);
+  uint32_t h = home;
+  // every key of the batch was entered by the forward kernel
+  for (uint32_t probes = 0; probes <= mask; ++probes) {
+    if (r.table[h] == key) return r.slot_base + h;
+    h = (h + 1u) & mask;
+  }
+  *a.bad_ids = 1u;
+  return r.slot_base + home;
 }
 
 // ---- clear / fill ---------------------------------------------------------------------
