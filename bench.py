@@ -265,7 +265,7 @@ def main():
     # ------------------------------------------------------------------ extra measurements
     # (other entry points on the same tables and batches; --no-extras leaves them out, e.g. for
     # a kernel profile of the timed path alone)
-    momentum_ms = adam_ms = fused = line = storage = from_walks_ms = small = None
+    momentum_ms = adam_ms = fused = line = storage = from_walks_ms = small = shared = None
     if not args.no_extras:
         # ------------------------------------------------------------------ momentum variant (extra)
         # the paper's optimizer (dense mult / sparse put / dense mult_add); timed on the last batch
@@ -462,6 +462,21 @@ def main():
                    "put_ms": put_ms, "put_GBps": n_uniq * (2 * row_bytes + rb_blk) / put_ms / 1e6}
         del block, uniq_ws, batch_ids
 
+        # ------------------------------------------------------------------ shared negatives (extra)
+        # A variant of the method, not the timed configuration: every pair of a run of equal
+        # centres (one centre position of a walk) uses the negatives drawn for the run's first
+        # pair.  Same call, same kernels; the rows of a run's negatives are then gathered once
+        # from HBM and found in the L2 for the other pairs of the run.
+        cb = centers[lo:lo + B]
+        starts_run = torch.ones(B, dtype=torch.bool, device=dev)
+        starts_run[1:] = cb[1:] != cb[:-1]
+        first_of_run = torch.nonzero(starts_run).flatten()
+        shared_negs = negs[first_of_run[torch.cumsum(starts_run, 0) - 1]].contiguous()
+        shared = {"runs": int(first_of_run.numel()),
+                  "step_ms": timed(lambda: gs.gs_sgns_step(w_in, w_out, cb, contexts[lo:lo + B], shared_negs, lr,
+                                                           loss_out=losses[:1], ws=sgns_ws))}
+        del shared_negs, starts_run, first_of_run
+
         # ------------------------------------------------------------------ small batches (extra)
         # 2048 pairs on the same graph: the regime where a step is a chain of short dependent
         # kernels; with a caller workspace and on the library's static scratch array
@@ -504,6 +519,7 @@ def main():
         "line": line,
         "storage_ops": storage,
         "small_batch": small,
+        "shared_negatives_per_run": shared,
         "roofline": {"bound": "hbm", "kernel": "gs_sgns_step (all kernels of one call)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "algorithmic_frac": achieved / HBM_PEAK_GBS,
