@@ -63,3 +63,45 @@ def test_static_step_rejects_what_does_not_fit(gs):
     with pytest.raises(gs.GsError) as err:
         gs.gs_sgns_step_static(wide[0], wide[1], ids[:8], ids[:8], torch.zeros((8, 1), dtype=torch.int32, device=DEV), 0.1)
     assert err.value.status == gs.GS_EWORKSPACE
+
+
+def test_static_step_replays_from_a_captured_graph(gs):
+    """The use the entry point is for: captured once into a HIP graph (nothing is allocated,
+    the scratch array is cleared by a kernel), replayed on fresh batches with eager work and
+    synchronisation between the replays; every replay against the eager gs_sgns_step, bit for
+    bit.  The address of the scratch array is looked up by the warm-up call outside the capture."""
+    from paper_2407_15452_amd import inputs
+    n, dim, b, k = 30_000, 64, 2_048, 5
+    f_in, f_out = inputs.random_tables(n, dim, seed=9, scale=0.2)
+    a_in, a_out = f_in.to(DEV), f_out.to(DEV)
+    b_in, b_out = a_in.clone(), a_out.clone()
+    c_buf = torch.zeros(b, dtype=torch.int32, device=DEV)
+    o_buf = torch.zeros(b, dtype=torch.int32, device=DEV)
+    n_buf = torch.zeros((b, k), dtype=torch.int32, device=DEV)
+    loss_a = torch.zeros(1, dtype=torch.float64, device=DEV)
+    loss_b = torch.zeros(1, dtype=torch.float64, device=DEV)
+
+    def body():
+        gs.gs_sgns_step_static(a_in, a_out, c_buf, o_buf, n_buf, 0.025, loss_out=loss_a)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        body()                                   # warm-up outside capture (ids 0)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        body()
+    a_in.copy_(b_in); a_out.copy_(b_out)         # capture does not run the kernels; start equal
+    rng = np.random.default_rng(23)
+    for it in range(3):
+        c, o, neg = _batch(rng, n, b, k)
+        c_buf.copy_(c); o_buf.copy_(o); n_buf.copy_(neg)
+        graph.replay()
+        gs.gs_sgns_step(b_in, b_out, c, o, neg, 0.025, loss_out=loss_b)
+        torch.cuda.synchronize()
+        assert torch.equal(loss_a.view(torch.int64), loss_b.view(torch.int64))
+        assert torch.equal(a_in.view(torch.int32), b_in.view(torch.int32))
+        assert torch.equal(a_out.view(torch.int32), b_out.view(torch.int32))
+        _ = (a_in * 2).sum().item()              # eager work of the program's own between the replays
