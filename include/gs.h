@@ -321,7 +321,9 @@ int32_t gs_sgns_step_fused(void* w_in, void* w_out, int64_t num_nodes, int32_t d
  *   of pair i is the draw of gs_sample_negatives for pair index pair_index_base
  *   + i.  The result is that of gs_make_pairs + gs_sample_negatives +
  *   gs_sgns_step on that slice.  If the walks hold fewer than first_pair +
- *   num_pairs pairs, loss_sum_out is NaN (as for an id that is no row).
+ *   num_pairs pairs, or pair_offsets is not the numbering of these walks,
+ *   loss_sum_out is NaN (as for an id that is no row; no access leaves the
+ *   walk buffer).
  *   walks int32[num_walks][walk_len]; pair_offsets as written by gs_pair_offsets;
  *   other arguments, limits and errors as for gs_sgns_step_fused; workspace
  *   gs_sgns_step_from_walks_workspace_bytes.

@@ -518,8 +518,12 @@ __global__ __launch_bounds__(kSgnsThreads) void sgns_forward_kernel(SgnsArgs a) 
         const int64_t len = valid_prefix(row, a.walk_len);
         int64_t at, other;
         pair_positions(gp - a.pair_offsets[lo], len, a.window, at, other);
-        c = row[at];
-        o = row[other];
+        if (at >= 0 && at < len && other >= 0 && other < len) {
+          c = row[at];
+          o = row[other];
+        } else {
+          *a.bad_ids = 1u;                  // pair_offsets does not belong to these walks
+        }
       } else {
         *a.bad_ids = 1u;                    // the walks do not hold that many pairs
       }

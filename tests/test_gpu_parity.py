@@ -996,3 +996,9 @@ def test_sgns_step_from_walks(gs, oracle, walk_len, window, k, dtype):
     # a slice that reaches past the last pair is reported through the loss
     loss = gs.gs_sgns_step_from_walks(d_in, d_out, walks, window, offsets, total - 3, 10, noise_d, k, 77, 0.02)
     assert np.isnan(float(loss.item()))
+    # offsets that are not the numbering of these walks (every count doubled): reported the same
+    # way, and no position outside a walk's live prefix is read
+    other = offsets * 2
+    loss = gs.gs_sgns_step_from_walks(d_in, d_out, walks, window, other, 0, min(total, 4096), noise_d, k, 77, 0.02)
+    torch.cuda.synchronize()
+    assert np.isnan(float(loss.item()))
